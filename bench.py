@@ -1,0 +1,261 @@
+#!/usr/bin/env python3
+"""Forward-convolution benchmark on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-layers] [--no-cpu]
+
+A step is one call of the fused convolution (conv_fwd_ws through the C ABI: filter-tile and patch-tile staging,
+MFMA main loop, fused bias+ReLU store; plus the fixed-order reduce when a split variant is selected) on one
+batch of seeded synthetic input that is already resident in device memory.  The variant is chosen by the
+library's autotuner before timing starts.  The headline workload is the mid-network 3x3 layer of the batch
+sweep at batch 20 in fp32 (the paper's arithmetic); `layers` in the JSON line reports every benchmark layer at
+batch 1/5/20 and every storage type: ms, GFLOP/s and the fraction of the MFMA and HBM rooflines.
+
+Prints ONE JSON line on stdout; everything else goes to stderr.
+"""
+import argparse
+import json
+import os
+import statistics
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+# MI355X published peaks
+PEAK_TFLOPS = {"f32": 157.3, "f16": 2500.0, "bf16": 2500.0}
+PEAK_HBM_GBS = 8000.0
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def all_workloads():
+    from paper_1611_06945_amd import workloads as wl
+
+    ws = [wl.config1(), wl.config2(), wl.config3()]
+    for dt in (wl.F32, wl.F16, wl.BF16):
+        for n in (1, 5, 20):
+            ws.append(wl.config4(n, dt))
+    ws += wl.config5_layers(20, wl.F16)
+    return ws
+
+
+class Resident:
+    """A workload with its tensors in device memory (optionally several rotating copies)."""
+
+    def __init__(self, w, copies=1):
+        import torch
+
+        from paper_1611_06945_amd import binding as B
+        from paper_1611_06945_amd import workloads as wl
+
+        self.w, self.B, self.torch = w, B, torch
+        self.desc = B.desc_of(w.shape, w.dtype, relu=True)
+        data = w.generate()
+        tdt = {wl.F32: torch.float32, wl.F16: torch.float16, wl.BF16: torch.bfloat16}[w.dtype]
+
+        def up(a):
+            if w.dtype == wl.BF16:
+                import numpy as np
+
+                return torch.from_numpy(a.view(np.int16)).cuda().view(torch.bfloat16)
+            return torch.from_numpy(a).cuda()
+
+        self.sets = []
+        for _ in range(copies):
+            self.sets.append((up(data["in"]).clone(), up(data["filt"]).clone(), torch.from_numpy(data["bias"]).cuda(),
+                              torch.empty(w.shape.out_shape(), dtype=tdt, device="cuda")))
+        self.ws_bytes = max(256, B.conv_workspace_bytes(self.desc))
+        self.ws = torch.empty(self.ws_bytes, dtype=torch.uint8, device="cuda")
+        self.i = 0
+
+    def autotune(self):
+        x, f, b, o = self.sets[0]
+        self.B.conv_autotune(self.desc, x, f, b, o, self.ws, self.ws_bytes)
+        self.variant = self.B.conv_variant_name(self.desc, -1)
+        return self.variant
+
+    def step(self):
+        x, f, b, o = self.sets[self.i]
+        self.i = (self.i + 1) % len(self.sets)
+        self.B.conv_fwd_ws(self.desc, x, f, b, o, self.ws, self.ws_bytes)
+
+    def time_batches(self, launches, batches, warmup):
+        """Median and minimum time per launch (ms) over `batches` event-bracketed batches of `launches` launches."""
+        torch = self.torch
+        for _ in range(warmup):
+            self.step()
+        torch.cuda.synchronize()
+        per = []
+        for _ in range(batches):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(launches):
+                self.step()
+            e1.record()
+            e1.synchronize()
+            per.append(e0.elapsed_time(e1) / launches)
+        return statistics.median(per), min(per)
+
+
+def layer_report(w, launches=100, batches=5, rotate_mb=0):
+    from paper_1611_06945_amd import workloads as wl
+
+    dt = wl.DTYPE_NAMES[w.dtype]
+    abytes = w.shape.algorithmic_bytes(w.dtype)
+    r = Resident(w)
+    variant = r.autotune()
+    med, mn = r.time_batches(launches, batches, warmup=20)
+    rep = {
+        "layer": w.name, "N": w.shape.N, "dtype": dt, "variant": variant,
+        "ms": round(med, 6), "ms_min": round(mn, 6),
+        "gflops": round(w.shape.flops / (med * 1e-3) / 1e9, 1),
+        "frac_mfma_peak": round(w.shape.flops / (med * 1e-3) / (PEAK_TFLOPS[dt] * 1e12), 5),
+        "hbm_gbs_algorithmic": round(abytes / (med * 1e-3) / 1e9, 1),
+        "frac_hbm_peak": round(abytes / (med * 1e-3) / (PEAK_HBM_GBS * 1e9), 5),
+        "flops": w.shape.flops, "algorithmic_bytes": abytes,
+    }
+    if rotate_mb:
+        # enough distinct tensor sets to exceed the last-level cache, so the figure is an HBM figure
+        copies = max(2, int(rotate_mb * 1e6 / abytes) + 1)
+        rr = Resident(w, copies=copies)
+        rr.autotune()
+        med_r, _ = rr.time_batches(max(launches, copies), batches, warmup=copies)
+        rep["ms_rotated"] = round(med_r, 6)
+        rep["frac_hbm_peak_rotated"] = round(abytes / (med_r * 1e-3) / (PEAK_HBM_GBS * 1e9), 5)
+        rep["rotated_copies"] = copies
+    return rep
+
+
+def cpu_baseline(w, budget_s=12.0):
+    """The oracle as it stands, timed on this host's cores on the same workload (whole layer, repeated)."""
+    import numpy as np
+
+    import oracle
+    from paper_1611_06945_amd import workloads as wl
+
+    data = w.generate()
+    x = wl.storage_to_f64(data["in"], w.dtype)
+    f = wl.storage_to_f64(data["filt"], w.dtype)
+    b = data["bias"].astype(np.float64)
+    oracle.conv_fwd(x[:1], f, b, stride=w.shape.stride, pad=w.shape.pad, relu=True)  # load + thread pool warm-up
+    n, t0 = 0, time.perf_counter()
+    while True:
+        oracle.conv_fwd(x, f, b, stride=w.shape.stride, pad=w.shape.pad, relu=True)
+        n += 1
+        dt = time.perf_counter() - t0
+        if dt >= budget_s or n >= 50:
+            break
+    return {"value": round(w.shape.flops * n / dt / 1e9, 3), "unit": "GFLOP/s", "cores": oracle.threads(),
+            "kind": "oracle", "ms_per_step": round(dt / n * 1e3, 3),
+            "sample": "%d full passes of %s (fp64 direct convolution, %.1f s)" % (n, w.name, dt)}
+
+
+def stored_traffic(kernel_key):
+    """HBM bytes per launch measured offline with rocprofv3 --pmc (see profiles/); None if not recorded."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    try:
+        with open(path) as fh:
+            return json.load(fh).get(kernel_key)
+    except (OSError, ValueError):
+        return None
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=2000)
+    ap.add_argument("--warmup", type=int, default=100)
+    ap.add_argument("--workload", default="cfg4_mid3x3_n20_f32")
+    ap.add_argument("--no-layers", action="store_true", help="skip the per-layer table")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    a = ap.parse_args()
+    if a.gpus != 1:
+        log("bench.py: this build runs on ONE GPU (the paper's method is single-device inference); --gpus %d is not "
+            "supported." % a.gpus)
+        sys.exit(2)
+
+    import torch
+
+    from paper_1611_06945_amd import binding as B
+    from paper_1611_06945_amd import workloads as wl
+
+    if not torch.cuda.is_available():
+        log("bench.py: no GPU visible")
+        sys.exit(3)
+    B.lib()  # fail loudly if the HIP library is not built
+    torch.cuda.set_device(0)
+    log("device:", torch.cuda.get_device_name(0))
+
+    table = {w.name: w for w in all_workloads()}
+    if a.workload not in table:
+        log("unknown workload %r; choose from %s" % (a.workload, sorted(table)))
+        sys.exit(2)
+    w = table[a.workload]
+    dt = wl.DTYPE_NAMES[w.dtype]
+
+    # ---- headline: exactly `steps` timed steps after `warmup` untimed ones --------------------------------
+    r = Resident(w)
+    variant = r.autotune()
+    log("headline %s -> %s" % (w.name, variant))
+    for _ in range(a.warmup):
+        r.step()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    for _ in range(a.steps):
+        r.step()
+    e1.record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    ev_ms = e0.elapsed_time(e1)
+    ms_per_step = wall_ms / a.steps
+    kern_ms = ev_ms / a.steps  # device-side average per launch over the timed region
+    gflops = w.shape.flops / (ms_per_step * 1e-3) / 1e9
+
+    mfma_bound = w.shape.flops / (PEAK_TFLOPS[dt] * 1e12) >= w.shape.algorithmic_bytes(w.dtype) / (PEAK_HBM_GBS * 1e9)
+    if mfma_bound:
+        ach = w.shape.flops / (kern_ms * 1e-3) / 1e12
+        roof = {"bound": "mfma", "achieved": round(ach, 3), "peak": PEAK_TFLOPS[dt], "unit": "TFLOP/s",
+                "frac": round(ach / PEAK_TFLOPS[dt], 5)}
+    else:
+        ach = w.shape.algorithmic_bytes(w.dtype) / (kern_ms * 1e-3) / 1e9
+        roof = {"bound": "hbm", "achieved": round(ach, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                "frac": round(ach / PEAK_HBM_GBS, 5)}
+    roof["traffic"] = stored_traffic("%s|%s" % (w.name, variant))
+    roof["kernel"] = variant
+    roof["kernel_ms"] = round(kern_ms, 6)
+
+    out = {
+        "metric": "conv_fwd_gflops", "value": round(gflops, 1), "unit": "GFLOP/s", "n_gpus": 1,
+        "steps": a.steps, "warmup": a.warmup, "ms_per_step": round(ms_per_step, 6), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": dt, "data": "synthetic",
+        "config": {"workload": w.name, "N": w.shape.N, "C": w.shape.C, "H": w.shape.H, "W": w.shape.W,
+                   "K": w.shape.K, "R": w.shape.R, "S": w.shape.S, "stride": w.shape.stride, "pad": w.shape.pad,
+                   "fused": "bias+relu", "variant": variant, "paper_row": w.paper_row},
+        "roofline": roof,
+    }
+
+    if not a.no_layers:
+        layers = []
+        for lw in all_workloads():
+            hbmish = lw.name.startswith("cfg2") or lw.name.startswith("cfg5_L1") or (lw.shape.N == 1 and lw.dtype != wl.F32)
+            rep = layer_report(lw, rotate_mb=300 if hbmish else 0)
+            layers.append(rep)
+            log("%-26s %-44s %9.4f ms %10.1f GFLOP/s  mfma %.3f  hbm %.3f" % (
+                rep["layer"], rep["variant"], rep["ms"], rep["gflops"], rep["frac_mfma_peak"], rep["frac_hbm_peak"]))
+        out["layers"] = layers
+
+    if not a.no_cpu:
+        out["cpu_baseline"] = cpu_baseline(w)
+        log("cpu oracle:", out["cpu_baseline"])
+
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

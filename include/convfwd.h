@@ -1,0 +1,168 @@
+/*
+ * convfwd.h -- C ABI of the MI355X (gfx950) forward-convolution library.
+ *
+ * The operation is the convolution layer the paper defines in Section 2
+ * ("Background": output = conv(input, filters); each output value is the dot
+ * product of one filter with a window of the input slid with a spatial stride)
+ * with the activation fused into the output write as in Section 3
+ * ("Graph-level Optimizations"), plus a per-output-channel bias:
+ *
+ *   out[n,k,oy,ox] = act( bias[k] + sum_{c,r,s} in[n,c,oy*stride-pad+r,ox*stride-pad+s]
+ *                                                * filt[k,c,r,s] )
+ *
+ * zero padding, no filter flip, OH = floor((H+2*pad-R)/stride)+1 (OW likewise;
+ * floor reproduces the in->out sizes of Appendix A), groups = 1, dilation = 1.
+ *
+ * Conventions shared by every entry point
+ *   - Tensors are dense, C order: in [N][C][H][W], filt [K][C][R][S],
+ *     out [N][K][OH][OW], element type `dtype` (fp32, or fp16/bf16 storage with
+ *     fp32 accumulation and one round-to-nearest-even on the store).
+ *   - `bias` is [K] fp32 or NULL (= no bias); it is added in fp32 before `act`.
+ *   - All tensor pointers are DEVICE pointers owned by the caller.  The library
+ *     reads in/filt/bias, writes out (which must not alias them), keeps no pointer
+ *     after returning, never allocates or frees device memory and never
+ *     synchronises, except conv_autotune() which times kernels and therefore
+ *     synchronises `stream`.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Kernels are enqueued on it and the call returns immediately.
+ *   - Return value: 0 on success, a negative conv_status otherwise.  Descriptor
+ *     and pointer validation happens before the first HIP call, so the error
+ *     paths work on a host without a GPU.
+ *   - Thread safety: the variant cache is guarded by a mutex; kernels hold no state.
+ */
+#ifndef CONVFWD_H
+#define CONVFWD_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { CONV_F32 = 0, CONV_F16 = 1, CONV_BF16 = 2 } conv_dtype; /* storage type of in/filt/out */
+
+enum { CONV_FLAG_RELU = 1u }; /* act = max(x,0); without it act is the identity */
+
+typedef enum {
+    CONV_OK = 0,
+    CONV_EINVAL = -1,     /* NULL descriptor/pointer; N,C,H,W,K,R,S < 1; stride < 1; pad < 0; window larger than
+                             the padded input; a tensor with 2^31 or more elements; unknown flag bits */
+    CONV_EDTYPE = -2,     /* dtype is not one of conv_dtype */
+    CONV_EWORKSPACE = -3, /* workspace NULL/too small for what was asked (forced split variant, autotune) */
+    CONV_EHIP = -4,       /* a HIP call failed; conv_strerror(CONV_EHIP) carries the HIP message */
+    CONV_ENOVARIANT = -5, /* variant index out of range, or no kernel accepts this descriptor */
+    CONV_EIO = -6         /* autotune-cache file could not be read or written, or is malformed */
+} conv_status;
+
+typedef struct {
+    int32_t N, C, H, W;   /* input batch, channels, height, width            */
+    int32_t K, R, S;      /* output channels, window height, window width    */
+    int32_t stride, pad;  /* same stride and symmetric zero pad on both axes */
+    int32_t dtype;        /* conv_dtype                                      */
+    uint32_t flags;       /* CONV_FLAG_*                                     */
+} conv_desc;
+
+/* Output extent (formula above).  Pure host code.  CONV_EINVAL if the descriptor is not valid. */
+int conv_out_shape(const conv_desc* desc, int32_t* OH, int32_t* OW);
+
+/* FLOPs of the layer in the convention of Appendix A: 2*N*K*OH*OW*C*R*S.  0 if the descriptor is invalid. */
+double conv_flops(const conv_desc* desc);
+
+/*
+ * Bytes of device workspace with which every variant valid for `desc` can run
+ * (split-reduction variants keep fp32 partial sums there).  conv_fwd() needs
+ * none.  Returns 0 for an invalid descriptor.
+ */
+size_t conv_workspace_bytes(const conv_desc* desc);
+
+/*
+ * Enqueue the fused convolution on `stream` using the variant selected for
+ * `desc` (forced > autotuned/cached > heuristic), restricted to variants that
+ * need no workspace.  Asynchronous; see the conventions above.
+ */
+int conv_fwd(const conv_desc* desc, const void* in, const void* filt, const float* bias, void* out,
+             void* stream);
+
+/*
+ * As conv_fwd, but may also pick a split-reduction variant (paper, Section 3
+ * "Variant Selection and Autotuning": several variants per operation), whose
+ * partial sums go to `workspace` (device memory, 256-byte aligned, contents
+ * undefined afterwards) and are then reduced in a fixed order, so results are
+ * bit-reproducible.  If `workspace_bytes` is too small for the selected variant
+ * the best variant that fits is used instead; CONV_EWORKSPACE only if a forced
+ * variant does not fit.
+ */
+int conv_fwd_ws(const conv_desc* desc, const void* in, const void* filt, const float* bias, void* out,
+                void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Brute-force autotuning (paper, Section 3 "Variant Selection and Autotuning":
+ * exhaustive search over a fixed set of configurations, by measured run time):
+ * runs every variant valid for `desc` that fits `workspace_bytes` on the given
+ * buffers, times it with device events on `stream`, and records the fastest in
+ * the in-process cache used by conv_fwd/conv_fwd_ws (two entries: best overall,
+ * best without workspace).  `out` is overwritten.  Synchronises `stream`.
+ * `workspace` may be NULL (then only variants without workspace are tried).
+ */
+int conv_autotune(const conv_desc* desc, const void* in, const void* filt, const float* bias, void* out,
+                  void* workspace, size_t workspace_bytes, void* stream);
+
+/* Number of variants valid for `desc` (negative conv_status on error).  Pure host code. */
+int conv_variant_count(const conv_desc* desc);
+
+/*
+ * Name of variant `idx` in [0, conv_variant_count) -- or, with idx = -1, of the
+ * variant conv_fwd_ws would pick now given unlimited workspace; idx = -2, of the
+ * one conv_fwd would pick -- copied NUL-terminated into buf[0..n).  Names read
+ * like the paper's tuning strings, e.g. "igemm_f32_M128N128K16_w2x2" or "..._sk4".
+ */
+int conv_variant_name(const conv_desc* desc, int idx, char* buf, size_t n);
+
+/* Workspace bytes variant `idx` of `desc` needs (0 for unsplit variants); negative conv_status on error. */
+long long conv_variant_workspace(const conv_desc* desc, int idx);
+
+/* Force variant `idx` for this exact descriptor in later conv_fwd/conv_fwd_ws calls (tests run every variant this
+ * way); idx = -1 removes the override. */
+int conv_force_variant(const conv_desc* desc, int idx);
+
+/* Last measured time (microseconds per launch) of variant `idx` from conv_autotune in this process; < 0 if none. */
+double conv_variant_time_us(const conv_desc* desc, int idx);
+
+/*
+ * Autotune cache persistence: a text file, one line per descriptor
+ * ("N C H W K R S stride pad dtype flags | best-name | best-no-workspace-name").
+ * Load merges into the in-process cache and ignores lines naming unknown
+ * variants; a missing, unreadable or malformed file gives CONV_EIO and leaves
+ * the cache as it was.  conv_cache_clear drops every cached and forced choice.
+ */
+int conv_cache_load(const char* path);
+int conv_cache_save(const char* path);
+void conv_cache_clear(void);
+
+/*
+ * Cooperative tile load plan (paper, Section 3 "Metaprogramming for NN
+ * Convolutions": `threads` threads loading `words` words need ceil(words/threads)
+ * loads each, and only the last one needs a bounds guard, and only when `words`
+ * is not a multiple of `threads`).  The tile loaders of the kernels are unrolled
+ * from the same rule at compile time; this host entry point exposes it for
+ * checking.  CONV_EINVAL if either count is < 1.
+ */
+int conv_coop_load_plan(int threads, int words, int* loads_per_thread, int* last_load_guarded);
+
+/*
+ * Per-channel spatial max-pool, window win x win, stride `stride`, no padding,
+ * OH = floor((H-win)/stride)+1 (the glue between layers of a convolution stack;
+ * paper, Section 2).  in [N][C][H][W] -> out [N][C][OH][OW], element type
+ * `dtype`, device pointers, asynchronous on `stream`.
+ */
+int maxpool_fwd(int32_t N, int32_t C, int32_t H, int32_t W, int32_t win, int32_t stride, int32_t dtype,
+                const void* in, void* out, void* stream);
+
+/* Text for a conv_status; for CONV_EHIP it includes the message of the last failed HIP call of this thread. */
+const char* conv_strerror(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CONVFWD_H */

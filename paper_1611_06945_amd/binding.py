@@ -1,0 +1,206 @@
+"""Thin ctypes binding over libconvfwd.so: same names as include/convfwd.h, argument marshalling only.
+
+Tensor arguments may be torch tensors (their ``data_ptr()`` is passed) or plain
+integer device addresses.  ``stream`` may be None (torch's current stream if
+torch is importable and a GPU is present, else the default stream), a
+``torch.cuda.Stream`` or a raw ``hipStream_t`` value.
+
+There is no fallback: if the shared library is missing the import of any
+function here raises, and nothing in this module computes a convolution itself.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Tuple
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libconvfwd.so")
+
+CONV_F32, CONV_F16, CONV_BF16 = 0, 1, 2
+CONV_FLAG_RELU = 1
+CONV_OK, CONV_EINVAL, CONV_EDTYPE, CONV_EWORKSPACE, CONV_EHIP, CONV_ENOVARIANT, CONV_EIO = 0, -1, -2, -3, -4, -5, -6
+
+
+class conv_desc(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in ("N", "C", "H", "W", "K", "R", "S", "stride", "pad", "dtype")] + [
+        ("flags", ctypes.c_uint32)
+    ]
+
+    def __repr__(self):
+        return "conv_desc(N=%d,C=%d,H=%d,W=%d,K=%d,R=%d,S=%d,stride=%d,pad=%d,dtype=%d,flags=%d)" % (
+            self.N, self.C, self.H, self.W, self.K, self.R, self.S, self.stride, self.pad, self.dtype, self.flags)
+
+
+class ConvError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__("%s failed: %s (%d)" % (where, strerror(status), status))
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """Load libconvfwd.so (raises OSError with a build hint if it is not there)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise OSError("%s not found: build it with `python -m paper_1611_06945_amd.build`" % LIB_PATH)
+        L = ctypes.CDLL(LIB_PATH)
+        dp = ctypes.POINTER(conv_desc)
+        vp, i32p = ctypes.c_void_p, ctypes.POINTER(ctypes.c_int32)
+        L.conv_out_shape.argtypes = [dp, i32p, i32p]
+        L.conv_out_shape.restype = ctypes.c_int
+        L.conv_flops.argtypes = [dp]
+        L.conv_flops.restype = ctypes.c_double
+        L.conv_workspace_bytes.argtypes = [dp]
+        L.conv_workspace_bytes.restype = ctypes.c_size_t
+        L.conv_fwd.argtypes = [dp, vp, vp, vp, vp, vp]
+        L.conv_fwd.restype = ctypes.c_int
+        L.conv_fwd_ws.argtypes = [dp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+        L.conv_fwd_ws.restype = ctypes.c_int
+        L.conv_autotune.argtypes = [dp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+        L.conv_autotune.restype = ctypes.c_int
+        L.conv_variant_count.argtypes = [dp]
+        L.conv_variant_count.restype = ctypes.c_int
+        L.conv_variant_name.argtypes = [dp, ctypes.c_int, ctypes.c_char_p, ctypes.c_size_t]
+        L.conv_variant_name.restype = ctypes.c_int
+        L.conv_variant_workspace.argtypes = [dp, ctypes.c_int]
+        L.conv_variant_workspace.restype = ctypes.c_longlong
+        L.conv_force_variant.argtypes = [dp, ctypes.c_int]
+        L.conv_force_variant.restype = ctypes.c_int
+        L.conv_variant_time_us.argtypes = [dp, ctypes.c_int]
+        L.conv_variant_time_us.restype = ctypes.c_double
+        L.conv_cache_load.argtypes = [ctypes.c_char_p]
+        L.conv_cache_load.restype = ctypes.c_int
+        L.conv_cache_save.argtypes = [ctypes.c_char_p]
+        L.conv_cache_save.restype = ctypes.c_int
+        L.conv_cache_clear.argtypes = []
+        L.conv_cache_clear.restype = None
+        L.conv_coop_load_plan.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.POINTER(ctypes.c_int),
+                                          ctypes.POINTER(ctypes.c_int)]
+        L.conv_coop_load_plan.restype = ctypes.c_int
+        L.maxpool_fwd.argtypes = [ctypes.c_int32] * 7 + [vp, vp, vp]
+        L.maxpool_fwd.restype = ctypes.c_int
+        L.conv_strerror.argtypes = [ctypes.c_int]
+        L.conv_strerror.restype = ctypes.c_char_p
+        _lib = L
+    return _lib
+
+
+def make_desc(N, C, H, W, K, R, S, stride=1, pad=0, dtype=CONV_F32, relu=False, flags=None) -> conv_desc:
+    f = (CONV_FLAG_RELU if relu else 0) if flags is None else flags
+    return conv_desc(N, C, H, W, K, R, S, stride, pad, dtype, f)
+
+
+def desc_of(shape, dtype=CONV_F32, relu=True) -> conv_desc:
+    """conv_desc from a workloads.ConvShape."""
+    return make_desc(shape.N, shape.C, shape.H, shape.W, shape.K, shape.R, shape.S, shape.stride, shape.pad, dtype, relu)
+
+
+def _ptr(x) -> Optional[int]:
+    if x is None:
+        return None
+    if isinstance(x, int):
+        return x
+    if hasattr(x, "data_ptr"):
+        return int(x.data_ptr())
+    raise TypeError("expected a torch tensor, an int device address or None, got %r" % type(x))
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        try:
+            import torch
+
+            if torch.cuda.is_available():
+                return int(torch.cuda.current_stream().cuda_stream) or None
+        except ImportError:
+            pass
+        return None
+    if isinstance(stream, int):
+        return stream or None
+    return int(stream.cuda_stream) or None
+
+
+def _check(rc: int, where: str) -> int:
+    if rc < 0:
+        raise ConvError(rc, where)
+    return rc
+
+
+def strerror(status: int) -> str:
+    return lib().conv_strerror(int(status)).decode()
+
+
+def conv_out_shape(desc: conv_desc) -> Tuple[int, int]:
+    oh, ow = ctypes.c_int32(), ctypes.c_int32()
+    _check(lib().conv_out_shape(ctypes.byref(desc), ctypes.byref(oh), ctypes.byref(ow)), "conv_out_shape")
+    return oh.value, ow.value
+
+
+def conv_flops(desc: conv_desc) -> float:
+    return float(lib().conv_flops(ctypes.byref(desc)))
+
+
+def conv_workspace_bytes(desc: conv_desc) -> int:
+    return int(lib().conv_workspace_bytes(ctypes.byref(desc)))
+
+
+def conv_fwd(desc, inp, filt, bias, out, stream=None) -> None:
+    _check(lib().conv_fwd(ctypes.byref(desc), _ptr(inp), _ptr(filt), _ptr(bias), _ptr(out), _stream(stream)), "conv_fwd")
+
+
+def conv_fwd_ws(desc, inp, filt, bias, out, workspace, workspace_bytes, stream=None) -> None:
+    _check(lib().conv_fwd_ws(ctypes.byref(desc), _ptr(inp), _ptr(filt), _ptr(bias), _ptr(out), _ptr(workspace),
+                             int(workspace_bytes), _stream(stream)), "conv_fwd_ws")
+
+
+def conv_autotune(desc, inp, filt, bias, out, workspace=None, workspace_bytes=0, stream=None) -> None:
+    _check(lib().conv_autotune(ctypes.byref(desc), _ptr(inp), _ptr(filt), _ptr(bias), _ptr(out), _ptr(workspace),
+                               int(workspace_bytes), _stream(stream)), "conv_autotune")
+
+
+def conv_variant_count(desc) -> int:
+    return _check(lib().conv_variant_count(ctypes.byref(desc)), "conv_variant_count")
+
+
+def conv_variant_name(desc, idx: int) -> str:
+    buf = ctypes.create_string_buffer(192)
+    _check(lib().conv_variant_name(ctypes.byref(desc), int(idx), buf, len(buf)), "conv_variant_name")
+    return buf.value.decode()
+
+
+def conv_variant_workspace(desc, idx: int) -> int:
+    return _check(int(lib().conv_variant_workspace(ctypes.byref(desc), int(idx))), "conv_variant_workspace")
+
+
+def conv_force_variant(desc, idx: int) -> None:
+    _check(lib().conv_force_variant(ctypes.byref(desc), int(idx)), "conv_force_variant")
+
+
+def conv_variant_time_us(desc, idx: int) -> float:
+    return float(lib().conv_variant_time_us(ctypes.byref(desc), int(idx)))
+
+
+def conv_cache_load(path: str) -> None:
+    _check(lib().conv_cache_load(os.fsencode(path)), "conv_cache_load")
+
+
+def conv_cache_save(path: str) -> None:
+    _check(lib().conv_cache_save(os.fsencode(path)), "conv_cache_save")
+
+
+def conv_cache_clear() -> None:
+    lib().conv_cache_clear()
+
+
+def conv_coop_load_plan(threads: int, words: int) -> Tuple[int, bool]:
+    n, g = ctypes.c_int(), ctypes.c_int()
+    _check(lib().conv_coop_load_plan(int(threads), int(words), ctypes.byref(n), ctypes.byref(g)), "conv_coop_load_plan")
+    return n.value, bool(g.value)
+
+
+def maxpool_fwd(N, C, H, W, win, stride, dtype, inp, out, stream=None) -> None:
+    _check(lib().maxpool_fwd(N, C, H, W, win, stride, dtype, _ptr(inp), _ptr(out), _stream(stream)), "maxpool_fwd")

@@ -1,0 +1,530 @@
+// Host side of libconvfwd.so: descriptor validation, the variant registry, variant
+// selection (forced > autotuned > heuristic), the brute-force autotuner, cache
+// persistence and the extern "C" entry points declared in include/convfwd.h.
+#include <algorithm>
+#include <array>
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <fstream>
+#include <map>
+#include <mutex>
+#include <sstream>
+
+#include "common.h"
+
+using namespace convfwd;
+
+namespace {
+
+typedef std::array<int64_t, 11> Key;
+
+Key key_of(const conv_desc& d)
+{
+    return Key{d.N, d.C, d.H, d.W, d.K, d.R, d.S, d.stride, d.pad, d.dtype, (int64_t)d.flags};
+}
+
+struct Choice {
+    std::string best;       // fastest variant overall (may need workspace)
+    std::string best_nows;  // fastest variant that needs no workspace
+};
+
+struct State {
+    std::mutex mu;
+    std::vector<Variant> variants;
+    std::map<std::string, int> by_name;
+    std::map<Key, Choice> cache;
+    std::map<Key, int> forced;                   // index into valid_list(desc)
+    std::map<Key, std::vector<double>> times_us;  // per valid-list index, from the last autotune
+};
+
+State& state()
+{
+    static State* st = [] {
+        State* s = new State;
+        register_igemm_f32(s->variants);
+        register_igemm_f16(s->variants);
+        register_igemm_bf16(s->variants);
+        for (size_t i = 0; i < s->variants.size(); ++i) s->by_name[s->variants[i].name] = (int)i;
+        return s;
+    }();
+    return *st;
+}
+
+thread_local std::string g_hip_msg;
+
+int hip_fail(hipError_t e, const char* what)
+{
+    g_hip_msg = std::string(what) + ": " + hipGetErrorString(e);
+    return CONV_EHIP;
+}
+
+const uint32_t kKnownFlags = CONV_FLAG_RELU;
+
+// Validation shared by every entry point; fills OH/OW.
+int check_desc(const conv_desc* d, int& OH, int& OW)
+{
+    if (!d) return CONV_EINVAL;
+    if (d->dtype != CONV_F32 && d->dtype != CONV_F16 && d->dtype != CONV_BF16) return CONV_EDTYPE;
+    if (d->N < 1 || d->C < 1 || d->H < 1 || d->W < 1 || d->K < 1 || d->R < 1 || d->S < 1) return CONV_EINVAL;
+    if (d->stride < 1 || d->pad < 0) return CONV_EINVAL;
+    if (d->flags & ~kKnownFlags) return CONV_EINVAL;
+    const int64_t sh = (int64_t)d->H + 2LL * d->pad - d->R, sw = (int64_t)d->W + 2LL * d->pad - d->S;
+    if (sh < 0 || sw < 0) return CONV_EINVAL;
+    const int64_t oh = sh / d->stride + 1, ow = sw / d->stride + 1;
+    const int64_t lim = (int64_t)1 << 31;
+    const int64_t n_in = (int64_t)d->N * d->C * d->H * d->W;
+    const int64_t n_f = (int64_t)d->K * d->C * d->R * d->S;
+    if (oh >= lim || ow >= lim) return CONV_EINVAL;
+    // guard the products against overflow before forming them
+    if ((double)d->N * d->C * (double)d->H * d->W >= (double)lim) return CONV_EINVAL;
+    if ((double)d->K * d->C * (double)d->R * d->S >= (double)lim) return CONV_EINVAL;
+    if ((double)d->N * d->K * (double)oh * (double)ow >= (double)lim) return CONV_EINVAL;
+    // the padded coordinates formed inside the kernels must fit an int as well
+    if ((double)(d->H + 2.0 * d->pad) * (double)(d->W + 2.0 * d->pad) >= (double)lim) return CONV_EINVAL;
+    (void)n_in;
+    (void)n_f;
+    OH = (int)oh;
+    OW = (int)ow;
+    return CONV_OK;
+}
+
+std::vector<int> valid_list(State& st, const conv_desc& d, int OH, int OW)
+{
+    std::vector<int> r;
+    for (size_t i = 0; i < st.variants.size(); ++i)
+        if (st.variants[i].valid(st.variants[i], d, OH, OW)) r.push_back((int)i);
+    return r;
+}
+
+size_t ws_bytes_of(const Variant& v, const conv_desc& d, int OH, int OW)
+{
+    if (v.split <= 1) return 0;
+    return (size_t)v.split * (size_t)d.K * (size_t)d.N * OH * OW * sizeof(float);
+}
+
+// Rough cost model used only when nothing was autotuned for this descriptor: number of rounds the
+// workgroups need on 256 CUs times the work of one workgroup, small tiles charged for their extra
+// operand traffic, splits charged for the second pass.  Ties go to the more specialised variant
+// (the paper's "most specialised possible" rule for non-autotuned selection).
+double heuristic_cost(const Variant& v, const conv_desc& d, int OH, int OW)
+{
+    const double P = (double)d.N * OH * OW, Q = (double)d.C * d.R * d.S;
+    const double tiles = std::ceil(d.K / (double)v.tm) * std::ceil(P / (double)v.tn) * v.split;
+    const double steps = std::ceil(std::ceil(Q / v.tk) / v.split);
+    const double wg_per_cu = (v.tm * v.tn >= 128 * 128) ? 1.0 : (v.tm * v.tn >= 64 * 128) ? 2.0 : 3.0;
+    const double rounds = std::ceil(tiles / (256.0 * wg_per_cu));
+    const double per_wg = (double)v.tm * v.tn * v.tk * steps * (1.0 + 24.0 / v.tm + 24.0 / v.tn) * wg_per_cu;
+    double cost = rounds * per_wg + 6.0e4 * wg_per_cu;  // fixed ramp-up per launch
+    if (v.split > 1) cost += 2.0e5 + (double)v.split * d.K * P * 0.02;
+    cost *= 1.0 - 0.03 * v.specificity;
+    return cost;
+}
+
+int pick_heuristic(State& st, const std::vector<int>& valid, const conv_desc& d, int OH, int OW, size_t ws_limit)
+{
+    int best = -1;
+    double best_cost = 0;
+    for (int idx : valid) {
+        const Variant& v = st.variants[idx];
+        if (ws_bytes_of(v, d, OH, OW) > ws_limit) continue;
+        const double c = heuristic_cost(v, d, OH, OW);
+        if (best < 0 || c < best_cost) {
+            best = idx;
+            best_cost = c;
+        }
+    }
+    return best;
+}
+
+// Returns the registry index to run, or a negative status.
+int select_variant(State& st, const conv_desc& d, int OH, int OW, size_t ws_limit)
+{
+    const std::vector<int> valid = valid_list(st, d, OH, OW);
+    if (valid.empty()) return CONV_ENOVARIANT;
+    const Key k = key_of(d);
+    auto f = st.forced.find(k);
+    if (f != st.forced.end()) {
+        if (f->second < 0 || f->second >= (int)valid.size()) return CONV_ENOVARIANT;
+        const int idx = valid[f->second];
+        if (ws_bytes_of(st.variants[idx], d, OH, OW) > ws_limit) return CONV_EWORKSPACE;
+        return idx;
+    }
+    auto c = st.cache.find(k);
+    if (c != st.cache.end()) {
+        for (const std::string* nm : {&c->second.best, &c->second.best_nows}) {
+            auto it = st.by_name.find(*nm);
+            if (it == st.by_name.end()) continue;
+            const Variant& v = st.variants[it->second];
+            if (!v.valid(v, d, OH, OW)) continue;
+            if (ws_bytes_of(v, d, OH, OW) <= ws_limit) return it->second;
+        }
+    }
+    const int h = pick_heuristic(st, valid, d, OH, OW, ws_limit);
+    return h < 0 ? CONV_ENOVARIANT : h;
+}
+
+void fill_args(ConvArgs& a, const conv_desc& d, int OH, int OW, const void* in, const void* filt, const float* bias,
+               void* out, void* ws)
+{
+    a.in = in;
+    a.filt = filt;
+    a.bias = bias;
+    a.out = out;
+    a.ws = (float*)ws;
+    a.N = d.N; a.C = d.C; a.H = d.H; a.W = d.W; a.K = d.K; a.R = d.R; a.S = d.S;
+    a.stride = d.stride; a.pad = d.pad; a.OH = OH; a.OW = OW;
+    a.P = d.N * OH * OW;
+    a.Q = d.C * d.R * d.S;
+    a.HW = d.H * d.W;
+    a.OHW = OH * OW;
+    a.RS = d.R * d.S;
+    a.relu = (d.flags & CONV_FLAG_RELU) ? 1 : 0;
+    a.nsplit = 1;
+    a.steps_per_split = 0;
+    a.dRS = make_fastdiv((uint32_t)a.RS);
+    a.dS = make_fastdiv((uint32_t)d.S);
+    a.dOHW = make_fastdiv((uint32_t)a.OHW);
+    a.dOW = make_fastdiv((uint32_t)OW);
+}
+
+int run_variant(const Variant& v, const conv_desc& d, ConvArgs& a, hipStream_t s)
+{
+    hipError_t e = v.launch(v, a, s);
+    if (e != hipSuccess) return hip_fail(e, v.name.c_str());
+    if (v.split > 1) {
+        e = launch_split_reduce(a, d.dtype, s);
+        if (e != hipSuccess) return hip_fail(e, "split_reduce");
+    }
+    return CONV_OK;
+}
+
+bool aligned16(const void* p) { return (((uintptr_t)p) & 15u) == 0; }
+
+int fwd_common(const conv_desc* desc, const void* in, const void* filt, const float* bias, void* out, void* ws,
+               size_t ws_bytes, void* stream)
+{
+    int OH, OW;
+    const int rc = check_desc(desc, OH, OW);
+    if (rc) return rc;
+    if (!in || !filt || !out) return CONV_EINVAL;
+    if (!aligned16(in) || !aligned16(filt) || !aligned16(out) || (bias && (((uintptr_t)bias) & 3u))) return CONV_EINVAL;
+    if (ws && (((uintptr_t)ws) & 255u)) return CONV_EINVAL;
+    if (!ws) ws_bytes = 0;
+    State& st = state();
+    int idx;
+    {
+        std::lock_guard<std::mutex> g(st.mu);
+        idx = select_variant(st, *desc, OH, OW, ws_bytes);
+    }
+    if (idx < 0) return idx;
+    ConvArgs a;
+    fill_args(a, *desc, OH, OW, in, filt, bias, out, ws);
+    return run_variant(st.variants[idx], *desc, a, (hipStream_t)stream);
+}
+
+}  // namespace
+
+extern "C" {
+
+int conv_out_shape(const conv_desc* desc, int32_t* OH, int32_t* OW)
+{
+    int oh, ow;
+    const int rc = check_desc(desc, oh, ow);
+    if (rc) return rc;
+    if (!OH || !OW) return CONV_EINVAL;
+    *OH = oh;
+    *OW = ow;
+    return CONV_OK;
+}
+
+double conv_flops(const conv_desc* desc)
+{
+    int oh, ow;
+    if (check_desc(desc, oh, ow)) return 0.0;
+    return 2.0 * desc->N * desc->K * (double)oh * ow * desc->C * desc->R * desc->S;
+}
+
+size_t conv_workspace_bytes(const conv_desc* desc)
+{
+    int OH, OW;
+    if (check_desc(desc, OH, OW)) return 0;
+    State& st = state();
+    std::lock_guard<std::mutex> g(st.mu);
+    size_t need = 0;
+    for (int idx : valid_list(st, *desc, OH, OW)) need = std::max(need, ws_bytes_of(st.variants[idx], *desc, OH, OW));
+    return need;
+}
+
+int conv_fwd(const conv_desc* desc, const void* in, const void* filt, const float* bias, void* out, void* stream)
+{
+    return fwd_common(desc, in, filt, bias, out, nullptr, 0, stream);
+}
+
+int conv_fwd_ws(const conv_desc* desc, const void* in, const void* filt, const float* bias, void* out, void* workspace,
+                size_t workspace_bytes, void* stream)
+{
+    return fwd_common(desc, in, filt, bias, out, workspace, workspace_bytes, stream);
+}
+
+int conv_autotune(const conv_desc* desc, const void* in, const void* filt, const float* bias, void* out, void* workspace,
+                  size_t workspace_bytes, void* stream)
+{
+    int OH, OW;
+    const int rc = check_desc(desc, OH, OW);
+    if (rc) return rc;
+    if (!in || !filt || !out) return CONV_EINVAL;
+    if (!aligned16(in) || !aligned16(filt) || !aligned16(out) || (bias && (((uintptr_t)bias) & 3u))) return CONV_EINVAL;
+    if (workspace && (((uintptr_t)workspace) & 255u)) return CONV_EINVAL;
+    if (!workspace) workspace_bytes = 0;
+    State& st = state();
+    std::vector<int> valid;
+    {
+        std::lock_guard<std::mutex> g(st.mu);
+        valid = valid_list(st, *desc, OH, OW);
+    }
+    if (valid.empty()) return CONV_ENOVARIANT;
+    hipStream_t s = (hipStream_t)stream;
+    hipEvent_t e0, e1;
+    hipError_t e = hipEventCreate(&e0);
+    if (e != hipSuccess) return hip_fail(e, "hipEventCreate");
+    e = hipEventCreate(&e1);
+    if (e != hipSuccess) {
+        hipEventDestroy(e0);
+        return hip_fail(e, "hipEventCreate");
+    }
+    std::vector<double> times(valid.size(), -1.0);
+    int status = CONV_OK;
+    int best = -1, best_nows = -1;
+    for (size_t i = 0; i < valid.size() && status == CONV_OK; ++i) {
+        const Variant& v = st.variants[valid[i]];
+        const size_t need = ws_bytes_of(v, *desc, OH, OW);
+        if (need > workspace_bytes) continue;
+        ConvArgs a;
+        fill_args(a, *desc, OH, OW, in, filt, bias, out, workspace);
+        // warm-up, then a first timed launch pair to size the batch
+        for (int w = 0; w < 2 && status == CONV_OK; ++w) status = run_variant(v, *desc, a, s);
+        if (status) break;
+        auto timed = [&](int reps, float& ms) -> int {
+            hipError_t ee = hipEventRecord(e0, s);
+            if (ee != hipSuccess) return hip_fail(ee, "hipEventRecord");
+            for (int r = 0; r < reps; ++r) {
+                const int rr = run_variant(v, *desc, a, s);
+                if (rr) return rr;
+            }
+            ee = hipEventRecord(e1, s);
+            if (ee != hipSuccess) return hip_fail(ee, "hipEventRecord");
+            ee = hipEventSynchronize(e1);
+            if (ee != hipSuccess) return hip_fail(ee, "hipEventSynchronize");
+            ee = hipEventElapsedTime(&ms, e0, e1);
+            if (ee != hipSuccess) return hip_fail(ee, "hipEventElapsedTime");
+            return CONV_OK;
+        };
+        float ms = 0.f;
+        status = timed(3, ms);
+        if (status) break;
+        const double est_us = std::max(1.0, ms * 1000.0 / 3.0);
+        int reps = (int)std::min(100.0, std::max(5.0, 1500.0 / est_us));  // about 1.5 ms per batch
+        double best_us = 1e30;
+        for (int b = 0; b < 3 && status == CONV_OK; ++b) {
+            status = timed(reps, ms);
+            best_us = std::min(best_us, ms * 1000.0 / reps);
+        }
+        if (status) break;
+        times[i] = best_us;
+        if (best < 0 || best_us < times[best]) best = (int)i;
+        if (need == 0 && (best_nows < 0 || best_us < times[best_nows])) best_nows = (int)i;
+    }
+    hipEventDestroy(e0);
+    hipEventDestroy(e1);
+    if (status) return status;
+    if (best < 0) return CONV_EWORKSPACE;
+    {
+        std::lock_guard<std::mutex> g(st.mu);
+        Choice c;
+        c.best = st.variants[valid[best]].name;
+        c.best_nows = best_nows >= 0 ? st.variants[valid[best_nows]].name : std::string();
+        st.cache[key_of(*desc)] = c;
+        st.times_us[key_of(*desc)] = times;
+    }
+    return CONV_OK;
+}
+
+int conv_variant_count(const conv_desc* desc)
+{
+    int OH, OW;
+    const int rc = check_desc(desc, OH, OW);
+    if (rc) return rc;
+    State& st = state();
+    std::lock_guard<std::mutex> g(st.mu);
+    return (int)valid_list(st, *desc, OH, OW).size();
+}
+
+int conv_variant_name(const conv_desc* desc, int idx, char* buf, size_t n)
+{
+    int OH, OW;
+    const int rc = check_desc(desc, OH, OW);
+    if (rc) return rc;
+    if (!buf || n == 0) return CONV_EINVAL;
+    State& st = state();
+    std::lock_guard<std::mutex> g(st.mu);
+    int reg;
+    if (idx == -1 || idx == -2) {
+        reg = select_variant(st, *desc, OH, OW, idx == -1 ? (size_t)-1 : 0);
+        if (reg < 0) return reg;
+    } else {
+        const std::vector<int> valid = valid_list(st, *desc, OH, OW);
+        if (idx < 0 || idx >= (int)valid.size()) return CONV_ENOVARIANT;
+        reg = valid[idx];
+    }
+    snprintf(buf, n, "%s", st.variants[reg].name.c_str());
+    return CONV_OK;
+}
+
+long long conv_variant_workspace(const conv_desc* desc, int idx)
+{
+    int OH, OW;
+    const int rc = check_desc(desc, OH, OW);
+    if (rc) return rc;
+    State& st = state();
+    std::lock_guard<std::mutex> g(st.mu);
+    const std::vector<int> valid = valid_list(st, *desc, OH, OW);
+    if (idx < 0 || idx >= (int)valid.size()) return CONV_ENOVARIANT;
+    return (long long)ws_bytes_of(st.variants[valid[idx]], *desc, OH, OW);
+}
+
+int conv_force_variant(const conv_desc* desc, int idx)
+{
+    int OH, OW;
+    const int rc = check_desc(desc, OH, OW);
+    if (rc) return rc;
+    State& st = state();
+    std::lock_guard<std::mutex> g(st.mu);
+    if (idx == -1) {
+        st.forced.erase(key_of(*desc));
+        return CONV_OK;
+    }
+    if (idx < 0 || idx >= (int)valid_list(st, *desc, OH, OW).size()) return CONV_ENOVARIANT;
+    st.forced[key_of(*desc)] = idx;
+    return CONV_OK;
+}
+
+double conv_variant_time_us(const conv_desc* desc, int idx)
+{
+    int OH, OW;
+    if (check_desc(desc, OH, OW)) return -1.0;
+    State& st = state();
+    std::lock_guard<std::mutex> g(st.mu);
+    auto it = st.times_us.find(key_of(*desc));
+    if (it == st.times_us.end() || idx < 0 || idx >= (int)it->second.size()) return -1.0;
+    return it->second[idx];
+}
+
+int conv_cache_load(const char* path)
+{
+    if (!path) return CONV_EINVAL;
+    std::ifstream f(path);
+    if (!f) return CONV_EIO;
+    State& st = state();
+    std::map<Key, Choice> loaded;
+    std::string line;
+    while (std::getline(f, line)) {
+        if (line.empty() || line[0] == '#') continue;
+        // "N C H W K R S stride pad dtype flags | best | best_nows"
+        std::vector<std::string> parts;
+        size_t pos = 0;
+        while (true) {
+            size_t bar = line.find('|', pos);
+            parts.push_back(line.substr(pos, bar == std::string::npos ? std::string::npos : bar - pos));
+            if (bar == std::string::npos) break;
+            pos = bar + 1;
+        }
+        if (parts.size() != 3) return CONV_EIO;
+        std::istringstream ks(parts[0]);
+        Key k;
+        for (auto& x : k)
+            if (!(ks >> x)) return CONV_EIO;
+        std::string extra;
+        if (ks >> extra) return CONV_EIO;
+        auto trim = [](std::string s) {
+            const size_t b = s.find_first_not_of(" \t\r"), e = s.find_last_not_of(" \t\r");
+            return b == std::string::npos ? std::string() : s.substr(b, e - b + 1);
+        };
+        Choice c;
+        c.best = trim(parts[1]);
+        c.best_nows = trim(parts[2]);
+        loaded[k] = c;
+    }
+    std::lock_guard<std::mutex> g(st.mu);
+    for (auto& kv : loaded) {
+        Choice c = kv.second;
+        if (!st.by_name.count(c.best)) c.best.clear();
+        if (!st.by_name.count(c.best_nows)) c.best_nows.clear();
+        if (c.best.empty() && c.best_nows.empty()) continue;  // names from another build of the library
+        st.cache[kv.first] = c;
+    }
+    return CONV_OK;
+}
+
+int conv_cache_save(const char* path)
+{
+    if (!path) return CONV_EINVAL;
+    State& st = state();
+    std::ofstream f(path);
+    if (!f) return CONV_EIO;
+    f << "# convfwd autotune cache: N C H W K R S stride pad dtype flags | best | best without workspace\n";
+    std::lock_guard<std::mutex> g(st.mu);
+    for (auto& kv : st.cache) {
+        for (size_t i = 0; i < kv.first.size(); ++i) f << (i ? " " : "") << kv.first[i];
+        f << " | " << kv.second.best << " | " << kv.second.best_nows << "\n";
+    }
+    f.flush();
+    return f ? CONV_OK : CONV_EIO;
+}
+
+void conv_cache_clear(void)
+{
+    State& st = state();
+    std::lock_guard<std::mutex> g(st.mu);
+    st.cache.clear();
+    st.forced.clear();
+    st.times_us.clear();
+}
+
+int conv_coop_load_plan(int threads, int words, int* loads_per_thread, int* last_load_guarded)
+{
+    if (threads < 1 || words < 1 || !loads_per_thread || !last_load_guarded) return CONV_EINVAL;
+    const CoopPlan p = coop_plan(threads, words);
+    *loads_per_thread = p.loads;
+    *last_load_guarded = p.last_guarded ? 1 : 0;
+    return CONV_OK;
+}
+
+int maxpool_fwd(int32_t N, int32_t C, int32_t H, int32_t W, int32_t win, int32_t stride, int32_t dtype, const void* in,
+                void* out, void* stream)
+{
+    if (dtype != CONV_F32 && dtype != CONV_F16 && dtype != CONV_BF16) return CONV_EDTYPE;
+    if (N < 1 || C < 1 || H < 1 || W < 1 || win < 1 || stride < 1 || win > H || win > W || !in || !out)
+        return CONV_EINVAL;
+    if ((double)N * C * (double)H * W >= 2147483648.0) return CONV_EINVAL;
+    const hipError_t e = launch_maxpool(N, C, H, W, win, stride, dtype, in, out, (hipStream_t)stream);
+    if (e != hipSuccess) return hip_fail(e, "maxpool");
+    return CONV_OK;
+}
+
+const char* conv_strerror(int status)
+{
+    thread_local std::string buf;
+    switch (status) {
+        case CONV_OK: return "success";
+        case CONV_EINVAL: return "invalid descriptor, pointer, alignment or size";
+        case CONV_EDTYPE: return "unsupported dtype";
+        case CONV_EWORKSPACE: return "workspace missing or too small";
+        case CONV_EHIP: buf = "HIP error: " + g_hip_msg; return buf.c_str();
+        case CONV_ENOVARIANT: return "no such variant for this descriptor";
+        case CONV_EIO: return "autotune cache file unreadable, unwritable or malformed";
+        default: return "unknown status";
+    }
+}
+
+}  // extern "C"

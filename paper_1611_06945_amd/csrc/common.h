@@ -1,0 +1,114 @@
+// Internal declarations shared by the host dispatcher and the kernel files of
+// libconvfwd.so.  Nothing here is part of the public ABI (include/convfwd.h).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <string>
+#include <vector>
+
+#include "../../include/convfwd.h"
+
+namespace convfwd {
+
+// Division of a non-negative 31-bit integer by a constant known at launch time.
+// The paper's point that ND-Array index arithmetic reduces to chains of constant
+// multiplies, divides and modulos (Section 3, "ND-Arrays") is kept: the divisor is
+// fixed per launch, so the kernel multiplies and shifts instead of dividing.
+//   q = (n * mul) >> shift   exact for 0 <= n < 2^31, 1 <= d < 2^31
+// with L = ceil(log2 d), mul = ceil(2^(31+L) / d) (< 2^32), shift = 31 + L.
+struct FastDiv {
+    uint32_t mul;
+    uint32_t shift;
+    uint32_t d;
+#ifdef __HIPCC__
+    __device__ __forceinline__ uint32_t div(uint32_t n) const
+    {
+        return (uint32_t)(((uint64_t)n * mul) >> shift);
+    }
+    __device__ __forceinline__ void divmod(uint32_t n, uint32_t& q, uint32_t& r) const
+    {
+        q = div(n);
+        r = n - q * d;
+    }
+#endif
+};
+
+inline FastDiv make_fastdiv(uint32_t d)
+{
+    FastDiv f;
+    uint32_t L = 0;
+    while ((1ull << L) < d) ++L;
+    uint64_t pw = 1ull << (31 + L);
+    f.mul = (uint32_t)((pw + d - 1) / d);
+    f.shift = 31 + L;
+    f.d = d;
+    return f;
+}
+
+// Cooperative tile load: `threads` threads fetch `words` words in ceil(words/threads)
+// loads each; only the last load needs a guard, and only if words % threads != 0
+// (paper, Section 3, "Metaprogramming for NN Convolutions").  constexpr, so the
+// kernels unroll their tile loaders from it.
+struct CoopPlan {
+    int loads;
+    bool last_guarded;
+};
+constexpr CoopPlan coop_plan(int threads, int words)
+{
+    return CoopPlan{(words + threads - 1) / threads, (words % threads) != 0};
+}
+
+// Everything a kernel needs, passed by value.
+struct ConvArgs {
+    const void* in;
+    const void* filt;
+    const float* bias;  // may be null
+    void* out;
+    float* ws;  // partial sums [nsplit][K][P] when nsplit > 1
+    int N, C, H, W, K, R, S, stride, pad, OH, OW;
+    int P;    // N*OH*OW, the pixel (GEMM-N) extent
+    int Q;    // C*R*S, the reduction extent
+    int HW;   // H*W
+    int OHW;  // OH*OW
+    int RS;   // R*S
+    int relu;
+    int nsplit;           // number of reduction splits (gridDim.z)
+    int steps_per_split;  // reduction steps (of the kernel's own step size) per split
+    FastDiv dRS, dS, dOHW, dOW;
+};
+
+struct Variant;
+typedef hipError_t (*LaunchFn)(const Variant& v, ConvArgs& a, hipStream_t s);
+typedef bool (*ValidFn)(const Variant& v, const conv_desc& d, int OH, int OW);
+
+// One compiled kernel configuration (the paper's "variant + tuning parameters").
+struct Variant {
+    std::string name;  // e.g. igemm_f32_M128N128K16_w2x2_sk4
+    int dtype;         // conv_dtype it is compiled for
+    int split;         // reduction splits; 1 = result written directly with the fused epilogue
+    int tm, tn, tk;    // workgroup tile: output channels x pixels x reduction step
+    int threads;       // workgroup size
+    int family;        // 0 generic implicit GEMM, 1 pointwise, 2 first layer / small C
+    int specificity;   // higher = written for a narrower class of shapes (heuristic tie-break)
+    ValidFn valid;
+    LaunchFn launch;
+};
+
+enum { FAM_IGEMM = 0, FAM_POINTWISE = 1, FAM_FIRSTLAYER = 2 };
+
+// Each kernel file appends its variants.
+void register_igemm_f32(std::vector<Variant>& out);
+void register_igemm_f16(std::vector<Variant>& out);
+void register_igemm_bf16(std::vector<Variant>& out);
+
+// Split-reduction second pass and the max-pool helper (aux_kernels.hip).
+hipError_t launch_split_reduce(const ConvArgs& a, int dtype, hipStream_t s);
+hipError_t launch_maxpool(int N, int C, int H, int W, int win, int stride, int dtype, const void* in, void* out,
+                          hipStream_t s);
+
+inline const char* dtype_name(int dt) { return dt == CONV_F32 ? "f32" : dt == CONV_F16 ? "f16" : "bf16"; }
+inline int dtype_size(int dt) { return dt == CONV_F32 ? 4 : 2; }
+
+}  // namespace convfwd

@@ -1,0 +1,193 @@
+"""Host-side checks of libconvfwd.so that need no GPU: exported symbols, descriptor validation,
+shape/FLOP formulas against the paper's table, the cooperative-load rule, variant listing, cache files."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_1611_06945_amd import binding as B
+from paper_1611_06945_amd.workloads import config1, config2, config3, config4, config5_layers
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "convfwd.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b([a-z_]+)\s*\(", text)) - {"defined"})
+
+
+def test_library_exports_every_declared_symbol():
+    names = declared_functions()
+    assert {"conv_fwd", "conv_fwd_ws", "conv_autotune", "conv_out_shape", "maxpool_fwd", "conv_strerror",
+            "conv_cache_load", "conv_cache_save", "conv_force_variant", "conv_variant_count",
+            "conv_variant_name", "conv_workspace_bytes", "conv_coop_load_plan"} <= set(names)
+    L = B.lib()
+    for n in names:
+        assert hasattr(L, n), "libconvfwd.so does not export %s" % n
+
+
+def test_binding_mirrors_the_header():
+    for n in declared_functions():
+        assert hasattr(B, n) or n == "conv_strerror", n
+    assert B.strerror(0) == "success"
+
+
+def test_out_shape_and_flops_match_appendix_a(appendix_a):
+    for row in appendix_a:
+        d = B.make_desc(row["b"], row["in_c"], row["in_y"], row["in_x"], row["oc"], row["ksz"], row["ksz"],
+                        row["stride"], row["pad"])
+        assert B.conv_out_shape(d) == (row["out_y"], row["out_x"]), row
+        assert "%.6g" % B.conv_flops(d) == "%.6g" % row["flops"], row
+
+
+def test_out_shape_of_benchmark_configs():
+    assert B.conv_out_shape(B.desc_of(config1().shape)) == (32, 32)
+    assert B.conv_out_shape(B.desc_of(config2().shape)) == (28, 28)
+    assert B.conv_out_shape(B.desc_of(config3().shape)) == (55, 55)
+    assert B.conv_out_shape(B.desc_of(config4(5).shape)) == (13, 13)
+    assert [B.conv_out_shape(B.desc_of(w.shape)) for w in config5_layers()] == [(55, 55), (27, 27), (13, 13), (13, 13), (13, 13)]
+
+
+@pytest.mark.parametrize("field,value", [("N", 0), ("C", 0), ("H", 0), ("W", -1), ("K", 0), ("R", 0), ("S", 0),
+                                         ("stride", 0), ("pad", -1), ("flags", 2)])
+def test_invalid_descriptor_fields(field, value):
+    d = B.make_desc(1, 3, 8, 8, 4, 3, 3, 1, 1)
+    setattr(d, field, value)
+    with pytest.raises(B.ConvError) as e:
+        B.conv_out_shape(d)
+    assert e.value.status == B.CONV_EINVAL
+    assert B.conv_flops(d) == 0.0
+    assert B.conv_workspace_bytes(d) == 0
+
+
+def test_invalid_geometry_dtype_and_sizes():
+    with pytest.raises(B.ConvError) as e:
+        B.conv_out_shape(B.make_desc(1, 1, 4, 4, 1, 5, 5))  # window larger than the padded input
+    assert e.value.status == B.CONV_EINVAL
+    assert B.conv_out_shape(B.make_desc(1, 1, 4, 4, 1, 5, 5, 1, 1)) == (2, 2)
+    assert B.conv_out_shape(B.make_desc(1, 1, 2, 2, 1, 2, 2, 1, 2)) == (5, 5)  # pad >= window is legal
+    with pytest.raises(B.ConvError) as e:
+        B.conv_out_shape(B.make_desc(1, 1, 4, 4, 1, 1, 1, dtype=7))
+    assert e.value.status == B.CONV_EDTYPE
+    with pytest.raises(B.ConvError) as e:
+        B.conv_out_shape(B.make_desc(4096, 1024, 32, 32, 1, 1, 1))  # 2^32 input elements
+    assert e.value.status == B.CONV_EINVAL
+    assert B.lib().conv_out_shape(None, None, None) == B.CONV_EINVAL
+
+
+def test_null_and_misaligned_pointers_are_rejected_before_any_gpu_call():
+    d = B.make_desc(1, 3, 8, 8, 4, 3, 3, 1, 1)
+    L = B.lib()
+    assert L.conv_fwd(ctypes.byref(d), None, 256, None, 512, None) == B.CONV_EINVAL
+    assert L.conv_fwd(ctypes.byref(d), 256, None, None, 512, None) == B.CONV_EINVAL
+    assert L.conv_fwd(ctypes.byref(d), 256, 512, None, None, None) == B.CONV_EINVAL
+    assert L.conv_fwd(ctypes.byref(d), 260, 512, None, 1024, None) == B.CONV_EINVAL  # not 16-byte aligned
+    assert L.conv_fwd(None, 256, 512, None, 1024, None) == B.CONV_EINVAL
+    assert L.conv_autotune(ctypes.byref(d), None, 256, None, 512, None, 0, None) == B.CONV_EINVAL
+    assert L.maxpool_fwd(1, 1, 2, 2, 3, 2, 0, 256, 512, None) == B.CONV_EINVAL  # window larger than input
+    assert L.maxpool_fwd(1, 1, 5, 5, 3, 2, 9, 256, 512, None) == B.CONV_EDTYPE
+    assert L.maxpool_fwd(1, 1, 5, 5, 3, 2, 0, None, 512, None) == B.CONV_EINVAL
+
+
+def test_cooperative_load_plan_worked_example():
+    # Section 3, "Metaprogramming for NN Convolutions": 96 threads loading 256 words issue three loads and only the
+    # third is guarded; 64 threads loading 256 words issue four loads, none guarded.
+    assert B.conv_coop_load_plan(96, 256) == (3, True)
+    assert B.conv_coop_load_plan(64, 256) == (4, False)
+    assert B.conv_coop_load_plan(256, 256) == (1, False)
+    assert B.conv_coop_load_plan(256, 1) == (1, True)
+    for threads in (1, 7, 64, 96, 256):
+        for words in (1, 63, 64, 65, 255, 256, 257, 2048):
+            n, g = B.conv_coop_load_plan(threads, words)
+            assert n == -(-words // threads) and g == (words % threads != 0)
+    with pytest.raises(B.ConvError):
+        B.conv_coop_load_plan(0, 5)
+
+
+def all_bench_descs():
+    ws = [config1(), config2(), config3()] + [config4(n, dt) for n in (1, 5, 20) for dt in (0, 1, 2)] + config5_layers()
+    return [(w.name, B.desc_of(w.shape, w.dtype, relu=True)) for w in ws]
+
+
+def test_every_benchmark_shape_has_variants_with_unique_names():
+    for name, d in all_bench_descs():
+        n = B.conv_variant_count(d)
+        assert n >= 2, name
+        names = [B.conv_variant_name(d, i) for i in range(n)]
+        assert len(set(names)) == n
+        tag = {0: "_f32_", 1: "_f16_", 2: "_bf16_"}[d.dtype]
+        assert all(tag in x for x in names), (name, names)
+        assert B.conv_variant_name(d, -1) in names and B.conv_variant_name(d, -2) in names
+        # the choice conv_fwd makes needs no workspace; the declared workspace covers every variant
+        nows = names.index(B.conv_variant_name(d, -2))
+        assert B.conv_variant_workspace(d, nows) == 0
+        assert B.conv_workspace_bytes(d) == max(B.conv_variant_workspace(d, i) for i in range(n))
+        with pytest.raises(B.ConvError) as e:
+            B.conv_variant_name(d, n)
+        assert e.value.status == B.CONV_ENOVARIANT
+
+
+def test_pointwise_variants_only_offered_for_pointwise_shapes():
+    d2 = B.desc_of(config2().shape, 0)
+    names2 = [B.conv_variant_name(d2, i) for i in range(B.conv_variant_count(d2))]
+    assert any(n.startswith("pw_") for n in names2)
+    d4 = B.desc_of(config4(5).shape, 0)
+    assert not any(B.conv_variant_name(d4, i).startswith("pw_") for i in range(B.conv_variant_count(d4)))
+    # element-wise filter loaders are the only ones valid when C*R*S is not a multiple of the vector width
+    d3 = B.desc_of(config3().shape, 0)
+    assert all(B.conv_variant_name(d3, i).split("_sk")[0].endswith("_s") or "_v" not in B.conv_variant_name(d3, i)
+               for i in range(B.conv_variant_count(d3)))
+
+
+def test_force_variant_and_cache_roundtrip(tmp_path):
+    B.conv_cache_clear()
+    d = B.desc_of(config4(5).shape, 0)
+    n = B.conv_variant_count(d)
+    default = B.conv_variant_name(d, -1)
+    B.conv_force_variant(d, n - 1)
+    assert B.conv_variant_name(d, -1) == B.conv_variant_name(d, n - 1)
+    with pytest.raises(B.ConvError):
+        B.conv_force_variant(d, n)
+    B.conv_force_variant(d, -1)
+    assert B.conv_variant_name(d, -1) == default
+
+    # a cache file naming a different (valid) variant changes the selection; clear restores the heuristic
+    other = next(B.conv_variant_name(d, i) for i in range(n)
+                 if B.conv_variant_name(d, i) != default and B.conv_variant_workspace(d, i) == 0)
+    path = tmp_path / "cache.txt"
+    path.write_text("# comment\n5 256 13 13 384 3 3 1 1 0 1 | %s | %s\n" % (other, other))
+    B.conv_cache_load(str(path))
+    assert B.conv_variant_name(d, -1) == other and B.conv_variant_name(d, -2) == other
+    out = tmp_path / "saved.txt"
+    B.conv_cache_save(str(out))
+    assert ("5 256 13 13 384 3 3 1 1 0 1 | %s | %s" % (other, other)) in out.read_text()
+    B.conv_cache_clear()
+    assert B.conv_variant_name(d, -1) == default
+    B.conv_cache_load(str(out))
+    assert B.conv_variant_name(d, -1) == other
+    B.conv_cache_clear()
+
+
+def test_bad_cache_files_leave_the_cache_alone(tmp_path):
+    B.conv_cache_clear()
+    d = B.desc_of(config4(5).shape, 0)
+    default = B.conv_variant_name(d, -1)
+    with pytest.raises(B.ConvError) as e:
+        B.conv_cache_load(str(tmp_path / "missing.txt"))
+    assert e.value.status == B.CONV_EIO
+    bad = tmp_path / "bad.txt"
+    bad.write_text("5 256 13 13 384 3 3 1 1 0 1 | only-one-field\n")
+    with pytest.raises(B.ConvError):
+        B.conv_cache_load(str(bad))
+    bad.write_text("5 256 13 x 384 3 3 1 1 0 1 | a | b\n")
+    with pytest.raises(B.ConvError):
+        B.conv_cache_load(str(bad))
+    # unknown variant names (a cache from another build) are ignored, not an error
+    bad.write_text("5 256 13 13 384 3 3 1 1 0 1 | nosuch | nosuch\n")
+    B.conv_cache_load(str(bad))
+    assert B.conv_variant_name(d, -1) == default
+    with pytest.raises(B.ConvError) as e:
+        B.conv_cache_save(str(tmp_path / "no_such_dir" / "x.txt"))
+    assert e.value.status == B.CONV_EIO
