@@ -47,7 +47,8 @@ enum { CONV_FLAG_RELU = 1u }; /* act = max(x,0); without it act is the identity 
 typedef enum {
     CONV_OK = 0,
     CONV_EINVAL = -1,     /* NULL descriptor/pointer; N,C,H,W,K,R,S < 1; stride < 1; pad < 0; window larger than
-                             the padded input; a tensor with 2^31 or more elements; unknown flag bits */
+                             the padded input; a tensor with 2^31 or more elements or 4 GiB or more; a tensor pointer
+                             that is not 16-byte aligned; unknown flag bits */
     CONV_EDTYPE = -2,     /* dtype is not one of conv_dtype */
     CONV_EWORKSPACE = -3, /* workspace NULL/too small for what was asked (forced split variant, autotune) */
     CONV_EHIP = -4,       /* a HIP call failed; conv_strerror(CONV_EHIP) carries the HIP message */

@@ -80,6 +80,11 @@ int check_desc(const conv_desc* d, int& OH, int& OW)
     if ((double)d->N * d->C * (double)d->H * d->W >= (double)lim) return CONV_EINVAL;
     if ((double)d->K * d->C * (double)d->R * d->S >= (double)lim) return CONV_EINVAL;
     if ((double)d->N * d->K * (double)oh * (double)ow >= (double)lim) return CONV_EINVAL;
+    // tile loads go through 32-bit buffer descriptors: every tensor must also stay below 4 GiB
+    const double esz = d->dtype == CONV_F32 ? 4.0 : 2.0, lim_b = 4294967296.0;
+    if ((double)d->N * d->C * (double)d->H * d->W * esz >= lim_b) return CONV_EINVAL;
+    if ((double)d->K * d->C * (double)d->R * d->S * esz >= lim_b) return CONV_EINVAL;
+    if ((double)d->N * d->K * (double)oh * (double)ow * esz >= lim_b) return CONV_EINVAL;
     // the padded coordinates formed inside the kernels must fit an int as well
     if ((double)(d->H + 2.0 * d->pad) * (double)(d->W + 2.0 * d->pad) >= (double)lim) return CONV_EINVAL;
     (void)n_in;
@@ -180,6 +185,9 @@ void fill_args(ConvArgs& a, const conv_desc& d, int OH, int OW, const void* in, 
     a.OHW = OH * OW;
     a.RS = d.R * d.S;
     a.relu = (d.flags & CONV_FLAG_RELU) ? 1 : 0;
+    a.in_bytes = (uint32_t)((uint64_t)d.N * d.C * d.H * d.W * dtype_size(d.dtype));
+    a.filt_bytes = (uint32_t)((uint64_t)d.K * d.C * d.R * d.S * dtype_size(d.dtype));
+    a.out_bytes = (uint32_t)((uint64_t)d.N * d.K * OH * OW * dtype_size(d.dtype));
     a.nsplit = 1;
     a.steps_per_split = 0;
     a.dRS = make_fastdiv((uint32_t)a.RS);

@@ -74,6 +74,7 @@ struct ConvArgs {
     int OHW;  // OH*OW
     int RS;   // R*S
     int relu;
+    uint32_t in_bytes, filt_bytes, out_bytes;  // extents for the hardware bounds check of tile loads
     int nsplit;           // number of reduction splits (gridDim.z)
     int steps_per_split;  // reduction steps (of the kernel's own step size) per split
     FastDiv dRS, dS, dOHW, dOW;

@@ -27,6 +27,40 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+// Buffer descriptors let the hardware do the bounds test of a guarded tile load: a load whose byte offset is not
+// below `bytes` returns zero, so a lane that must not read (padding, ragged tile edge) is simply pointed out of
+// range -- no branch and no exec-mask juggling around the load (the paper's point about keeping conditionals out
+// of the unrolled load sequence, Section 3 "Metaprogramming for NN Convolutions").
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p, uint32_t bytes)
+{
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, (int)bytes, 0x00020000);
+}
+constexpr uint32_t kOutOfRange = 0xFFFFFFFFu;
+
+template <typename E>
+__device__ __forceinline__ E buffer_load_elem(__amdgpu_buffer_rsrc_t r, uint32_t byte_off)
+{
+    if constexpr (sizeof(E) == 4)
+        return __builtin_bit_cast(E, __builtin_amdgcn_raw_buffer_load_b32(r, (int)byte_off, 0, 0));
+    else
+        return (E)__builtin_amdgcn_raw_buffer_load_b16(r, (int)byte_off, 0, 0);
+}
+// Stores through a descriptor: a store whose offset is out of range is dropped by the hardware.
+template <typename E>
+__device__ __forceinline__ void buffer_store_elem(E v, __amdgpu_buffer_rsrc_t r, uint32_t byte_off)
+{
+    if constexpr (sizeof(E) == 4)
+        __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, v), r, (int)byte_off, 0, 0);
+    else
+        __builtin_amdgcn_raw_buffer_store_b16((uint16_t)v, r, (int)byte_off, 0, 0);
+}
+__device__ __forceinline__ uint4 buffer_load_vec(__amdgpu_buffer_rsrc_t r, uint32_t byte_off)
+{
+    const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(r, (int)byte_off, 0, 0);
+    return make_uint4(v.x, v.y, v.z, v.w);
+}
 
 // ---------------------------------------------------------------------------
 // storage types
@@ -199,8 +233,9 @@ __global__ __launch_bounds__(CFG::NT) void igemm_kernel(ConvArgs a)
     const int lrow = lane % MB, kg = lane / MB;
     const int p0 = blockIdx.x * TN, m0 = blockIdx.y * TM;
 
-    const elem_t* __restrict__ gin = (const elem_t*)a.in;
-    const elem_t* __restrict__ gfilt = (const elem_t*)a.filt;
+    constexpr uint32_t ES = sizeof(elem_t);
+    const __amdgpu_buffer_rsrc_t rin = make_rsrc(a.in, a.in_bytes);
+    const __amdgpu_buffer_rsrc_t rfilt = make_rsrc(a.filt, a.filt_bytes);
 
     // reduction steps of this split
     const int total_steps = (a.Q + TK - 1) / TK;
@@ -246,9 +281,7 @@ __global__ __launch_bounds__(CFG::NT) void igemm_kernel(ConvArgs a)
                 const bool in_tile = (i + 1 < planAv.loads || !planAv.last_guarded) ? true : (v < TM * TK / VEC);
                 const int row = v / (TK / VEC), col = (v % (TK / VEC)) * VEC;
                 const bool ok = in_tile && (m0 + row < a.K) && (q0 + col < a.Q);
-                uint4 val = make_uint4(0, 0, 0, 0);
-                if (ok) val = *(const uint4*)(gfilt + (size_t)(m0 + row) * a.Q + q0 + col);
-                a_vec[i] = val;
+                a_vec[i] = buffer_load_vec(rfilt, ok ? (uint32_t)((m0 + row) * a.Q + q0 + col) * ES : kOutOfRange);
             }
         } else {
 #pragma unroll
@@ -257,9 +290,7 @@ __global__ __launch_bounds__(CFG::NT) void igemm_kernel(ConvArgs a)
                 const bool in_tile = (i + 1 < planAs.loads || !planAs.last_guarded) ? true : (v < TM * TK);
                 const int row = v / TK, col = v % TK;
                 const bool ok = in_tile && (m0 + row < a.K) && (q0 + col < a.Q);
-                elem_t val = 0;
-                if (ok) val = gfilt[(size_t)(m0 + row) * a.Q + q0 + col];
-                a_sc[i] = val;
+                a_sc[i] = buffer_load_elem<elem_t>(rfilt, ok ? (uint32_t)((m0 + row) * a.Q + q0 + col) * ES : kOutOfRange);
             }
         }
         // patch tile
@@ -276,9 +307,7 @@ __global__ __launch_bounds__(CFG::NT) void igemm_kernel(ConvArgs a)
                 for (int e = 0; e < CHW; ++e) {
                     const bool ok = g_pvalid && (q + e < a.Q) && ((unsigned)(g_iy0 + ri) < (unsigned)a.H) &&
                                     ((unsigned)(g_ix0 + si) < (unsigned)a.W);
-                    elem_t val = 0;
-                    if (ok) val = gin[g_base + off];
-                    b_reg[j][e] = val;
+                    b_reg[j][e] = buffer_load_elem<elem_t>(rin, ok ? (uint32_t)(g_base + off) * ES : kOutOfRange);
                     ++si;
                     ++off;
                     if (si == a.S) {
@@ -300,9 +329,7 @@ __global__ __launch_bounds__(CFG::NT) void igemm_kernel(ConvArgs a)
                 const int krow = v / (TN / 4);
                 const int c = q0 + krow;
                 const bool ok = in_tile && g_pvalid && (c < a.C);
-                uint4 val = make_uint4(0, 0, 0, 0);
-                if (ok) val = *(const uint4*)(gin + (size_t)g_base + (size_t)c * a.HW);
-                b_vec[i] = val;
+                b_vec[i] = buffer_load_vec(rin, ok ? (uint32_t)(g_base + c * a.HW) * ES : kOutOfRange);
             }
         }
     };
@@ -367,35 +394,40 @@ __global__ __launch_bounds__(CFG::NT) void igemm_kernel(ConvArgs a)
         const elem_t* __restrict__ A = As[buf];
         const elem_t* __restrict__ B = Bs[buf];
         if constexpr (CFG::B_KMAJOR) {
+            // all fragments of the step are requested first, so the LDS latency overlaps the MFMA chain
+            f32x4 af[KPL / 4][BM];
+            float bf[KPL][BN];
 #pragma unroll
-            for (int ii = 0; ii < KPL / 4; ++ii) {
-                f32x4 af[BM];
+            for (int ii = 0; ii < KPL / 4; ++ii)
 #pragma unroll
-                for (int bm = 0; bm < BM; ++bm) af[bm] = *(const f32x4*)&A[a_row0 + bm * MB * LDA + ii * 4];
+                for (int bm = 0; bm < BM; ++bm) af[ii][bm] = *(const f32x4*)&A[a_row0 + bm * MB * LDA + ii * 4];
 #pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    float bf[BN];
+            for (int kk = 0; kk < KPL; ++kk)
 #pragma unroll
-                    for (int bn = 0; bn < BN; ++bn) bf[bn] = B[(kg * KPL + ii * 4 + e) * LDB + b_col0 + bn * MB];
+                for (int bn = 0; bn < BN; ++bn) bf[kk][bn] = B[(kg * KPL + kk) * LDB + b_col0 + bn * MB];
 #pragma unroll
-                    for (int bm = 0; bm < BM; ++bm)
-#pragma unroll
-                        for (int bn = 0; bn < BN; ++bn) acc[bm][bn] = mma_t::run(af[bm][e], bf[bn], acc[bm][bn]);
-                }
-            }
-        } else {
-#pragma unroll
-            for (int i = 0; i < NMMA; ++i) {
-                uint4 af[BM], bf[BN];
-#pragma unroll
-                for (int bm = 0; bm < BM; ++bm) af[bm] = *(const uint4*)&A[a_row0 + bm * MB * LDA + i * 8];
-#pragma unroll
-                for (int bn = 0; bn < BN; ++bn) bf[bn] = *(const uint4*)&B[(b_col0 + bn * MB) * LDB + kg * KPL + i * 8];
+            for (int kk = 0; kk < KPL; ++kk)
 #pragma unroll
                 for (int bm = 0; bm < BM; ++bm)
 #pragma unroll
-                    for (int bn = 0; bn < BN; ++bn) acc[bm][bn] = mma_t::run(af[bm], bf[bn], acc[bm][bn]);
+                    for (int bn = 0; bn < BN; ++bn)
+                        acc[bm][bn] = mma_t::run(af[kk / 4][bm][kk % 4], bf[kk][bn], acc[bm][bn]);
+        } else {
+            uint4 af[NMMA][BM], bf[NMMA][BN];
+#pragma unroll
+            for (int i = 0; i < NMMA; ++i) {
+#pragma unroll
+                for (int bm = 0; bm < BM; ++bm) af[i][bm] = *(const uint4*)&A[a_row0 + bm * MB * LDA + i * 8];
+#pragma unroll
+                for (int bn = 0; bn < BN; ++bn)
+                    bf[i][bn] = *(const uint4*)&B[(b_col0 + bn * MB) * LDB + kg * KPL + i * 8];
             }
+#pragma unroll
+            for (int i = 0; i < NMMA; ++i)
+#pragma unroll
+                for (int bm = 0; bm < BM; ++bm)
+#pragma unroll
+                    for (int bn = 0; bn < BN; ++bn) acc[bm][bn] = mma_t::run(af[i][bm], bf[i][bn], acc[bm][bn]);
         }
     };
 
@@ -416,29 +448,54 @@ __global__ __launch_bounds__(CFG::NT) void igemm_kernel(ConvArgs a)
     }
 
     // ---- epilogue ---------------------------------------------------------------------------------
-    const bool split = a.nsplit > 1;
+    // Pixel coordinates of this lane's accumulator columns.
+    int e_p[BN];
+    uint32_t e_img[BN], e_pix[BN];
 #pragma unroll
     for (int bn = 0; bn < BN; ++bn) {
-        const int p = p0 + wn * BN * MB + bn * MB + lrow;
-        if (p >= a.P) continue;
-        uint32_t n_img, pix;
-        a.dOHW.divmod((uint32_t)p, n_img, pix);
+        e_p[bn] = p0 + wn * BN * MB + bn * MB + lrow;
+        a.dOHW.divmod(e_p[bn] < a.P ? (uint32_t)e_p[bn] : 0u, e_img[bn], e_pix[bn]);
+    }
+    if (a.nsplit > 1) {
+        // partial sums of this split, [split][K][P] fp32; the fixed-order second pass applies bias and activation
+        const __amdgpu_buffer_rsrc_t rws = make_rsrc(a.ws + (size_t)blockIdx.z * a.K * a.P, (uint32_t)a.K * a.P * 4u);
 #pragma unroll
-        for (int bm = 0; bm < BM; ++bm) {
+        for (int bm = 0; bm < BM; ++bm)
 #pragma unroll
             for (int v = 0; v < ACC_N; ++v) {
                 const int k = m0 + wm * BM * MB + bm * MB + acc_row<MB>(v, lane);
-                if (k >= a.K) continue;
-                float x = acc[bm][bn][v];
-                if (split) {
-                    a.ws[((size_t)blockIdx.z * a.K + k) * a.P + p] = x;
-                } else {
-                    if (a.bias) x += a.bias[k];
-                    if (a.relu) x = x > 0.0f ? x : 0.0f;
-                    ((elem_t*)a.out)[((size_t)n_img * a.K + k) * a.OHW + pix] = Prec<DT>::from_f32(x);
+#pragma unroll
+                for (int bn = 0; bn < BN; ++bn) {
+                    const bool ok = k < a.K && e_p[bn] < a.P;
+                    buffer_store_elem<float>(acc[bm][bn][v], rws, ok ? (uint32_t)(k * a.P + e_p[bn]) * 4u : kOutOfRange);
                 }
             }
-        }
+    } else {
+        // bias of every accumulator row of this lane is fetched up front (a null bias reads as zeros)
+        const __amdgpu_buffer_rsrc_t rbias = make_rsrc(a.bias, a.bias ? (uint32_t)a.K * 4u : 0u);
+        float bias_r[BM][ACC_N];
+#pragma unroll
+        for (int bm = 0; bm < BM; ++bm)
+#pragma unroll
+            for (int v = 0; v < ACC_N; ++v) {
+                const int k = m0 + wm * BM * MB + bm * MB + acc_row<MB>(v, lane);
+                bias_r[bm][v] = buffer_load_elem<float>(rbias, (uint32_t)k * 4u);
+            }
+        const __amdgpu_buffer_rsrc_t rout = make_rsrc(a.out, a.out_bytes);
+#pragma unroll
+        for (int bm = 0; bm < BM; ++bm)
+#pragma unroll
+            for (int v = 0; v < ACC_N; ++v) {
+                const int k = m0 + wm * BM * MB + bm * MB + acc_row<MB>(v, lane);
+#pragma unroll
+                for (int bn = 0; bn < BN; ++bn) {
+                    float x = acc[bm][bn][v] + bias_r[bm][v];
+                    if (a.relu) x = x > 0.0f ? x : 0.0f;
+                    const bool ok = k < a.K && e_p[bn] < a.P;
+                    buffer_store_elem<elem_t>(Prec<DT>::from_f32(x), rout,
+                                              ok ? (uint32_t)((e_img[bn] * a.K + k) * a.OHW + e_pix[bn]) * ES : kOutOfRange);
+                }
+            }
     }
 }
 
@@ -474,6 +531,7 @@ bool igemm_valid(const Variant& v, const conv_desc& d, int OH, int OW)
     // a split must leave every part at least two reduction steps
     const long long steps = (Q + CFG::TK - 1) / CFG::TK;
     if (v.split > 1 && steps < 2LL * v.split) return false;
+    if (v.split > 1 && (long long)d.K * P * 4 >= (1LL << 32)) return false;  // one split's partial sums: 32-bit offsets
     if (d.K > 65535LL * CFG::TM) return false;
     return true;
 }
