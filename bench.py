@@ -226,6 +226,16 @@ def main():
         ach = w.shape.algorithmic_bytes(w.dtype) / (kern_ms * 1e-3) / 1e9
         roof = {"bound": "hbm", "achieved": round(ach, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
                 "frac": round(ach / PEAK_HBM_GBS, 5)}
+    # measured ceilings of this very device, next to the published ones
+    scratch = torch.zeros(64, device="cuda")
+    big = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
+    big2 = torch.empty_like(big)
+    measured = {"mfma_tflops": {}, "stream_copy_gbs": round(B.conv_probe_stream_bandwidth(big, big2, big.numel()), 1),
+                "note": "register-only MFMA issue loop (best block shape) and 1 GiB device-to-device copy (read+write bytes)"}
+    for code, name in ((wl.F32, "f32"), (wl.F16, "f16"), (wl.BF16, "bf16")):
+        measured["mfma_tflops"][name] = round(max(B.conv_probe_mfma_peak(code, 32, scratch), B.conv_probe_mfma_peak(code, 16, scratch)), 1)
+    del big, big2
+    roof["frac_of_measured"] = round(ach / (measured["mfma_tflops"][dt] if mfma_bound else measured["stream_copy_gbs"]), 5)
     roof["traffic"] = stored_traffic("%s|%s" % (w.name, variant))
     roof["kernel"] = variant
     roof["kernel_ms"] = round(kern_ms, 6)
@@ -238,6 +248,7 @@ def main():
                    "K": w.shape.K, "R": w.shape.R, "S": w.shape.S, "stride": w.shape.stride, "pad": w.shape.pad,
                    "fused": "bias+relu", "variant": variant, "paper_row": w.paper_row},
         "roofline": roof,
+        "measured_peaks": measured,
     }
 
     if not a.no_layers:

@@ -160,6 +160,17 @@ int conv_coop_load_plan(int threads, int words, int* loads_per_thread, int* last
 int maxpool_fwd(int32_t N, int32_t C, int32_t H, int32_t W, int32_t win, int32_t stride, int32_t dtype,
                 const void* in, void* out, void* stream);
 
+/*
+ * Measured ceilings of the device, for reporting next to the published peaks (the paper's own practice of timing on
+ * the device with device-level timers, Section 4 "Experimental Setup").  Both synchronise `stream`.
+ *  - conv_probe_mfma_peak: TFLOP/s of a register-only MFMA issue loop for `dtype` with 16x16 or 32x32 blocks
+ *    (`block` = 16 or 32); `scratch` is any 4-byte device location (never written in practice).
+ *  - conv_probe_stream_bandwidth: GB/s (bytes read + bytes written) of a plain copy of `bytes` from `src` to `dst`,
+ *    both device pointers, 16-byte aligned, not overlapping.
+ */
+int conv_probe_mfma_peak(int32_t dtype, int32_t block, void* scratch, void* stream, double* tflops);
+int conv_probe_stream_bandwidth(const void* src, void* dst, size_t bytes, void* stream, double* gbytes_per_s);
+
 /* Text for a conv_status; for CONV_EHIP it includes the message of the last failed HIP call of this thread. */
 const char* conv_strerror(int status);
 

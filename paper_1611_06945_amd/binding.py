@@ -83,6 +83,10 @@ def lib() -> ctypes.CDLL:
         L.conv_coop_load_plan.restype = ctypes.c_int
         L.maxpool_fwd.argtypes = [ctypes.c_int32] * 7 + [vp, vp, vp]
         L.maxpool_fwd.restype = ctypes.c_int
+        L.conv_probe_mfma_peak.argtypes = [ctypes.c_int32, ctypes.c_int32, vp, vp, ctypes.POINTER(ctypes.c_double)]
+        L.conv_probe_mfma_peak.restype = ctypes.c_int
+        L.conv_probe_stream_bandwidth.argtypes = [vp, vp, ctypes.c_size_t, vp, ctypes.POINTER(ctypes.c_double)]
+        L.conv_probe_stream_bandwidth.restype = ctypes.c_int
         L.conv_strerror.argtypes = [ctypes.c_int]
         L.conv_strerror.restype = ctypes.c_char_p
         _lib = L
@@ -204,3 +208,16 @@ def conv_coop_load_plan(threads: int, words: int) -> Tuple[int, bool]:
 
 def maxpool_fwd(N, C, H, W, win, stride, dtype, inp, out, stream=None) -> None:
     _check(lib().maxpool_fwd(N, C, H, W, win, stride, dtype, _ptr(inp), _ptr(out), _stream(stream)), "maxpool_fwd")
+
+
+def conv_probe_mfma_peak(dtype: int, block: int, scratch, stream=None) -> float:
+    v = ctypes.c_double()
+    _check(lib().conv_probe_mfma_peak(dtype, block, _ptr(scratch), _stream(stream), ctypes.byref(v)), "conv_probe_mfma_peak")
+    return v.value
+
+
+def conv_probe_stream_bandwidth(src, dst, nbytes: int, stream=None) -> float:
+    v = ctypes.c_double()
+    _check(lib().conv_probe_stream_bandwidth(_ptr(src), _ptr(dst), int(nbytes), _stream(stream), ctypes.byref(v)),
+           "conv_probe_stream_bandwidth")
+    return v.value

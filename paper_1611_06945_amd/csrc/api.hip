@@ -45,6 +45,7 @@ State& state()
         register_igemm_f32(s->variants);
         register_igemm_f16(s->variants);
         register_igemm_bf16(s->variants);
+        register_wconv_f32(s->variants);
         for (size_t i = 0; i < s->variants.size(); ++i) s->by_name[s->variants[i].name] = (int)i;
         return s;
     }();
@@ -194,6 +195,8 @@ void fill_args(ConvArgs& a, const conv_desc& d, int OH, int OW, const void* in, 
     a.dS = make_fastdiv((uint32_t)d.S);
     a.dOHW = make_fastdiv((uint32_t)a.OHW);
     a.dOW = make_fastdiv((uint32_t)OW);
+    a.dHW = make_fastdiv((uint32_t)a.HW);
+    a.dW = make_fastdiv((uint32_t)d.W);
 }
 
 int run_variant(const Variant& v, const conv_desc& d, ConvArgs& a, hipStream_t s)
@@ -517,6 +520,23 @@ int maxpool_fwd(int32_t N, int32_t C, int32_t H, int32_t W, int32_t win, int32_t
     if ((double)N * C * (double)H * W >= 2147483648.0) return CONV_EINVAL;
     const hipError_t e = launch_maxpool(N, C, H, W, win, stride, dtype, in, out, (hipStream_t)stream);
     if (e != hipSuccess) return hip_fail(e, "maxpool");
+    return CONV_OK;
+}
+
+int conv_probe_mfma_peak(int32_t dtype, int32_t block, void* scratch, void* stream, double* tflops)
+{
+    if (dtype != CONV_F32 && dtype != CONV_F16 && dtype != CONV_BF16) return CONV_EDTYPE;
+    if ((block != 16 && block != 32) || !scratch || !tflops) return CONV_EINVAL;
+    const hipError_t e = probe_mfma(dtype, block, (float*)scratch, (hipStream_t)stream, tflops);
+    if (e != hipSuccess) return hip_fail(e, "probe_mfma");
+    return CONV_OK;
+}
+
+int conv_probe_stream_bandwidth(const void* src, void* dst, size_t bytes, void* stream, double* gbytes_per_s)
+{
+    if (!src || !dst || bytes < 16 || !gbytes_per_s || !aligned16(src) || !aligned16(dst)) return CONV_EINVAL;
+    const hipError_t e = probe_copy(src, dst, bytes, (hipStream_t)stream, gbytes_per_s);
+    if (e != hipSuccess) return hip_fail(e, "probe_copy");
     return CONV_OK;
 }
 

@@ -77,7 +77,7 @@ struct ConvArgs {
     uint32_t in_bytes, filt_bytes, out_bytes;  // extents for the hardware bounds check of tile loads
     int nsplit;           // number of reduction splits (gridDim.z)
     int steps_per_split;  // reduction steps (of the kernel's own step size) per split
-    FastDiv dRS, dS, dOHW, dOW;
+    FastDiv dRS, dS, dOHW, dOW, dHW, dW;
 };
 
 struct Variant;
@@ -91,23 +91,28 @@ struct Variant {
     int split;         // reduction splits; 1 = result written directly with the fused epilogue
     int tm, tn, tk;    // workgroup tile: output channels x pixels x reduction step
     int threads;       // workgroup size
-    int family;        // 0 generic implicit GEMM, 1 pointwise, 2 first layer / small C
+    int family;        // FAM_*
     int specificity;   // higher = written for a narrower class of shapes (heuristic tie-break)
     ValidFn valid;
     LaunchFn launch;
 };
 
-enum { FAM_IGEMM = 0, FAM_POINTWISE = 1, FAM_FIRSTLAYER = 2 };
+enum { FAM_IGEMM = 0, FAM_POINTWISE = 1, FAM_FIRSTLAYER = 2, FAM_WINDOW = 3 };
 
 // Each kernel file appends its variants.
 void register_igemm_f32(std::vector<Variant>& out);
 void register_igemm_f16(std::vector<Variant>& out);
 void register_igemm_bf16(std::vector<Variant>& out);
+void register_wconv_f32(std::vector<Variant>& out);
 
 // Split-reduction second pass and the max-pool helper (aux_kernels.hip).
 hipError_t launch_split_reduce(const ConvArgs& a, int dtype, hipStream_t s);
 hipError_t launch_maxpool(int N, int C, int H, int W, int win, int stride, int dtype, const void* in, void* out,
                           hipStream_t s);
+
+// Device ceilings measured in place (probe_kernels.hip).
+hipError_t probe_mfma(int dtype, int block, float* sink, hipStream_t s, double* tflops);
+hipError_t probe_copy(const void* src, void* dst, size_t bytes, hipStream_t s, double* gbs);
 
 inline const char* dtype_name(int dt) { return dt == CONV_F32 ? "f32" : dt == CONV_F16 ? "f16" : "bf16"; }
 inline int dtype_size(int dt) { return dt == CONV_F32 ? 4 : 2; }

@@ -55,6 +55,10 @@ SMALL_SHAPES = [
     ConvShape(3, 24, 6, 10, 50, 1, 1, 1, 0),    # pointwise, H*W % 4 == 0
     ConvShape(2, 20, 12, 12, 200, 3, 3, 1, 1),  # K spans two 128-row tiles; 180-long reduction allows splits
     ConvShape(2, 5, 23, 23, 96, 7, 7, 4, 0),    # first-layer like: few channels, big window, stride 4, K = 96
+    ConvShape(3, 64, 13, 13, 40, 3, 3, 1, 1),   # window-reuse kernel: 169 pixels per image, 4 channel chunks, ragged K
+    ConvShape(2, 32, 15, 15, 33, 3, 3, 1, 0),   # window-reuse kernel without padding (13x13 outputs)
+    ConvShape(2, 48, 12, 16, 16, 3, 3, 1, 1),   # window-reuse kernel, non-square image (192 pixels -> 13 blocks)
+    ConvShape(1, 32, 10, 11, 20, 3, 3, 1, 2),   # window-reuse kernel, pad 2 (12x13 outputs)
 ]
 
 
