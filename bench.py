@@ -147,7 +147,7 @@ def cpu_baseline(w, budget_s=12.0):
         oracle.conv_fwd(x, f, b, stride=w.shape.stride, pad=w.shape.pad, relu=True)
         n += 1
         dt = time.perf_counter() - t0
-        if dt >= budget_s or n >= 50:
+        if dt >= budget_s or n >= 1000:
             break
     return {"value": round(w.shape.flops * n / dt / 1e9, 3), "unit": "GFLOP/s", "cores": oracle.threads(),
             "kind": "oracle", "ms_per_step": round(dt / n * 1e3, 3),
@@ -159,7 +159,8 @@ def stored_traffic(kernel_key):
     path = os.path.join(ROOT, "profiles", "hbm_traffic.json")
     try:
         with open(path) as fh:
-            return json.load(fh).get(kernel_key)
+            rec = json.load(fh).get(kernel_key)
+            return None if rec is None else rec.get("total_bytes")
     except (OSError, ValueError):
         return None
 
