@@ -46,6 +46,8 @@ State& state()
         register_igemm_f16(s->variants);
         register_igemm_bf16(s->variants);
         register_wconv_f32(s->variants);
+        register_wconv_f16(s->variants);
+        register_wconv_bf16(s->variants);
         for (size_t i = 0; i < s->variants.size(); ++i) s->by_name[s->variants[i].name] = (int)i;
         return s;
     }();

@@ -104,6 +104,8 @@ void register_igemm_f32(std::vector<Variant>& out);
 void register_igemm_f16(std::vector<Variant>& out);
 void register_igemm_bf16(std::vector<Variant>& out);
 void register_wconv_f32(std::vector<Variant>& out);
+void register_wconv_f16(std::vector<Variant>& out);
+void register_wconv_bf16(std::vector<Variant>& out);
 
 // Split-reduction second pass and the max-pool helper (aux_kernels.hip).
 hipError_t launch_split_reduce(const ConvArgs& a, int dtype, hipStream_t s);

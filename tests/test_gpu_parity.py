@@ -59,6 +59,8 @@ SMALL_SHAPES = [
     ConvShape(2, 32, 15, 15, 33, 3, 3, 1, 0),   # window-reuse kernel without padding (13x13 outputs)
     ConvShape(2, 48, 12, 16, 16, 3, 3, 1, 1),   # window-reuse kernel, non-square image (192 pixels -> 13 blocks)
     ConvShape(1, 32, 10, 11, 20, 3, 3, 1, 2),   # window-reuse kernel, pad 2 (12x13 outputs)
+    ConvShape(2, 32, 27, 27, 40, 5, 5, 1, 2),   # 16-bit window kernel, 5x5: four bands of rows per image, last one partial
+    ConvShape(1, 64, 20, 20, 33, 3, 3, 1, 1),   # 16-bit window kernel, 3x3: bands of 9, 9 and 2 rows
 ]
 
 
