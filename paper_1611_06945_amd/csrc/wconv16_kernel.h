@@ -22,10 +22,14 @@
 
 namespace convfwd {
 
-template <int DT_, int R_, int S_, int KW_, int WM_, int TMB_, int WN_, int NBW_, int LBT_>
+template <int DT_, int R_, int S_, int KW_, int WM_, int TMB_, int WN_, int NBW_, int LBT_, int LBN_ = 0>
 struct Wconv16Cfg {
     static_assert(DT_ == CONV_F16 || DT_ == CONV_BF16, "16-bit storage only");
     static constexpr int DT = DT_, R = R_, S = S_, KW = KW_, WM = WM_, TMB = TMB_, WN = WN_, NBW = NBW_, LBT = LBT_;
+    // LBN > 0: the band is the whole image and its [CB][H*W] slab, contiguous and 16-byte aligned in global memory, is
+    // copied with LBN 16-byte loads per thread into a plain LDS buffer first and transposed from there (LDS to LDS);
+    // LBN = 0: the slab is gathered with 2-byte loads (any band, any alignment).
+    static constexpr int LBN = LBN_;
     static constexpr int RS = R * S;
     static constexpr int NT = 64 * KW * WM * WN;
     static constexpr int CB = 16 * KW;                 // channels per chunk
@@ -64,7 +68,8 @@ __global__ __launch_bounds__(CFG::NT) void wconv16_kernel(ConvArgs a)
     typedef uint16_t elem_t;
     constexpr int DT = CFG::DT, R = CFG::R, S = CFG::S, RS = CFG::RS, KW = CFG::KW, WM = CFG::WM, TMB = CFG::TMB;
     constexpr int WN = CFG::WN, NBW = CFG::NBW, LBT = CFG::LBT, NT = CFG::NT, CB = CFG::CB, TM = CFG::TM, TNP = CFG::TNP;
-    constexpr int KCH = CFG::KCH, LDA = CFG::LDA, CP = CFG::CP;
+    constexpr int KCH = CFG::KCH, LDA = CFG::LDA, CP = CFG::CP, LBN = CFG::LBN;
+    constexpr bool NAT = LBN > 0;
     constexpr CoopPlan planA = CFG::planA;
     typedef Mma<DT, 32> mma_t;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
@@ -74,6 +79,7 @@ __global__ __launch_bounds__(CFG::NT) void wconv16_kernel(ConvArgs a)
     elem_t* const As0 = (elem_t*)smem_raw;              // [2][TM*LDA]
     elem_t* const Bs0 = As0 + 2 * TM * LDA;             // [2][npos*CP]
     const int b_elems = geo.npos * CP;
+    elem_t* const Nat = Bs0 + 2 * b_elems;               // [CB][H*W] raw copy of the chunk's image slab (LBN > 0 only)
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int kw = wave % KW, wn = (wave / KW) % WN, wm = wave / (KW * WN);
@@ -110,6 +116,7 @@ __global__ __launch_bounds__(CFG::NT) void wconv16_kernel(ConvArgs a)
     const int ntask = band_pix * (CB / 8);
     int t_goff[LBT];   // element offset of (channel octet's first channel, pixel) relative to the chunk's first channel
     int t_lds[LBT];    // element index in the LDS slab, or -1
+    int t_nat[LBT];    // element index of (octet's first channel, pixel) in the raw LDS copy (LBN > 0)
 #pragma unroll
     for (int i = 0; i < LBT; ++i) {
         const int t = i * NT + tid;
@@ -119,11 +126,14 @@ __global__ __launch_bounds__(CFG::NT) void wconv16_kernel(ConvArgs a)
         uint32_t y, x;
         a.dW.divmod((uint32_t)pix, y, x);
         t_goff[i] = (oct * 8) * a.HW + iy_lo * a.W + pix;
+        t_nat[i] = t_goff[i];
         t_lds[i] = ok ? ((iy_lo - iy_first + (int)y) * PW + (int)x + a.pad) * CP + oct * 8 : -1;
     }
 
     uint4 a_reg[planA.loads];
-    elem_t b_reg[LBT][8];
+    elem_t b_reg[NAT ? 1 : LBT][8];
+    uint4 n_reg[NAT ? LBN : 1];
+    const int nvecN = (CB * a.HW) >> 3;  // 16-byte vectors of one [CB][H*W] slab
 
     auto load_chunk = [&](int chunk) {
         const int c0 = chunk * CB;
@@ -136,12 +146,20 @@ __global__ __launch_bounds__(CFG::NT) void wconv16_kernel(ConvArgs a)
             a_reg[i] = buffer_load_vec(rfilt, ok ? (uint32_t)((m0 + row) * a.Q + c0 * RS + col) * 2u : kOutOfRange);
         }
         const int slab = (img * a.C + c0) * a.HW;
+        if constexpr (NAT) {
 #pragma unroll
-        for (int i = 0; i < LBT; ++i) {
+            for (int i = 0; i < LBN; ++i) {
+                const int v = i * NT + tid;
+                n_reg[i] = buffer_load_vec(rin, v < nvecN ? (uint32_t)slab * 2u + (uint32_t)v * 16u : kOutOfRange);
+            }
+        } else {
 #pragma unroll
-            for (int j = 0; j < 8; ++j)
-                b_reg[i][j] = buffer_load_elem<elem_t>(
-                    rin, t_lds[i] >= 0 ? (uint32_t)(slab + t_goff[i] + j * a.HW) * 2u : kOutOfRange);
+            for (int i = 0; i < LBT; ++i) {
+#pragma unroll
+                for (int j = 0; j < 8; ++j)
+                    b_reg[i][j] = buffer_load_elem<elem_t>(
+                        rin, t_lds[i] >= 0 ? (uint32_t)(slab + t_goff[i] + j * a.HW) * 2u : kOutOfRange);
+            }
         }
     };
 
@@ -155,14 +173,39 @@ __global__ __launch_bounds__(CFG::NT) void wconv16_kernel(ConvArgs a)
             const int row = v / (KCH / 8), col = (v % (KCH / 8)) * 8;
             if (in_tile) *(uint4*)&As[row * LDA + col] = a_reg[i];
         }
+        if constexpr (NAT) {
+#pragma unroll
+            for (int i = 0; i < LBN; ++i) {
+                const int v = i * NT + tid;
+                if (v < nvecN) *(uint4*)&Nat[v * 8] = n_reg[i];
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < LBT; ++i) {
+                if (t_lds[i] >= 0) {
+                    uint4 pk;
+                    pk.x = (uint32_t)b_reg[i][0] | ((uint32_t)b_reg[i][1] << 16);
+                    pk.y = (uint32_t)b_reg[i][2] | ((uint32_t)b_reg[i][3] << 16);
+                    pk.z = (uint32_t)b_reg[i][4] | ((uint32_t)b_reg[i][5] << 16);
+                    pk.w = (uint32_t)b_reg[i][6] | ((uint32_t)b_reg[i][7] << 16);
+                    *(uint4*)&Bs[t_lds[i]] = pk;
+                }
+            }
+        }
+    };
+
+    // LBN > 0: second half of the staging, raw LDS copy -> channel-innermost slab (after a barrier)
+    auto transpose_chunk = [&](int buf) {
+        elem_t* Bs = Bs0 + buf * b_elems;
 #pragma unroll
         for (int i = 0; i < LBT; ++i) {
             if (t_lds[i] >= 0) {
+                const elem_t* src = Nat + t_nat[i];
                 uint4 pk;
-                pk.x = (uint32_t)b_reg[i][0] | ((uint32_t)b_reg[i][1] << 16);
-                pk.y = (uint32_t)b_reg[i][2] | ((uint32_t)b_reg[i][3] << 16);
-                pk.z = (uint32_t)b_reg[i][4] | ((uint32_t)b_reg[i][5] << 16);
-                pk.w = (uint32_t)b_reg[i][6] | ((uint32_t)b_reg[i][7] << 16);
+                pk.x = (uint32_t)src[0 * a.HW] | ((uint32_t)src[1 * a.HW] << 16);
+                pk.y = (uint32_t)src[2 * a.HW] | ((uint32_t)src[3 * a.HW] << 16);
+                pk.z = (uint32_t)src[4 * a.HW] | ((uint32_t)src[5 * a.HW] << 16);
+                pk.w = (uint32_t)src[6 * a.HW] | ((uint32_t)src[7 * a.HW] << 16);
                 *(uint4*)&Bs[t_lds[i]] = pk;
             }
         }
@@ -241,6 +284,10 @@ __global__ __launch_bounds__(CFG::NT) void wconv16_kernel(ConvArgs a)
         load_chunk(chunk_begin);
         __syncthreads();  // zero fill done before the first real write
         store_chunk(0);
+        if constexpr (NAT) {
+            __syncthreads();
+            transpose_chunk(0);
+        }
         __syncthreads();
         int buf = 0;
         for (int chunk = chunk_begin; chunk < chunk_end; ++chunk) {
@@ -248,6 +295,12 @@ __global__ __launch_bounds__(CFG::NT) void wconv16_kernel(ConvArgs a)
             if (more) load_chunk(chunk + 1);
             compute(buf, tap_first{}, tap_mid{});
             if (more) store_chunk(buf ^ 1);  // the other buffer was last read before the previous barrier
+            if constexpr (NAT) {
+                if (more) {
+                    __syncthreads();  // raw copy complete; it is not touched again before the barrier that ends this step
+                    transpose_chunk(buf ^ 1);
+                }
+            }
             compute(buf, tap_mid{}, tap_last{});
             __syncthreads();
             buf ^= 1;
@@ -314,10 +367,11 @@ __global__ __launch_bounds__(CFG::NT) void wconv16_kernel(ConvArgs a)
 }
 
 template <class CFG>
-size_t wconv16_lds_bytes(int W, int pad, int OH, int OW)
+size_t wconv16_lds_bytes(int H, int W, int pad, int OH, int OW)
 {
     const Wconv16Geom g = wconv16_geom<CFG>(W, pad, OH, OW);
-    const size_t pipe = 2 * sizeof(uint16_t) * ((size_t)CFG::TM * CFG::LDA + (size_t)g.npos * CFG::CP);
+    size_t pipe = 2 * sizeof(uint16_t) * ((size_t)CFG::TM * CFG::LDA + (size_t)g.npos * CFG::CP);
+    if (CFG::LBN > 0) pipe += sizeof(uint16_t) * (((size_t)CFG::CB * H * W + 7) / 8 * 8);
     const size_t red = sizeof(float) * (size_t)CFG::RED_FLOATS;
     return pipe > red ? pipe : red;
 }
@@ -325,7 +379,7 @@ size_t wconv16_lds_bytes(int W, int pad, int OH, int OW)
 template <class CFG>
 hipError_t wconv16_launch(const Variant& v, ConvArgs& a, hipStream_t s)
 {
-    const size_t lds = wconv16_lds_bytes<CFG>(a.W, a.pad, a.OH, a.OW);
+    const size_t lds = wconv16_lds_bytes<CFG>(a.H, a.W, a.pad, a.OH, a.OW);
     static size_t lds_allowed = 0;
     if (lds > lds_allowed) {
         const hipError_t e = hipFuncSetAttribute((const void*)wconv16_kernel<CFG>,
@@ -349,10 +403,15 @@ bool wconv16_valid(const Variant& v, const conv_desc& d, int OH, int OW)
     if ((d.C % CFG::CB) != 0) return false;
     if (OW > CFG::TNP) return false;
     const Wconv16Geom g = wconv16_geom<CFG>(d.W, d.pad, OH, OW);
+    if (CFG::LBN > 0) {
+        if (g.bands != 1) return false;  // the raw copy is the whole image slab
+        if ((long long)CFG::CB * d.H * d.W / 8 > (long long)CFG::NT * CFG::LBN) return false;
+        if (((long long)d.C * d.H * d.W) % 8 != 0) return false;  // every image's slab must start 16-byte aligned
+    }
     // every (input pixel of a band, channel octet) needs a staging slot
     const long long in_rows = g.in_rows < d.H ? g.in_rows : d.H;
     if (in_rows * d.W * (CFG::CB / 8) > (long long)CFG::NT * CFG::LBT) return false;
-    if (wconv16_lds_bytes<CFG>(d.W, d.pad, OH, OW) > 160 * 1024) return false;
+    if (wconv16_lds_bytes<CFG>(d.H, d.W, d.pad, OH, OW) > 160 * 1024) return false;
     // at least 60 % of the pixel columns computed over the image must be real
     if ((long long)OH * OW * 10 < (long long)g.bands * CFG::TNP * 6) return false;
     const int chunks = d.C / CFG::CB;
@@ -370,8 +429,8 @@ void wconv16_register(std::vector<Variant>& out, std::initializer_list<int> spli
     for (int sk : splits) {
         Variant v;
         char buf[160];
-        snprintf(buf, sizeof buf, "wconv_%s_%dx%d_M%dN%dC%d_w%dx%dx%d", dtype_name(CFG::DT), CFG::R, CFG::S, CFG::TM,
-                 CFG::TNP, CFG::CB, CFG::KW, CFG::WM, CFG::WN);
+        snprintf(buf, sizeof buf, "wconv_%s_%dx%d_M%dN%dC%d_w%dx%dx%d%s", dtype_name(CFG::DT), CFG::R, CFG::S, CFG::TM,
+                 CFG::TNP, CFG::CB, CFG::KW, CFG::WM, CFG::WN, CFG::LBN > 0 ? "_img" : "");
         v.name = buf;
         if (sk > 1) v.name += "_sk" + std::to_string(sk);
         v.dtype = CFG::DT;
