@@ -23,6 +23,10 @@ void register_igemm_f16(std::vector<Variant>& out)
     igemm_register<H16CFG(32, 1, 4, 1, 1, 32, false)>(out, "igemm", FAM_IGEMM, 0, sk_few);  // M32  N128
     igemm_register<H16CFG(16, 1, 4, 1, 1, 32, false)>(out, "igemm", FAM_IGEMM, 0, sk_one);  // M16  N64
     igemm_register<H16CFG(16, 2, 2, 1, 2, 32, false)>(out, "igemm", FAM_IGEMM, 0, sk_few);  // M32  N64
+    // twice the reduction step
+    igemm_register<H16CFG(32, 1, 4, 3, 1, 64, false)>(out, "igemm", FAM_IGEMM, 0, sk_one);  // M96  N128
+    igemm_register<H16CFG(32, 2, 2, 1, 2, 64, false)>(out, "igemm", FAM_IGEMM, 0, sk_one);  // M64  N128
+    igemm_register<H16CFG(32, 2, 2, 2, 1, 64, true)>(out, "igemm", FAM_IGEMM, 0, sk_few);   // M128 N64
 }
 
 }  // namespace convfwd
