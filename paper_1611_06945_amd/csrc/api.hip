@@ -199,6 +199,12 @@ void fill_args(ConvArgs& a, const conv_desc& d, int OH, int OW, const void* in, 
     a.dOW = make_fastdiv((uint32_t)OW);
     a.dHW = make_fastdiv((uint32_t)a.HW);
     a.dW = make_fastdiv((uint32_t)d.W);
+    a.SP4 = (d.S + 3) / 4;
+    a.QP = d.C * d.R * a.SP4 * 4;
+    a.dRSP = make_fastdiv((uint32_t)(d.R * a.SP4 * 4));
+    a.dSP = make_fastdiv((uint32_t)(a.SP4 * 4));
+    a.dRSP4 = make_fastdiv((uint32_t)(d.R * a.SP4));
+    a.dSP4 = make_fastdiv((uint32_t)a.SP4);
 }
 
 int run_variant(const Variant& v, const conv_desc& d, ConvArgs& a, hipStream_t s)

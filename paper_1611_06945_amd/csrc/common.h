@@ -73,11 +73,14 @@ struct ConvArgs {
     int HW;   // H*W
     int OHW;  // OH*OW
     int RS;   // R*S
+    int SP4;  // ceil(S/4): 4-column vectors per window row (s-vector gather)
+    int QP;   // C*R*4*SP4: reduction extent with window rows padded to a multiple of 4 columns
     int relu;
     uint32_t in_bytes, filt_bytes, out_bytes;  // extents for the hardware bounds check of tile loads
     int nsplit;           // number of reduction splits (gridDim.z)
     int steps_per_split;  // reduction steps (of the kernel's own step size) per split
     FastDiv dRS, dS, dOHW, dOW, dHW, dW;
+    FastDiv dRSP, dSP, dRSP4, dSP4;  // by R*SP, SP = 4*SP4, R*SP4, SP4
 };
 
 struct Variant;
