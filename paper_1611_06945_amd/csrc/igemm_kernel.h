@@ -177,7 +177,11 @@ __device__ __forceinline__ int acc_row(int v, int lane)
 // MODE_SVEC: gather whose reduction axis is (c, r, s padded to a multiple of 4): a thread fetches four consecutive
 // window columns of its pixel with one 16-byte load.  With stride 4 (the 11x11 first layers) the lanes of a wave then
 // read one contiguous kilobyte instead of 64 scattered words.  fp32 only.
-enum { MODE_GATHER = 0, MODE_POINTWISE = 1, MODE_SVEC = 2 };
+// MODE_TABLE: gather for layers without padding: the offset c*H*W + r*W + s of every reduction index is the same for
+// all pixels, so it is tabulated once per workgroup in LDS and a patch element costs one LDS read, one add and one
+// load -- no divisions, no window-position bookkeeping, no bounds tests in the loop (any stride, any storage type).
+enum { MODE_GATHER = 0, MODE_POINTWISE = 1, MODE_SVEC = 2, MODE_TABLE = 3 };
+constexpr int kTableMax = 4096;  // longest reduction axis the offset table holds
 
 // ---------------------------------------------------------------------------
 // compile-time geometry of one variant
@@ -230,6 +234,7 @@ __global__ __launch_bounds__(CFG::NT) void igemm_kernel(ConvArgs a)
 
     __shared__ __attribute__((aligned(16))) elem_t As[2][CFG::A_ELEMS];
     __shared__ __attribute__((aligned(16))) elem_t Bs[2][CFG::B_ELEMS];
+    __shared__ int q_off[(CFG::MODE == MODE_TABLE) ? kTableMax : 1];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
@@ -267,6 +272,16 @@ __global__ __launch_bounds__(CFG::NT) void igemm_kernel(ConvArgs a)
         } else {
             g_base = (int)n_img * a.C * a.HW + (int)rem;  // 1x1, stride 1, pad 0: pixel index == input index
         }
+    }
+
+    if constexpr (CFG::MODE == MODE_TABLE) {
+        for (int q = tid; q < a.Q; q += NT) {
+            uint32_t c, rs, r, sx;
+            a.dRS.divmod((uint32_t)q, c, rs);
+            a.dS.divmod(rs, r, sx);
+            q_off[q] = (int)c * a.HW + (int)r * a.W + (int)sx;
+        }
+        __syncthreads();
     }
 
     // ---- staging registers --------------------------------------------------------------------
@@ -309,7 +324,18 @@ __global__ __launch_bounds__(CFG::NT) void igemm_kernel(ConvArgs a)
             }
         }
         // patch tile
-        if constexpr (CFG::MODE == MODE_GATHER) {
+        if constexpr (CFG::MODE == MODE_TABLE) {
+#pragma unroll
+            for (int j = 0; j < NCH; ++j) {
+                const int q = q0 + (g_grp + j * GROUPS) * CHW;
+#pragma unroll
+                for (int e = 0; e < CHW; ++e) {
+                    const bool ok = g_pvalid && (q + e < a.Q);
+                    const int off = q_off[ok ? q + e : 0];
+                    b_reg[j][e] = buffer_load_elem<elem_t>(rin, ok ? (uint32_t)(g_base + off) * ES : kOutOfRange);
+                }
+            }
+        } else if constexpr (CFG::MODE == MODE_GATHER) {
 #pragma unroll
             for (int j = 0; j < NCH; ++j) {
                 const int q = q0 + (g_grp + j * GROUPS) * CHW;
@@ -578,6 +604,10 @@ bool igemm_valid(const Variant& v, const conv_desc& d, int OH, int OW)
     if (d.dtype != CFG::DT) return false;
     const long long Q = (long long)d.C * d.R * d.S, P = (long long)d.N * OH * OW;
     if (CFG::AVEC && (Q % CFG::VEC) != 0) return false;
+    if (CFG::MODE == MODE_TABLE) {
+        if (d.pad != 0 || Q > kTableMax) return false;
+        if (d.R == 1 && d.S == 1 && d.stride == 1) return false;  // the pointwise variants cover this
+    }
     if (CFG::MODE == MODE_SVEC) {
         if (d.S < 3) return false;  // nothing to vectorise
         if ((long long)d.C * d.R * ((d.S + 3) / 4 * 4) >= (1LL << 30)) return false;
