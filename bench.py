@@ -154,6 +154,66 @@ def cpu_baseline(w, budget_s=12.0):
             "sample": "%d full passes of %s (fp64 direct convolution, %.1f s)" % (n, w.name, dt)}
 
 
+def sweep_appendix_a(batch, dtype, table_out=None, launches=100, batches=5):
+    """The paper's whole benchmark set (Appendix A) through the autotuner: per operation the selected variant, its time
+    and rates, and the comparison the paper draws between per-operation tuning and one variant for everything."""
+    from paper_1611_06945_amd import binding as B
+    from paper_1611_06945_amd import workloads as wl
+
+    dt = wl.DTYPE_NAMES[dtype]
+    ops, per_variant = [], {}
+    for w in wl.appendix_a(batch, dtype):
+        r = Resident(w)
+        chosen = r.autotune()
+        n = B.conv_variant_count(r.desc)
+        times = {B.conv_variant_name(r.desc, i): B.conv_variant_time_us(r.desc, i) for i in range(n)}
+        med, mn = r.time_batches(launches, batches, warmup=20)
+        abytes = w.shape.algorithmic_bytes(w.dtype)
+        t_mfma = w.shape.flops / (PEAK_TFLOPS[dt] * 1e12)
+        t_hbm = abytes / (PEAK_HBM_GBS * 1e9)
+        ops.append({"op": w.name, "paper_row": w.paper_row, "flops": w.shape.flops, "algorithmic_bytes": abytes,
+                    "variant": chosen, "ms": round(med, 6), "ms_min": round(mn, 6),
+                    "tuner_us": round(times[chosen], 3),
+                    "gflops": round(w.shape.flops / (med * 1e-3) / 1e9, 1),
+                    "bound": "mfma" if t_mfma >= t_hbm else "hbm",
+                    "frac_roofline": round(max(t_mfma, t_hbm) / (med * 1e-3), 5),
+                    "n_variants": n})
+        for name, t in times.items():
+            per_variant.setdefault(name, {})[w.name] = t
+        log("%-46s %-40s %8.4f ms %9.1f GFLOP/s  roofline %.3f (%s)" % (
+            w.name, chosen, med, ops[-1]["gflops"], ops[-1]["frac_roofline"], ops[-1]["bound"]))
+        del r
+    # one variant for every operation: the variant valid on all of them with the smallest summed time
+    everywhere = {name: sum(t.values()) for name, t in per_variant.items() if len(t) == len(ops)}
+    single = min(everywhere, key=everywhere.get) if everywhere else None
+    for o in ops:
+        o["single_variant_us"] = round(per_variant[single][o["op"]], 3) if single else None
+        o["tuning_gain"] = round(o["single_variant_us"] / o["tuner_us"], 3) if single else None
+    tot_flops = sum(o["flops"] for o in ops)
+    tot_ms = sum(o["ms"] for o in ops)
+    summary = {
+        "workload": "appendix_a_n%d_%s" % (batch, dt), "ops": len(ops), "total_flops": tot_flops,
+        "total_ms": round(tot_ms, 5), "gflops": round(tot_flops / (tot_ms * 1e-3) / 1e9, 1),
+        "single_variant": single,
+        "single_variant_total_us": round(everywhere[single], 2) if single else None,
+        "autotuned_total_us": round(sum(o["tuner_us"] for o in ops), 2),
+        "variants_valid_everywhere": len(everywhere),
+    }
+    if table_out:
+        with open(table_out, "w") as fh:
+            fh.write("ms: per launch, Python loop through the C ABI, event-bracketed batches (median); tuner us: the same "
+                     "variant timed by the library's autotuner (C loop, device events); one-variant us: the single "
+                     "variant valid on every operation with the smallest total, timed the same way; gain = one-variant / tuner.\n\n")
+            fh.write("| # | operation (KSZ,S,OC, in -> out) | GFLOP | variant | ms | tuner us | GFLOP/s | bound | frac of roofline | one-variant us | gain |\n")
+            fh.write("|---|---|---|---|---|---|---|---|---|---|---|\n")
+            for i, o in enumerate(ops):
+                fh.write("| %d | %s | %.3f | %s | %.4f | %.2f | %.0f | %s | %.3f | %s | %s |\n" % (
+                    i, o["paper_row"], o["flops"] / 1e9, o["variant"], o["ms"], o["tuner_us"], o["gflops"], o["bound"],
+                    o["frac_roofline"], o["single_variant_us"], o["tuning_gain"]))
+            fh.write("\n" + json.dumps(summary) + "\n")
+    return summary, ops
+
+
 def stored_traffic(kernel_key):
     """HBM bytes per launch measured offline with rocprofv3 --pmc (see profiles/); None if not recorded."""
     path = os.path.join(ROOT, "profiles", "hbm_traffic.json")
@@ -173,6 +233,10 @@ def main():
     ap.add_argument("--workload", default="cfg4_mid3x3_n20_f32")
     ap.add_argument("--no-layers", action="store_true", help="skip the per-layer table")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--sweep", choices=["appendix_a"], help="time the paper's whole benchmark set instead of one workload")
+    ap.add_argument("--sweep-batch", type=int, default=5)
+    ap.add_argument("--sweep-dtype", choices=["f32", "f16", "bf16"], default="f32")
+    ap.add_argument("--table-out", help="with --sweep: also write the per-operation table (markdown) to this file")
     a = ap.parse_args()
     if a.gpus != 1:
         log("bench.py: this build runs on ONE GPU (the paper's method is single-device inference); --gpus %d is not "
@@ -190,6 +254,17 @@ def main():
     B.lib()  # fail loudly if the HIP library is not built
     torch.cuda.set_device(0)
     log("device:", torch.cuda.get_device_name(0))
+
+    if a.sweep:
+        code = {"f32": wl.F32, "f16": wl.F16, "bf16": wl.BF16}[a.sweep_dtype]
+        summary, ops = sweep_appendix_a(a.sweep_batch, code, a.table_out)
+        log("sweep:", summary)
+        print(json.dumps({
+            "metric": "conv_fwd_gflops", "value": summary["gflops"], "unit": "GFLOP/s", "n_gpus": 1,
+            "steps": len(ops), "warmup": 0, "ms_per_step": summary["total_ms"], "higher_is_better": True,
+            "scaling": "weak", "vs_baseline": None, "dtype": a.sweep_dtype, "data": "synthetic",
+            "config": {"workload": summary["workload"], "fused": "bias+relu"}, "sweep": summary, "ops": ops}), flush=True)
+        return
 
     table = {w.name: w for w in all_workloads()}
     if a.workload not in table:

@@ -210,6 +210,40 @@ def config5_layers(batch: int = 20, dtype: int = F16) -> List[Workload]:
     return out
 
 
+# The paper's benchmark set (Appendix A, "Benchmark Operations List"): every convolution of three ImageNet networks,
+# as (KSZ, stride, OC, in_y, in_x, in_chan, pad), sorted by FLOPs as printed there.  The table prints no padding;
+# `pad` is what the printed in -> out sizes imply under floor rounding.  Batch is a parameter (the paper uses 5).
+_APPENDIX_A = (
+    (5, 1, 32, 28, 28, 16, 2), (5, 1, 64, 14, 14, 32, 2), (1, 1, 256, 7, 7, 832, 0), (1, 1, 112, 14, 14, 512, 0),
+    (1, 1, 128, 14, 14, 512, 0), (1, 1, 64, 28, 28, 256, 0), (1, 1, 64, 56, 56, 64, 0), (1, 1, 128, 14, 14, 528, 0),
+    (1, 1, 144, 14, 14, 512, 0), (1, 1, 96, 28, 28, 192, 0), (1, 1, 384, 7, 7, 832, 0), (1, 1, 160, 14, 14, 512, 0),
+    (1, 1, 160, 14, 14, 528, 0), (1, 1, 4096, 1, 1, 4096, 0), (1, 1, 192, 14, 14, 480, 0), (5, 1, 128, 14, 14, 32, 2),
+    (3, 1, 320, 7, 7, 160, 1), (1, 1, 384, 13, 13, 384, 0), (1, 1, 128, 28, 28, 256, 0), (1, 1, 256, 14, 14, 528, 0),
+    (1, 1, 96, 54, 54, 96, 0), (3, 1, 384, 7, 7, 192, 1), (3, 1, 208, 14, 14, 96, 1), (1, 1, 1000, 6, 6, 1024, 0),
+    (1, 1, 1024, 6, 6, 1024, 0), (6, 1, 4096, 6, 6, 256, 0), (3, 1, 224, 14, 14, 112, 1), (1, 1, 256, 27, 27, 256, 0),
+    (3, 1, 256, 14, 14, 128, 1), (5, 1, 96, 28, 28, 32, 2), (3, 1, 288, 14, 14, 144, 1), (3, 1, 128, 28, 28, 96, 1),
+    (3, 1, 320, 14, 14, 160, 1), (11, 4, 96, 224, 224, 3, 0), (11, 4, 96, 227, 227, 3, 0), (7, 2, 64, 224, 224, 3, 3),
+    (3, 1, 1024, 6, 6, 384, 1), (3, 1, 256, 13, 13, 384, 1), (3, 1, 384, 13, 13, 256, 1), (3, 1, 192, 28, 28, 128, 1),
+    (3, 1, 384, 13, 13, 384, 1), (3, 1, 192, 56, 56, 64, 1), (5, 1, 256, 27, 27, 96, 2),
+)
+
+
+def appendix_a(batch: int = 5, dtype: int = F32) -> List[Workload]:
+    """All 43 operations of the paper's benchmark set at one batch size, in the table's order (by FLOPs).
+
+    Inputs: image-like U[-128,128] for the three-channel first layers, half-normal (post-ReLU activations) elsewhere;
+    He-scaled normal filters; seeds 6000 + 100*row + {0,1,2}.
+    """
+    out = []
+    for i, (ksz, st, oc, iy, ix, ic, pad) in enumerate(_APPENDIX_A):
+        sh = ConvShape(batch, ic, iy, ix, oc, ksz, ksz, st, pad)
+        in_dist = ("uniform", -128.0, 128.0) if ic == 3 else ("halfnormal", 1.0)
+        out.append(Workload("appA_%02d_k%ds%d_%dx%dx%d_oc%d_n%d_%s" % (i, ksz, st, iy, ix, ic, oc, batch, DTYPE_NAMES[dtype]),
+                            6, i, sh, dtype, in_dist, ("normal", he_sigma(sh)),
+                            paper_row="%d,%d,%d, %dx%dx%d -> %dx%dx%d" % (ksz, st, oc, iy, ix, ic, sh.OH, sh.OW, oc)))
+    return out
+
+
 STACK_POOL_AFTER = (1, 2)  # max-pool 3x3 stride 2 follows these layers of the stack
 
 

@@ -7,6 +7,7 @@ import re
 import pytest
 
 from paper_1611_06945_amd import binding as B
+from paper_1611_06945_amd import workloads as wl
 from paper_1611_06945_amd.workloads import config1, config2, config3, config4, config5_layers
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
@@ -191,3 +192,17 @@ def test_bad_cache_files_leave_the_cache_alone(tmp_path):
     with pytest.raises(B.ConvError) as e:
         B.conv_cache_save(str(tmp_path / "no_such_dir" / "x.txt"))
     assert e.value.status == B.CONV_EIO
+
+
+def test_appendix_a_workload_list_is_the_papers_table(appendix_a):
+    # the package's own copy of the benchmark set must be the table of Appendix A, row for row
+    ws = wl.appendix_a(5, wl.F32)
+    assert len(ws) == len(appendix_a) == 43
+    for r, w in zip(appendix_a, ws):
+        s = w.shape
+        assert (s.N, s.R, s.S, s.stride, s.K, s.H, s.W, s.C, s.pad) == (
+            r["b"], r["ksz"], r["ksz"], r["stride"], r["oc"], r["in_y"], r["in_x"], r["in_c"], r["pad"])
+        assert (s.OH, s.OW) == (r["out_y"], r["out_x"])
+        assert abs(s.flops - r["flops"]) <= 1e-5 * r["flops"]
+    assert len({w.name for w in ws}) == 43
+    assert len({w.seeds() for w in ws}) == 43
