@@ -45,6 +45,9 @@ State& state()
         register_igemm_f32(s->variants);
         register_igemm_f16(s->variants);
         register_igemm_bf16(s->variants);
+        register_ugemm_f32(s->variants);
+        register_ugemm_f16(s->variants);
+        register_ugemm_bf16(s->variants);
         register_wconv_f32(s->variants);
         register_wconv_f16(s->variants);
         register_wconv_bf16(s->variants);

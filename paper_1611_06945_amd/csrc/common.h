@@ -106,6 +106,9 @@ enum { FAM_IGEMM = 0, FAM_POINTWISE = 1, FAM_FIRSTLAYER = 2, FAM_WINDOW = 3 };
 void register_igemm_f32(std::vector<Variant>& out);
 void register_igemm_f16(std::vector<Variant>& out);
 void register_igemm_bf16(std::vector<Variant>& out);
+void register_ugemm_f32(std::vector<Variant>& out);
+void register_ugemm_f16(std::vector<Variant>& out);
+void register_ugemm_bf16(std::vector<Variant>& out);
 void register_wconv_f32(std::vector<Variant>& out);
 void register_wconv_f16(std::vector<Variant>& out);
 void register_wconv_bf16(std::vector<Variant>& out);

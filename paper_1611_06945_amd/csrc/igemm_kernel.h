@@ -221,6 +221,112 @@ struct IgemmCfg {
     static_assert(MODE != MODE_SVEC || (B_KMAJOR && !AVEC && (CHW % 4) == 0), "s-vector mode: fp32, element-wise filter loads");
 };
 
+// One reduction step of a wave: its BM x BN accumulator blocks advance by the TK reduction elements held in the LDS
+// tiles A ([row][k]) and B ([k][pixel] for fp32, [pixel][k] for 16-bit storage).  All operand fragments of the step are
+// requested from LDS first, so the LDS latency overlaps the MFMA chain.
+template <class CFG, class ACC>
+__device__ __forceinline__ void igemm_compute(const typename CFG::elem_t* __restrict__ A, const typename CFG::elem_t* __restrict__ B,
+                                              ACC (&acc)[CFG::BM][CFG::BN], int a_row0, int b_col0, int kg)
+{
+    constexpr int MB = CFG::MB, BM = CFG::BM, BN = CFG::BN, LDA = CFG::LDA, LDB = CFG::LDB, KPL = CFG::KPL, NMMA = CFG::NMMA;
+    typedef Mma<CFG::DT, MB> mma_t;
+    if constexpr (CFG::B_KMAJOR) {
+        f32x4 af[KPL / 4][BM];
+        float bf[KPL][BN];
+#pragma unroll
+        for (int ii = 0; ii < KPL / 4; ++ii)
+#pragma unroll
+            for (int bm = 0; bm < BM; ++bm) af[ii][bm] = *(const f32x4*)&A[a_row0 + bm * MB * LDA + ii * 4];
+#pragma unroll
+        for (int kk = 0; kk < KPL; ++kk)
+#pragma unroll
+            for (int bn = 0; bn < BN; ++bn) bf[kk][bn] = B[(kg * KPL + kk) * LDB + b_col0 + bn * MB];
+#pragma unroll
+        for (int kk = 0; kk < KPL; ++kk)
+#pragma unroll
+            for (int bm = 0; bm < BM; ++bm)
+#pragma unroll
+                for (int bn = 0; bn < BN; ++bn) acc[bm][bn] = mma_t::run(af[kk / 4][bm][kk % 4], bf[kk][bn], acc[bm][bn]);
+    } else {
+        uint4 af[NMMA][BM], bf[NMMA][BN];
+#pragma unroll
+        for (int i = 0; i < NMMA; ++i) {
+#pragma unroll
+            for (int bm = 0; bm < BM; ++bm) af[i][bm] = *(const uint4*)&A[a_row0 + bm * MB * LDA + i * 8];
+#pragma unroll
+            for (int bn = 0; bn < BN; ++bn) bf[i][bn] = *(const uint4*)&B[(b_col0 + bn * MB) * LDB + kg * KPL + i * 8];
+        }
+#pragma unroll
+        for (int i = 0; i < NMMA; ++i)
+#pragma unroll
+            for (int bm = 0; bm < BM; ++bm)
+#pragma unroll
+                for (int bn = 0; bn < BN; ++bn) acc[bm][bn] = mma_t::run(af[i][bm], bf[i][bn], acc[bm][bn]);
+    }
+}
+
+// Epilogue shared by the implicit-GEMM kernels: the accumulator blocks of one wave go out either as fp32 partial sums
+// of this reduction split ([split][K][P], finished by the fixed-order second pass) or, with bias and activation applied
+// and rounded once to the storage type, as the NKHW output (paper, Section 3 "Graph-level Optimizations").
+template <class CFG, class ACC>
+__device__ __forceinline__ void igemm_epilogue(const ConvArgs& a, ACC (&acc)[CFG::BM][CFG::BN], int p0, int m0, int wm, int wn,
+                                               int lane, int lrow)
+{
+    typedef typename CFG::elem_t elem_t;
+    constexpr int DT = CFG::DT, MB = CFG::MB, BM = CFG::BM, BN = CFG::BN;
+    constexpr int ACC_N = sizeof(ACC) / sizeof(float);
+    constexpr uint32_t ES = sizeof(elem_t);
+    // Pixel coordinates of this lane's accumulator columns.
+    int e_p[BN];
+    uint32_t e_img[BN], e_pix[BN];
+#pragma unroll
+    for (int bn = 0; bn < BN; ++bn) {
+        e_p[bn] = p0 + wn * BN * MB + bn * MB + lrow;
+        a.dOHW.divmod(e_p[bn] < a.P ? (uint32_t)e_p[bn] : 0u, e_img[bn], e_pix[bn]);
+    }
+    if (a.nsplit > 1) {
+        // partial sums of this split, [split][K][P] fp32; the fixed-order second pass applies bias and activation
+        const __amdgpu_buffer_rsrc_t rws = make_rsrc(a.ws + (size_t)blockIdx.z * a.K * a.P, (uint32_t)a.K * a.P * 4u);
+#pragma unroll
+        for (int bm = 0; bm < BM; ++bm)
+#pragma unroll
+            for (int v = 0; v < ACC_N; ++v) {
+                const int k = m0 + wm * BM * MB + bm * MB + acc_row<MB>(v, lane);
+#pragma unroll
+                for (int bn = 0; bn < BN; ++bn) {
+                    const bool ok = k < a.K && e_p[bn] < a.P;
+                    buffer_store_elem<float>(acc[bm][bn][v], rws, ok ? (uint32_t)(k * a.P + e_p[bn]) * 4u : kOutOfRange);
+                }
+            }
+    } else {
+        // bias of every accumulator row of this lane is fetched up front (a null bias reads as zeros)
+        const __amdgpu_buffer_rsrc_t rbias = make_rsrc(a.bias, a.bias ? (uint32_t)a.K * 4u : 0u);
+        float bias_r[BM][ACC_N];
+#pragma unroll
+        for (int bm = 0; bm < BM; ++bm)
+#pragma unroll
+            for (int v = 0; v < ACC_N; ++v) {
+                const int k = m0 + wm * BM * MB + bm * MB + acc_row<MB>(v, lane);
+                bias_r[bm][v] = buffer_load_elem<float>(rbias, (uint32_t)k * 4u);
+            }
+        const __amdgpu_buffer_rsrc_t rout = make_rsrc(a.out, a.out_bytes);
+#pragma unroll
+        for (int bm = 0; bm < BM; ++bm)
+#pragma unroll
+            for (int v = 0; v < ACC_N; ++v) {
+                const int k = m0 + wm * BM * MB + bm * MB + acc_row<MB>(v, lane);
+#pragma unroll
+                for (int bn = 0; bn < BN; ++bn) {
+                    float x = acc[bm][bn][v] + bias_r[bm][v];
+                    if (a.relu) x = x > 0.0f ? x : 0.0f;
+                    const bool ok = k < a.K && e_p[bn] < a.P;
+                    buffer_store_elem<elem_t>(Prec<DT>::from_f32(x), rout,
+                                              ok ? (uint32_t)((e_img[bn] * a.K + k) * a.OHW + e_pix[bn]) * ES : kOutOfRange);
+                }
+            }
+    }
+}
+
 template <class CFG>
 __global__ __launch_bounds__(CFG::NT) void igemm_kernel(ConvArgs a)
 {
@@ -475,46 +581,7 @@ __global__ __launch_bounds__(CFG::NT) void igemm_kernel(ConvArgs a)
     const int a_row0 = (wm * BM * MB + lrow) * LDA + kg * KPL;  // + bm*MB*LDA
     const int b_col0 = wn * BN * MB + lrow;                     // + bn*MB
 
-    auto compute = [&](int buf) {
-        const elem_t* __restrict__ A = As[buf];
-        const elem_t* __restrict__ B = Bs[buf];
-        if constexpr (CFG::B_KMAJOR) {
-            // all fragments of the step are requested first, so the LDS latency overlaps the MFMA chain
-            f32x4 af[KPL / 4][BM];
-            float bf[KPL][BN];
-#pragma unroll
-            for (int ii = 0; ii < KPL / 4; ++ii)
-#pragma unroll
-                for (int bm = 0; bm < BM; ++bm) af[ii][bm] = *(const f32x4*)&A[a_row0 + bm * MB * LDA + ii * 4];
-#pragma unroll
-            for (int kk = 0; kk < KPL; ++kk)
-#pragma unroll
-                for (int bn = 0; bn < BN; ++bn) bf[kk][bn] = B[(kg * KPL + kk) * LDB + b_col0 + bn * MB];
-#pragma unroll
-            for (int kk = 0; kk < KPL; ++kk)
-#pragma unroll
-                for (int bm = 0; bm < BM; ++bm)
-#pragma unroll
-                    for (int bn = 0; bn < BN; ++bn)
-                        acc[bm][bn] = mma_t::run(af[kk / 4][bm][kk % 4], bf[kk][bn], acc[bm][bn]);
-        } else {
-            uint4 af[NMMA][BM], bf[NMMA][BN];
-#pragma unroll
-            for (int i = 0; i < NMMA; ++i) {
-#pragma unroll
-                for (int bm = 0; bm < BM; ++bm) af[i][bm] = *(const uint4*)&A[a_row0 + bm * MB * LDA + i * 8];
-#pragma unroll
-                for (int bn = 0; bn < BN; ++bn)
-                    bf[i][bn] = *(const uint4*)&B[(b_col0 + bn * MB) * LDB + kg * KPL + i * 8];
-            }
-#pragma unroll
-            for (int i = 0; i < NMMA; ++i)
-#pragma unroll
-                for (int bm = 0; bm < BM; ++bm)
-#pragma unroll
-                    for (int bn = 0; bn < BN; ++bn) acc[bm][bn] = mma_t::run(af[i][bm], bf[i][bn], acc[bm][bn]);
-        }
-    };
+    auto compute = [&](int buf) { igemm_compute<CFG>(As[buf], Bs[buf], acc, a_row0, b_col0, kg); };
 
     // ---- main loop: registers prefetch step t+1 while MFMA consumes step t from LDS ----------
     if (step_begin < step_end) {
@@ -532,56 +599,7 @@ __global__ __launch_bounds__(CFG::NT) void igemm_kernel(ConvArgs a)
         }
     }
 
-    // ---- epilogue ---------------------------------------------------------------------------------
-    // Pixel coordinates of this lane's accumulator columns.
-    int e_p[BN];
-    uint32_t e_img[BN], e_pix[BN];
-#pragma unroll
-    for (int bn = 0; bn < BN; ++bn) {
-        e_p[bn] = p0 + wn * BN * MB + bn * MB + lrow;
-        a.dOHW.divmod(e_p[bn] < a.P ? (uint32_t)e_p[bn] : 0u, e_img[bn], e_pix[bn]);
-    }
-    if (a.nsplit > 1) {
-        // partial sums of this split, [split][K][P] fp32; the fixed-order second pass applies bias and activation
-        const __amdgpu_buffer_rsrc_t rws = make_rsrc(a.ws + (size_t)blockIdx.z * a.K * a.P, (uint32_t)a.K * a.P * 4u);
-#pragma unroll
-        for (int bm = 0; bm < BM; ++bm)
-#pragma unroll
-            for (int v = 0; v < ACC_N; ++v) {
-                const int k = m0 + wm * BM * MB + bm * MB + acc_row<MB>(v, lane);
-#pragma unroll
-                for (int bn = 0; bn < BN; ++bn) {
-                    const bool ok = k < a.K && e_p[bn] < a.P;
-                    buffer_store_elem<float>(acc[bm][bn][v], rws, ok ? (uint32_t)(k * a.P + e_p[bn]) * 4u : kOutOfRange);
-                }
-            }
-    } else {
-        // bias of every accumulator row of this lane is fetched up front (a null bias reads as zeros)
-        const __amdgpu_buffer_rsrc_t rbias = make_rsrc(a.bias, a.bias ? (uint32_t)a.K * 4u : 0u);
-        float bias_r[BM][ACC_N];
-#pragma unroll
-        for (int bm = 0; bm < BM; ++bm)
-#pragma unroll
-            for (int v = 0; v < ACC_N; ++v) {
-                const int k = m0 + wm * BM * MB + bm * MB + acc_row<MB>(v, lane);
-                bias_r[bm][v] = buffer_load_elem<float>(rbias, (uint32_t)k * 4u);
-            }
-        const __amdgpu_buffer_rsrc_t rout = make_rsrc(a.out, a.out_bytes);
-#pragma unroll
-        for (int bm = 0; bm < BM; ++bm)
-#pragma unroll
-            for (int v = 0; v < ACC_N; ++v) {
-                const int k = m0 + wm * BM * MB + bm * MB + acc_row<MB>(v, lane);
-#pragma unroll
-                for (int bn = 0; bn < BN; ++bn) {
-                    float x = acc[bm][bn][v] + bias_r[bm][v];
-                    if (a.relu) x = x > 0.0f ? x : 0.0f;
-                    const bool ok = k < a.K && e_p[bn] < a.P;
-                    buffer_store_elem<elem_t>(Prec<DT>::from_f32(x), rout,
-                                              ok ? (uint32_t)((e_img[bn] * a.K + k) * a.OHW + e_pix[bn]) * ES : kOutOfRange);
-                }
-            }
-    }
+    igemm_epilogue<CFG>(a, acc, p0, m0, wm, wn, lane, lrow);
 }
 
 // ---------------------------------------------------------------------------
