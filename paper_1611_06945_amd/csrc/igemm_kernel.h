@@ -265,6 +265,70 @@ __device__ __forceinline__ void igemm_compute(const typename CFG::elem_t* __rest
     }
 }
 
+// The same step in two halves, for kernels that keep the operand fragments of the next step in registers while the
+// matrix pipe still works on the current one: igemm_read_frags fetches every fragment of a step from LDS,
+// igemm_mma_range<U0, U1> issues the MFMAs of reduction units [U0, U1) of the step (a unit is one reduction element
+// per lane group for fp32, one 8-element packet for 16-bit storage; CFG-wide count: igemm_units<CFG>()).
+template <class CFG, bool KMAJOR = CFG::B_KMAJOR>
+struct IgemmFrags;
+template <class CFG>
+struct IgemmFrags<CFG, true> {
+    f32x4 a[CFG::KPL / 4][CFG::BM];
+    float b[CFG::KPL][CFG::BN];
+};
+template <class CFG>
+struct IgemmFrags<CFG, false> {
+    uint4 a[CFG::NMMA][CFG::BM], b[CFG::NMMA][CFG::BN];
+};
+template <class CFG>
+constexpr int igemm_units()
+{
+    return CFG::B_KMAJOR ? CFG::KPL : CFG::NMMA;
+}
+
+template <class CFG>
+__device__ __forceinline__ void igemm_read_frags(const typename CFG::elem_t* __restrict__ A, const typename CFG::elem_t* __restrict__ B,
+                                                 IgemmFrags<CFG>& f, int a_row0, int b_col0, int kg)
+{
+    constexpr int MB = CFG::MB, BM = CFG::BM, BN = CFG::BN, LDA = CFG::LDA, LDB = CFG::LDB, KPL = CFG::KPL, NMMA = CFG::NMMA;
+    if constexpr (CFG::B_KMAJOR) {
+#pragma unroll
+        for (int ii = 0; ii < KPL / 4; ++ii)
+#pragma unroll
+            for (int bm = 0; bm < BM; ++bm) f.a[ii][bm] = *(const f32x4*)&A[a_row0 + bm * MB * LDA + ii * 4];
+#pragma unroll
+        for (int kk = 0; kk < KPL; ++kk)
+#pragma unroll
+            for (int bn = 0; bn < BN; ++bn) f.b[kk][bn] = B[(kg * KPL + kk) * LDB + b_col0 + bn * MB];
+    } else {
+#pragma unroll
+        for (int i = 0; i < NMMA; ++i) {
+#pragma unroll
+            for (int bm = 0; bm < BM; ++bm) f.a[i][bm] = *(const uint4*)&A[a_row0 + bm * MB * LDA + i * 8];
+#pragma unroll
+            for (int bn = 0; bn < BN; ++bn) f.b[i][bn] = *(const uint4*)&B[(b_col0 + bn * MB) * LDB + kg * KPL + i * 8];
+        }
+    }
+}
+
+template <class CFG, int U0, int U1, class ACC>
+__device__ __forceinline__ void igemm_mma_range(const IgemmFrags<CFG>& f, ACC (&acc)[CFG::BM][CFG::BN])
+{
+    constexpr int BM = CFG::BM, BN = CFG::BN;
+    typedef Mma<CFG::DT, CFG::MB> mma_t;
+#pragma unroll
+    for (int u = U0; u < U1; ++u)
+#pragma unroll
+        for (int bm = 0; bm < BM; ++bm)
+#pragma unroll
+            for (int bn = 0; bn < BN; ++bn) {
+                if constexpr (CFG::B_KMAJOR)
+                    acc[bm][bn] = mma_t::run(f.a[u / 4][bm][u % 4], f.b[u][bn], acc[bm][bn]);
+                else
+                    acc[bm][bn] = mma_t::run(f.a[u][bm], f.b[u][bn], acc[bm][bn]);
+            }
+}
+
 // Epilogue shared by the implicit-GEMM kernels: the accumulator blocks of one wave go out either as fp32 partial sums
 // of this reduction split ([split][K][P], finished by the fixed-order second pass) or, with bias and activation applied
 // and rounded once to the storage type, as the NKHW output (paper, Section 3 "Graph-level Optimizations").

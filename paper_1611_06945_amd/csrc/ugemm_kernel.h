@@ -42,7 +42,7 @@ __global__ __launch_bounds__(CFG::NT) void ugemm_kernel(ConvArgs a)
     constexpr uint32_t ES = sizeof(elem_t);
     static_assert(TN % 64 == 0, "the reduction indices a thread gathers must be the same for its whole wave");
     static_assert(NT % TK == 0 && NT % (TK / VEC) == 0, "filter tile rows advance by a constant per load");
-    static_assert(!SV || (CFG::B_KMAJOR && CFG::AVEC && PADMODE == PAD_NONE && (CHW % 4) == 0),
+    static_assert(!SV || (CFG::B_KMAJOR && CFG::AVEC && PADMODE == PAD_NONE && (CHW % 4) == 0 && NCH * CHW <= 32),
                   "s-vector gather: fp32, 16-byte filter loads, no padding");
 
     __shared__ __attribute__((aligned(16))) elem_t As[2][CFG::A_ELEMS];
@@ -113,6 +113,8 @@ __global__ __launch_bounds__(CFG::NT) void ugemm_kernel(ConvArgs a)
 
     // s-vector layout: this thread's filter column q' = q0 + a_col as (c, r, s') of the padded axis, advanced step by step
     int sv_c = 0, sv_r = 0, sv_s = 0;
+    int sv_left = 4;           // of the filter vectors in flight: how many leading columns are window columns
+    uint32_t sv_keep = ~0u;    // of the patch elements in flight (uniform): bit j*CHW+e set when the column is a window column
     if constexpr (SV) {
         uint32_t c, rem, r, sp;
         a.dRSP.divmod((uint32_t)(step_begin * TK + a_col), c, rem);
@@ -131,14 +133,11 @@ __global__ __launch_bounds__(CFG::NT) void ugemm_kernel(ConvArgs a)
             // columns (c, r, s'..s'+3) of the padded axis are filter elements (c, r, s'..s'+3) where s' + e < S, else zero
             const bool col_ok = sv_c < a.C;
             const uint32_t foff = (uint32_t)(sv_c * a.RS + sv_r * a.S + sv_s - a_col) * ES;  // a_voff already holds a_col
-            const int left = a.S - sv_s;  // >= 1
+            sv_left = a.S - sv_s;  // window columns the vector really holds; the rest is cleared when it goes to LDS
 #pragma unroll
             for (int i = 0; i < A_LOADS; ++i) {
                 const uint32_t vo = col_ok ? a_voff[i] + foff : kFarOffset;
-                u32x4 t = __builtin_amdgcn_raw_buffer_load_b128(rfilt, (int)vo, 0, 0);
-                if (left < 2) t.y = 0u;
-                if (left < 3) t.z = 0u;
-                if (left < 4) t.w = 0u;
+                const u32x4 t = __builtin_amdgcn_raw_buffer_load_b128(rfilt, (int)vo, 0, 0);
                 a_vec[i] = make_uint4(t.x, t.y, t.z, t.w);
             }
             // advance by one step (TK columns) for the next call; steps are visited in order
@@ -189,6 +188,7 @@ __global__ __launch_bounds__(CFG::NT) void ugemm_kernel(ConvArgs a)
         }
         // patch tile: the reduction indices are uniform, so (c, r, s) and the offset live on the scalar unit
         if constexpr (SV) {
+            uint32_t keep = 0u;
 #pragma unroll
             for (int j = 0; j < NCH; ++j) {
                 const int q = q0 + (u_grp + j * GROUPS) * CHW;  // a multiple of 4 in the padded axis
@@ -200,13 +200,15 @@ __global__ __launch_bounds__(CFG::NT) void ugemm_kernel(ConvArgs a)
                 for (int v4 = 0; v4 < CHW / 4; ++v4) {
                     const int s0 = svi * 4;
                     const uint32_t soff = ci < a.C ? (uint32_t)(ci * a.HW + ri * a.W + s0) * ES : kFarScalar;
-                    // four window columns at once; columns past the window are real neighbours or read as zero past the
-                    // end of the tensor, and are cleared here (their filter column is zero as well)
+                    // four window columns at once; columns past the window are real neighbours (or read as zero past the
+                    // end of the tensor) and are cleared when the tile goes to LDS -- not here, which would wait for the load
                     const u32x4 t = __builtin_amdgcn_raw_buffer_load_b128(rin, (int)b_voff, (int)soff, 0);
                     const uint32_t w4[4] = {t.x, t.y, t.z, t.w};
 #pragma unroll
-                    for (int e = 0; e < 4; ++e)
-                        b_reg[j][v4 * 4 + e] = (s0 + e < a.S) ? __builtin_bit_cast(elem_t, w4[e]) : (elem_t)0;
+                    for (int e = 0; e < 4; ++e) {
+                        b_reg[j][v4 * 4 + e] = __builtin_bit_cast(elem_t, w4[e]);
+                        if (s0 + e < a.S) keep |= 1u << (j * CHW + v4 * 4 + e);
+                    }
                     if (++svi == a.SP4) {
                         svi = 0;
                         if (++ri == a.R) {
@@ -216,6 +218,7 @@ __global__ __launch_bounds__(CFG::NT) void ugemm_kernel(ConvArgs a)
                     }
                 }
             }
+            sv_keep = keep;
         } else
 #pragma unroll
         for (int j = 0; j < NCH; ++j) {
@@ -261,6 +264,11 @@ __global__ __launch_bounds__(CFG::NT) void ugemm_kernel(ConvArgs a)
         for (int i = 0; i < A_LOADS; ++i) {
             const bool in_tile = (a_row0 + i * A_ROWSTEP) < TM;  // false only for the last load of a ragged plan
             if constexpr (CFG::AVEC) {
+                if constexpr (SV) {
+                    if (sv_left < 2) a_vec[i].y = 0u;
+                    if (sv_left < 3) a_vec[i].z = 0u;
+                    if (sv_left < 4) a_vec[i].w = 0u;
+                }
                 if (in_tile) *(uint4*)&As[buf][a_lds0 + i * A_ROWSTEP * LDA] = a_vec[i];
             } else {
                 if (in_tile) As[buf][a_lds0 + i * A_ROWSTEP * LDA] = a_sc[i];
@@ -270,7 +278,11 @@ __global__ __launch_bounds__(CFG::NT) void ugemm_kernel(ConvArgs a)
         for (int j = 0; j < NCH; ++j) {
             if constexpr (CFG::B_KMAJOR) {
 #pragma unroll
-                for (int e = 0; e < CHW; ++e) Bs[buf][b_lds0 + (j * GROUPS * CHW + e) * LDB] = b_reg[j][e];
+                for (int e = 0; e < CHW; ++e) {
+                    elem_t x = b_reg[j][e];
+                    if constexpr (SV) x = ((sv_keep >> (j * CHW + e)) & 1u) ? x : (elem_t)0;
+                    Bs[buf][b_lds0 + (j * GROUPS * CHW + e) * LDB] = x;
+                }
             } else {
                 uint4 pk;
                 pk.x = (uint32_t)b_reg[j][0] | ((uint32_t)b_reg[j][1] << 16);
@@ -293,23 +305,35 @@ __global__ __launch_bounds__(CFG::NT) void ugemm_kernel(ConvArgs a)
     const int fa_row0 = (wm * BM * MB + lrow) * LDA + kg * KPL;
     const int fb_col0 = wn * BN * MB + lrow;
 
-    // one step on LDS buffer `buf`: registers prefetch the next step while MFMA consumes this one
-    auto body = [&](auto bufc, int step) {
+    // Main loop.  A wave holds the operand fragments of step t in registers (fc); the tiles of step t+1 wait in the
+    // staging registers.  It issues most MFMAs of step t, writes the staged tiles to the other LDS buffer, passes the
+    // barrier, fetches the fragments of step t+1 (fn) and starts the global loads of step t+2 -- and only then issues
+    // the last MFMAs of step t, which need nothing but registers: they cover the LDS latency and the barrier skew, so
+    // the matrix pipe does not idle at the step boundary.
+    constexpr int NU = igemm_units<CFG>();
+    constexpr int TAILU = NU >= 4 ? NU / 4 : 1;
+    auto body = [&](auto bufc, int step, IgemmFrags<CFG>& fc, IgemmFrags<CFG>& fn) {
         constexpr int buf = decltype(bufc)::value;
         const bool more = step + 1 < step_end;
-        if (more) load_tiles(step + 1);
-        igemm_compute<CFG>(As[buf], Bs[buf], acc, fa_row0, fb_col0, kg);
+        igemm_mma_range<CFG, 0, NU - TAILU>(fc, acc);
         if (more) store_tiles(std::integral_constant<int, buf ^ 1>{});
         __syncthreads();
+        if (more) igemm_read_frags<CFG>(As[buf ^ 1], Bs[buf ^ 1], fn, fa_row0, fb_col0, kg);
+        if (step + 2 < step_end) load_tiles(step + 2);
+        __builtin_amdgcn_sched_barrier(0);  // keep the register-only MFMAs below behind the requests above
+        igemm_mma_range<CFG, NU - TAILU, NU>(fc, acc);
     };
 
     if (step_begin < step_end) {
+        IgemmFrags<CFG> f0, f1;
         load_tiles(step_begin);
         store_tiles(std::integral_constant<int, 0>{});
         __syncthreads();
+        igemm_read_frags<CFG>(As[0], Bs[0], f0, fa_row0, fb_col0, kg);
+        if (step_begin + 1 < step_end) load_tiles(step_begin + 1);
         for (int step = step_begin; step < step_end; step += 2) {
-            body(std::integral_constant<int, 0>{}, step);
-            if (step + 1 < step_end) body(std::integral_constant<int, 1>{}, step + 1);
+            body(std::integral_constant<int, 0>{}, step, f0, f1);
+            if (step + 1 < step_end) body(std::integral_constant<int, 1>{}, step + 1, f1, f0);
         }
     }
 
