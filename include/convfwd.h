@@ -131,6 +131,16 @@ int conv_force_variant(const conv_desc* desc, int idx);
 double conv_variant_time_us(const conv_desc* desc, int idx);
 
 /*
+ * Device-side time of the currently selected variant (the one conv_fwd_ws would run with this workspace): `launches`
+ * back-to-back launches on `stream`, bracketed by two events; *us_per_launch = elapsed / launches.  This is the paper's
+ * measurement rule (Section 4, "Experimental Results": device timers around the calls, host overheads excluded), used
+ * by the benchmark for layers whose run time is of the order of a host-side launch.  Synchronises the stream.
+ * Pointers, alignment and errors as conv_fwd_ws; launches >= 1 and us_per_launch != NULL, else CONV_EINVAL.
+ */
+int conv_time_us(const conv_desc* desc, const void* in, const void* filt, const float* bias, void* out, void* workspace,
+                 size_t workspace_bytes, void* stream, int launches, double* us_per_launch);
+
+/*
  * Autotune cache persistence: a text file, one line per descriptor
  * ("N C H W K R S stride pad dtype flags | best-name | best-no-workspace-name").
  * Load merges into the in-process cache and ignores lines naming unknown

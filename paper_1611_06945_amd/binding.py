@@ -47,6 +47,12 @@ def lib() -> ctypes.CDLL:
     if _lib is None:
         if not os.path.exists(LIB_PATH):
             raise OSError("%s not found: build it with `python -m paper_1611_06945_amd.build`" % LIB_PATH)
+        # The library and PyTorch must share ONE HIP runtime in the process (the tensors it is handed live in PyTorch's
+        # context).  PyTorch ships its own copy of the runtime; loading it first makes the dynamic loader resolve the
+        # library's dependency to that copy.  Loaded the other way round, two runtimes end up in the process and the
+        # second one finds no device.
+        import torch  # noqa: F401
+
         L = ctypes.CDLL(LIB_PATH)
         dp = ctypes.POINTER(conv_desc)
         vp, i32p = ctypes.c_void_p, ctypes.POINTER(ctypes.c_int32)
@@ -72,6 +78,8 @@ def lib() -> ctypes.CDLL:
         L.conv_force_variant.restype = ctypes.c_int
         L.conv_variant_time_us.argtypes = [dp, ctypes.c_int]
         L.conv_variant_time_us.restype = ctypes.c_double
+        L.conv_time_us.argtypes = [dp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp, ctypes.c_int, ctypes.POINTER(ctypes.c_double)]
+        L.conv_time_us.restype = ctypes.c_int
         L.conv_cache_load.argtypes = [ctypes.c_char_p]
         L.conv_cache_load.restype = ctypes.c_int
         L.conv_cache_save.argtypes = [ctypes.c_char_p]
@@ -164,6 +172,13 @@ def conv_fwd_ws(desc, inp, filt, bias, out, workspace, workspace_bytes, stream=N
 def conv_autotune(desc, inp, filt, bias, out, workspace=None, workspace_bytes=0, stream=None) -> None:
     _check(lib().conv_autotune(ctypes.byref(desc), _ptr(inp), _ptr(filt), _ptr(bias), _ptr(out), _ptr(workspace),
                                int(workspace_bytes), _stream(stream)), "conv_autotune")
+
+
+def conv_time_us(desc, inp, filt, bias, out, workspace=None, workspace_bytes=0, stream=None, launches=100) -> float:
+    us = ctypes.c_double(0.0)
+    _check(lib().conv_time_us(ctypes.byref(desc), _ptr(inp), _ptr(filt), _ptr(bias), _ptr(out), _ptr(workspace),
+                              int(workspace_bytes), _stream(stream), int(launches), ctypes.byref(us)), "conv_time_us")
+    return float(us.value)
 
 
 def conv_variant_count(desc) -> int:

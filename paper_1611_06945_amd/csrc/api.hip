@@ -289,6 +289,44 @@ int conv_fwd_ws(const conv_desc* desc, const void* in, const void* filt, const f
     return fwd_common(desc, in, filt, bias, out, workspace, workspace_bytes, stream);
 }
 
+int conv_time_us(const conv_desc* desc, const void* in, const void* filt, const float* bias, void* out, void* workspace,
+                 size_t workspace_bytes, void* stream, int launches, double* us_per_launch)
+{
+    if (launches < 1 || !us_per_launch) return CONV_EINVAL;
+    // one untimed call first: it validates everything and takes any one-time cost (function attributes) out of the timing
+    int rc = fwd_common(desc, in, filt, bias, out, workspace, workspace_bytes, stream);
+    if (rc) return rc;
+    hipStream_t s = (hipStream_t)stream;
+    hipEvent_t e0, e1;
+    hipError_t e = hipEventCreate(&e0);
+    if (e != hipSuccess) return hip_fail(e, "hipEventCreate");
+    e = hipEventCreate(&e1);
+    if (e != hipSuccess) {
+        hipEventDestroy(e0);
+        return hip_fail(e, "hipEventCreate");
+    }
+    e = hipEventRecord(e0, s);
+    if (e != hipSuccess) rc = hip_fail(e, "hipEventRecord");
+    for (int i = 0; i < launches && rc == CONV_OK; ++i) rc = fwd_common(desc, in, filt, bias, out, workspace, workspace_bytes, stream);
+    if (rc == CONV_OK) {
+        e = hipEventRecord(e1, s);
+        if (e != hipSuccess) rc = hip_fail(e, "hipEventRecord");
+    }
+    if (rc == CONV_OK) {
+        e = hipEventSynchronize(e1);
+        if (e != hipSuccess) rc = hip_fail(e, "hipEventSynchronize");
+    }
+    float ms = 0.f;
+    if (rc == CONV_OK) {
+        e = hipEventElapsedTime(&ms, e0, e1);
+        if (e != hipSuccess) rc = hip_fail(e, "hipEventElapsedTime");
+    }
+    hipEventDestroy(e0);
+    hipEventDestroy(e1);
+    if (rc == CONV_OK) *us_per_launch = (double)ms * 1000.0 / launches;
+    return rc;
+}
+
 int conv_autotune(const conv_desc* desc, const void* in, const void* filt, const float* bias, void* out, void* workspace,
                   size_t workspace_bytes, void* stream)
 {

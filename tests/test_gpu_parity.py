@@ -193,3 +193,13 @@ def test_autotune_records_times_and_selects_the_fastest():
     assert case.error(case.run()) <= TOL[wl.F32]
     assert case.error(case.run(with_ws=False)) <= TOL[wl.F32]
     B.conv_cache_clear()
+
+
+def test_device_side_timing_entry_point():
+    case = random_case(ConvShape(2, 20, 12, 12, 200, 3, 3, 1, 1), wl.F32, 81)
+    out = empty_out(case.shape.out_shape(), wl.F32)
+    ws = case.workspace()
+    us = B.conv_time_us(case.desc, case.d_in, case.d_filt, case.d_bias, out, ws, ws.numel(), launches=20)
+    assert 0.5 < us < 1e4, us
+    torch_mod().cuda.synchronize()
+    assert case.error(out) <= TOL[wl.F32]  # the timed launches compute the real thing

@@ -87,6 +87,10 @@ def test_null_and_misaligned_pointers_are_rejected_before_any_gpu_call():
     assert L.conv_fwd(ctypes.byref(d), 260, 512, None, 1024, None) == B.CONV_EINVAL  # not 16-byte aligned
     assert L.conv_fwd(None, 256, 512, None, 1024, None) == B.CONV_EINVAL
     assert L.conv_autotune(ctypes.byref(d), None, 256, None, 512, None, 0, None) == B.CONV_EINVAL
+    us = ctypes.c_double(0.0)
+    assert L.conv_time_us(ctypes.byref(d), 256, 512, None, 1024, None, 0, None, 0, ctypes.byref(us)) == B.CONV_EINVAL
+    assert L.conv_time_us(ctypes.byref(d), 256, 512, None, 1024, None, 0, None, 10, None) == B.CONV_EINVAL
+    assert L.conv_time_us(ctypes.byref(d), None, 512, None, 1024, None, 0, None, 10, ctypes.byref(us)) == B.CONV_EINVAL
     assert L.maxpool_fwd(1, 1, 2, 2, 3, 2, 0, 256, 512, None) == B.CONV_EINVAL  # window larger than input
     assert L.maxpool_fwd(1, 1, 5, 5, 3, 2, 9, 256, 512, None) == B.CONV_EDTYPE
     assert L.maxpool_fwd(1, 1, 5, 5, 3, 2, 0, None, 512, None) == B.CONV_EINVAL
