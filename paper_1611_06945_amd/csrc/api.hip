@@ -48,6 +48,7 @@ State& state()
         register_ugemm_f32(s->variants);
         register_ugemm_f16(s->variants);
         register_ugemm_bf16(s->variants);
+        register_fc(s->variants);
         register_wconv_f32(s->variants);
         register_wconv_f16(s->variants);
         register_wconv_bf16(s->variants);
@@ -121,6 +122,7 @@ size_t ws_bytes_of(const Variant& v, const conv_desc& d, int OH, int OW)
 double heuristic_cost(const Variant& v, const conv_desc& d, int OH, int OW)
 {
     const double P = (double)d.N * OH * OW, Q = (double)d.C * d.R * d.S;
+    if (v.family == FAM_FC) return 1.0 + std::abs(v.tm - 4);  // weight streaming: always ahead of the MFMA tiles when valid
     const double tiles = std::ceil(d.K / (double)v.tm) * std::ceil(P / (double)v.tn) * v.split;
     const double steps = std::ceil(std::ceil(Q / v.tk) / v.split);
     const double wg_per_cu = (v.tm * v.tn >= 128 * 128) ? 1.0 : (v.tm * v.tn >= 64 * 128) ? 2.0 : 3.0;

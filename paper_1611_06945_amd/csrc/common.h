@@ -100,7 +100,7 @@ struct Variant {
     LaunchFn launch;
 };
 
-enum { FAM_IGEMM = 0, FAM_POINTWISE = 1, FAM_FIRSTLAYER = 2, FAM_WINDOW = 3 };
+enum { FAM_IGEMM = 0, FAM_POINTWISE = 1, FAM_FIRSTLAYER = 2, FAM_WINDOW = 3, FAM_FC = 4 };
 
 // Each kernel file appends its variants.
 void register_igemm_f32(std::vector<Variant>& out);
@@ -109,6 +109,7 @@ void register_igemm_bf16(std::vector<Variant>& out);
 void register_ugemm_f32(std::vector<Variant>& out);
 void register_ugemm_f16(std::vector<Variant>& out);
 void register_ugemm_bf16(std::vector<Variant>& out);
+void register_fc(std::vector<Variant>& out);
 void register_wconv_f32(std::vector<Variant>& out);
 void register_wconv_f16(std::vector<Variant>& out);
 void register_wconv_bf16(std::vector<Variant>& out);

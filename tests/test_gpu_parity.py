@@ -61,6 +61,9 @@ SMALL_SHAPES = [
     ConvShape(1, 32, 10, 11, 20, 3, 3, 1, 2),   # window-reuse kernel, pad 2 (12x13 outputs)
     ConvShape(2, 32, 27, 27, 40, 5, 5, 1, 2),   # 16-bit window kernel, 5x5: four bands of rows per image, last one partial
     ConvShape(1, 64, 20, 20, 33, 3, 3, 1, 1),   # 16-bit window kernel, 3x3: bands of 9, 9 and 2 rows
+    ConvShape(5, 16, 6, 6, 70, 6, 6, 1, 0),     # fully connected (window = image), 5 images, K ragged against the row blocks
+    ConvShape(3, 1032, 1, 1, 33, 1, 1, 1, 0),   # fully connected 1x1 on 1x1: 258 / 129 vectors against 256 threads
+    ConvShape(8, 24, 2, 2, 10, 2, 2, 1, 0),     # fully connected, 8 images
 ]
 
 
