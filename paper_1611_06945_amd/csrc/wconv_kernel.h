@@ -48,8 +48,11 @@ __host__ __device__ inline int wconv_plane(int H, int W, int pad)
     return plane + ((16 - plane % 64) + 64) % 64;
 }
 
+// Variants with one 16-row block per wave are meant to run two workgroups per CU (four waves per SIMD when the
+// workgroup has 512 threads): the waves-per-SIMD attribute keeps the register allocation within that budget.
 template <class CFG>
-__global__ __launch_bounds__(CFG::NT) void wconv_kernel(ConvArgs a)
+__global__ __launch_bounds__(CFG::NT) __attribute__((amdgpu_waves_per_eu(CFG::TMB == 1 ? CFG::NT / 128 : 1)))
+void wconv_kernel(ConvArgs a)
 {
     constexpr int R = CFG::R, S = CFG::S, RS = R * S, CPL = CFG::CPL, TMB = CFG::TMB, NB = CFG::NB, CB = CFG::CB;
     constexpr int TM = CFG::TM, TNP = CFG::TNP, KCH = CFG::KCH, LDA = CFG::LDA, NT = CFG::NT, LB = CFG::LB, NBW = CFG::NBW;
@@ -76,25 +79,7 @@ __global__ __launch_bounds__(CFG::NT) void wconv_kernel(ConvArgs a)
     const __amdgpu_buffer_rsrc_t rin = make_rsrc(a.in, a.in_bytes);
     const __amdgpu_buffer_rsrc_t rfilt = make_rsrc(a.filt, a.filt_bytes);
 
-    // zero both image slabs once: the border stays zero, the interior is overwritten by every chunk
-    for (int i = tid; i < 2 * b_elems; i += NT) Bs0[i] = 0.0f;
-
     const int nvecB = (CB * a.HW) >> 2;  // 16-byte vectors of one image slab in global memory
-
-    // Where each element this thread moves lands in the padded LDS slab.  The same for every chunk, so the
-    // divisions are done once here and the main loop only adds the buffer base (-1: nothing to move).
-    int b_idx[LB][4];
-#pragma unroll
-    for (int i = 0; i < LB; ++i) {
-        const int v = i * NT + tid;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            uint32_t cl, pix, y, x;
-            a.dHW.divmod((uint32_t)(4 * v + e), cl, pix);
-            a.dW.divmod(pix, y, x);
-            b_idx[i][e] = v < nvecB ? (int)cl * PLANE + ((int)y + a.pad) * PW + (int)x + a.pad : -1;
-        }
-    }
 
     uint4 a_reg[planA.loads];
     uint4 b_reg[LB];
@@ -117,9 +102,30 @@ __global__ __launch_bounds__(CFG::NT) void wconv_kernel(ConvArgs a)
         }
     };
 
+    // the first chunk's loads go out before anything else: their latency is covered by the set-up work below
+    if (chunk_begin < chunk_end) load_chunk(chunk_begin);
+
+    // zero both image slabs once: the border stays zero, the interior is overwritten by every chunk
+    for (int i = tid; i < 2 * b_elems; i += NT) Bs0[i] = 0.0f;
+
+    // Where each element this thread moves lands in the padded LDS slab.  The same for every chunk, so the
+    // divisions are done once here and the main loop only adds the buffer base (-1: nothing to move).
+    int b_idx[LB][4];
+#pragma unroll
+    for (int i = 0; i < LB; ++i) {
+        const int v = i * NT + tid;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            uint32_t cl, pix, y, x;
+            a.dHW.divmod((uint32_t)(4 * v + e), cl, pix);
+            a.dW.divmod(pix, y, x);
+            b_idx[i][e] = v < nvecB ? (int)cl * PLANE + ((int)y + a.pad) * PW + (int)x + a.pad : -1;
+        }
+    }
+
     auto store_chunk = [&](int buf) {
         float* As = As0 + buf * TM * LDA;
-        float* Bs = Bs0 + buf * b_elems;
+        float* Bs = Bs0 + buf * b_elems;  // buf is a constant at every call site: LDS addresses are base + immediate
 #pragma unroll
         for (int i = 0; i < planA.loads; ++i) {
             const int v = i * NT + tid;
@@ -188,23 +194,27 @@ __global__ __launch_bounds__(CFG::NT) void wconv_kernel(ConvArgs a)
     typedef std::integral_constant<int, TSPLIT> tap_mid;
     typedef std::integral_constant<int, TAPS> tap_last;
 
+    // One chunk on LDS buffer `buf` (a compile-time constant: the loop below is unrolled by two, so every LDS address
+    // is a per-thread base plus an immediate and no vector instruction is spent on buffer switching -- on this device
+    // vector-ALU instructions and fp32 MFMAs of a SIMD never overlap).  The other LDS buffer was last read before the
+    // barrier that ended the previous chunk, so the next chunk is written into it in the middle of this chunk's MFMA
+    // chain: the LDS writes then overlap the matrix pipe instead of following it.
+    auto body = [&](auto bufc, int chunk) {
+        constexpr int buf = decltype(bufc)::value;
+        const bool more = chunk + 1 < chunk_end;
+        if (more) load_chunk(chunk + 1);
+        compute(buf, tap_first{}, tap_mid{});
+        if (more) store_chunk(buf ^ 1);
+        compute(buf, tap_mid{}, tap_last{});
+        __syncthreads();
+    };
     if (chunk_begin < chunk_end) {
-        load_chunk(chunk_begin);
         __syncthreads();  // zero fill done before the first interior write
         store_chunk(0);
         __syncthreads();
-        int buf = 0;
-        for (int chunk = chunk_begin; chunk < chunk_end; ++chunk) {
-            const bool more = chunk + 1 < chunk_end;
-            // The other LDS buffer was last read before the barrier that ended the previous iteration, so the next
-            // chunk can be written into it in the middle of this chunk's MFMA chain: the LDS writes then overlap the
-            // matrix pipe instead of following it.
-            if (more) load_chunk(chunk + 1);
-            compute(buf, tap_first{}, tap_mid{});
-            if (more) store_chunk(buf ^ 1);
-            compute(buf, tap_mid{}, tap_last{});
-            __syncthreads();
-            buf ^= 1;
+        for (int chunk = chunk_begin; chunk < chunk_end; chunk += 2) {
+            body(std::integral_constant<int, 0>{}, chunk);
+            if (chunk + 1 < chunk_end) body(std::integral_constant<int, 1>{}, chunk + 1);
         }
     } else {
         __syncthreads();
@@ -225,21 +235,28 @@ __global__ __launch_bounds__(CFG::NT) void wconv_kernel(ConvArgs a)
                 for (int v = 0; v < 4; ++v) red[(w * 16 + 4 * g + v) * TNP + (nb0 + nb) * 16 + li] = acc[mb][nb][v];
             }
         __syncthreads();
+        constexpr int NE = (16 * TNP + NT - 1) / NT;  // outputs of this 16-row block per thread
+        float bs[NE];
 #pragma unroll
-        for (int j = 0; j < (16 * TNP + NT - 1) / NT; ++j) {
+        for (int j = 0; j < NE; ++j) {  // all bias values first: one round trip instead of one per output
             const int e = j * NT + tid;
-            if ((16 * TNP) % NT != 0 && e >= 16 * TNP) break;
-            const int row = e / TNP, col = e % TNP;
+            bs[j] = buffer_load_elem<float>(rbias, (e < 16 * TNP && !split) ? (uint32_t)(m0 + mb * 16 + e / TNP) * 4u : kOutOfRange);
+        }
+#pragma unroll
+        for (int j = 0; j < NE; ++j) {
+            const int e = j * NT + tid;
+            const int idx = e < 16 * TNP ? e : 0;
+            const int row = idx / TNP, col = idx % TNP;
             float x = red[row * TNP + col];
             x += red[(16 + row) * TNP + col];
             x += red[(32 + row) * TNP + col];
             x += red[(48 + row) * TNP + col];
             const int k = m0 + mb * 16 + row, n = n0 + col;
-            const bool ok = k < a.K && n < a.OHW;
+            const bool ok = e < 16 * TNP && k < a.K && n < a.OHW;
             if (split) {
                 buffer_store_elem<float>(x, rws, ok ? (uint32_t)(k * a.P + img * a.OHW + n) * 4u : kOutOfRange);
             } else {
-                x += buffer_load_elem<float>(rbias, (uint32_t)k * 4u);
+                x += bs[j];
                 if (a.relu) x = x > 0.0f ? x : 0.0f;
                 buffer_store_elem<float>(x, rout, ok ? (uint32_t)((img * a.K + k) * a.OHW + n) * 4u : kOutOfRange);
             }
