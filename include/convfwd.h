@@ -42,7 +42,16 @@ extern "C" {
 
 typedef enum { CONV_F32 = 0, CONV_F16 = 1, CONV_BF16 = 2 } conv_dtype; /* storage type of in/filt/out */
 
-enum { CONV_FLAG_RELU = 1u }; /* act = max(x,0); without it act is the identity */
+enum {
+    CONV_FLAG_RELU = 1u,      /* act = max(x,0); without it act is the identity */
+    /* Optional channel-innermost formats (the paper's explicit data-format conversions, Section 3 "Graph-level
+     * Optimizations"): the same operation on tensors stored as in [N][H][W][C], filt [K][R][S][C], out [N][OH][OW][K].
+     * Kernels exist for fp16/bf16 with IN_NHWC and FILT_KRSC both set and C % 8 == 0 (and K % 8 == 0 with OUT_NHWC);
+     * any other combination of these bits gives CONV_ENOVARIANT.  conv_convert_layout() converts tensors. */
+    CONV_FLAG_IN_NHWC = 2u,
+    CONV_FLAG_OUT_NHWC = 4u,
+    CONV_FLAG_FILT_KRSC = 8u
+};
 
 typedef enum {
     CONV_OK = 0,
@@ -169,6 +178,20 @@ int conv_coop_load_plan(int threads, int words, int* loads_per_thread, int* last
  */
 int maxpool_fwd(int32_t N, int32_t C, int32_t H, int32_t W, int32_t win, int32_t stride, int32_t dtype,
                 const void* in, void* out, void* stream);
+
+/* The same pooling on either tensor layout: in_nhwc / out_nhwc != 0 means channel-innermost ([N][H][W][C]) for that
+ * side, 0 means [N][C][H][W].  With different layouts on the two sides it is also the format conversion between two
+ * layers.  Errors as maxpool_fwd. */
+int maxpool_fwd_layout(int32_t N, int32_t C, int32_t H, int32_t W, int32_t win, int32_t stride, int32_t dtype,
+                       int32_t in_nhwc, int32_t out_nhwc, const void* in, void* out, void* stream);
+
+/*
+ * Explicit data-format conversion (paper, Section 3, "Graph-level Optimizations"): out[a][s][b] = in[a][b][s] for
+ * dense tensors of `dtype` elements.  (A,B,S) = (N,C,H*W) turns [N][C][H][W] into [N][H][W][C]; (N,H*W,C) turns it
+ * back; (K,C,R*S) turns filters [K][C][R][S] into [K][R][S][C].  Device pointers, out must not alias in; enqueued on
+ * `stream`.  CONV_EINVAL for NULL/aliased pointers, extents < 1, A > 65535 or 2^31 or more elements.
+ */
+int conv_convert_layout(int32_t A, int32_t B, int32_t S, int32_t dtype, const void* in, void* out, void* stream);
 
 /*
  * Measured ceilings of the device, for reporting next to the published peaks (the paper's own practice of timing on

@@ -18,7 +18,7 @@ _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG, "libconvfwd.so")
 
 CONV_F32, CONV_F16, CONV_BF16 = 0, 1, 2
-CONV_FLAG_RELU = 1
+CONV_FLAG_RELU, CONV_FLAG_IN_NHWC, CONV_FLAG_OUT_NHWC, CONV_FLAG_FILT_KRSC = 1, 2, 4, 8
 CONV_OK, CONV_EINVAL, CONV_EDTYPE, CONV_EWORKSPACE, CONV_EHIP, CONV_ENOVARIANT, CONV_EIO = 0, -1, -2, -3, -4, -5, -6
 
 
@@ -91,6 +91,10 @@ def lib() -> ctypes.CDLL:
         L.conv_coop_load_plan.restype = ctypes.c_int
         L.maxpool_fwd.argtypes = [ctypes.c_int32] * 7 + [vp, vp, vp]
         L.maxpool_fwd.restype = ctypes.c_int
+        L.maxpool_fwd_layout.argtypes = [ctypes.c_int32] * 9 + [vp, vp, vp]
+        L.maxpool_fwd_layout.restype = ctypes.c_int
+        L.conv_convert_layout.argtypes = [ctypes.c_int32] * 4 + [vp, vp, vp]
+        L.conv_convert_layout.restype = ctypes.c_int
         L.conv_probe_mfma_peak.argtypes = [ctypes.c_int32, ctypes.c_int32, vp, vp, ctypes.POINTER(ctypes.c_double)]
         L.conv_probe_mfma_peak.restype = ctypes.c_int
         L.conv_probe_stream_bandwidth.argtypes = [vp, vp, ctypes.c_size_t, vp, ctypes.POINTER(ctypes.c_double)]
@@ -106,9 +110,12 @@ def make_desc(N, C, H, W, K, R, S, stride=1, pad=0, dtype=CONV_F32, relu=False, 
     return conv_desc(N, C, H, W, K, R, S, stride, pad, dtype, f)
 
 
-def desc_of(shape, dtype=CONV_F32, relu=True) -> conv_desc:
-    """conv_desc from a workloads.ConvShape."""
-    return make_desc(shape.N, shape.C, shape.H, shape.W, shape.K, shape.R, shape.S, shape.stride, shape.pad, dtype, relu)
+def desc_of(shape, dtype=CONV_F32, relu=True, in_nhwc=False, out_nhwc=False, filt_krsc=False) -> conv_desc:
+    """conv_desc from a workloads.ConvShape (optionally with channel-innermost tensor formats)."""
+    flags = ((CONV_FLAG_RELU if relu else 0) | (CONV_FLAG_IN_NHWC if in_nhwc else 0) |
+             (CONV_FLAG_OUT_NHWC if out_nhwc else 0) | (CONV_FLAG_FILT_KRSC if filt_krsc else 0))
+    return make_desc(shape.N, shape.C, shape.H, shape.W, shape.K, shape.R, shape.S, shape.stride, shape.pad, dtype,
+                     flags=flags)
 
 
 def _ptr(x) -> Optional[int]:
@@ -223,6 +230,16 @@ def conv_coop_load_plan(threads: int, words: int) -> Tuple[int, bool]:
 
 def maxpool_fwd(N, C, H, W, win, stride, dtype, inp, out, stream=None) -> None:
     _check(lib().maxpool_fwd(N, C, H, W, win, stride, dtype, _ptr(inp), _ptr(out), _stream(stream)), "maxpool_fwd")
+
+
+def maxpool_fwd_layout(N, C, H, W, win, stride, dtype, in_nhwc, out_nhwc, inp, out, stream=None) -> None:
+    _check(lib().maxpool_fwd_layout(N, C, H, W, win, stride, dtype, int(bool(in_nhwc)), int(bool(out_nhwc)), _ptr(inp),
+                                    _ptr(out), _stream(stream)), "maxpool_fwd_layout")
+
+
+def conv_convert_layout(A, Bdim, S, dtype, inp, out, stream=None) -> None:
+    """out[a][s][b] = in[a][b][s]: (N,C,H*W) NCHW->NHWC, (N,H*W,C) NHWC->NCHW, (K,C,R*S) KCRS->KRSC."""
+    _check(lib().conv_convert_layout(A, Bdim, S, dtype, _ptr(inp), _ptr(out), _stream(stream)), "conv_convert_layout")
 
 
 def conv_probe_mfma_peak(dtype: int, block: int, scratch, stream=None) -> float:

@@ -49,6 +49,8 @@ State& state()
         register_ugemm_f16(s->variants);
         register_ugemm_bf16(s->variants);
         register_fc(s->variants);
+        register_nhwc_f16(s->variants);
+        register_nhwc_bf16(s->variants);
         register_wconv_f32(s->variants);
         register_wconv_f16(s->variants);
         register_wconv_bf16(s->variants);
@@ -66,7 +68,8 @@ int hip_fail(hipError_t e, const char* what)
     return CONV_EHIP;
 }
 
-const uint32_t kKnownFlags = CONV_FLAG_RELU;
+constexpr uint32_t kLayoutFlags = CONV_FLAG_IN_NHWC | CONV_FLAG_OUT_NHWC | CONV_FLAG_FILT_KRSC;
+constexpr uint32_t kKnownFlags = CONV_FLAG_RELU | kLayoutFlags;
 
 // Validation shared by every entry point; fills OH/OW.
 int check_desc(const conv_desc* d, int& OH, int& OW)
@@ -104,8 +107,12 @@ int check_desc(const conv_desc* d, int& OH, int& OW)
 std::vector<int> valid_list(State& st, const conv_desc& d, int OH, int OW)
 {
     std::vector<int> r;
-    for (size_t i = 0; i < st.variants.size(); ++i)
+    // descriptors with channel-innermost tensors are served by the kernels written for them, and only those
+    const bool layout = (d.flags & kLayoutFlags) != 0;
+    for (size_t i = 0; i < st.variants.size(); ++i) {
+        if ((st.variants[i].family == FAM_NHWC) != layout) continue;
         if (st.variants[i].valid(st.variants[i], d, OH, OW)) r.push_back((int)i);
+    }
     return r;
 }
 
@@ -193,6 +200,7 @@ void fill_args(ConvArgs& a, const conv_desc& d, int OH, int OW, const void* in, 
     a.OHW = OH * OW;
     a.RS = d.R * d.S;
     a.relu = (d.flags & CONV_FLAG_RELU) ? 1 : 0;
+    a.out_nhwc = (d.flags & CONV_FLAG_OUT_NHWC) ? 1 : 0;
     a.in_bytes = (uint32_t)((uint64_t)d.N * d.C * d.H * d.W * dtype_size(d.dtype));
     a.filt_bytes = (uint32_t)((uint64_t)d.K * d.C * d.R * d.S * dtype_size(d.dtype));
     a.out_bytes = (uint32_t)((uint64_t)d.N * d.K * OH * OW * dtype_size(d.dtype));
@@ -209,6 +217,7 @@ void fill_args(ConvArgs& a, const conv_desc& d, int OH, int OW, const void* in, 
     a.dRSP = make_fastdiv((uint32_t)(d.R * a.SP4 * 4));
     a.dSP = make_fastdiv((uint32_t)(a.SP4 * 4));
     a.dRSP4 = make_fastdiv((uint32_t)(d.R * a.SP4));
+    a.dC = make_fastdiv((uint32_t)d.C);
     a.dSP4 = make_fastdiv((uint32_t)a.SP4);
 }
 
@@ -569,8 +578,31 @@ int maxpool_fwd(int32_t N, int32_t C, int32_t H, int32_t W, int32_t win, int32_t
     if (N < 1 || C < 1 || H < 1 || W < 1 || win < 1 || stride < 1 || win > H || win > W || !in || !out)
         return CONV_EINVAL;
     if ((double)N * C * (double)H * W >= 2147483648.0) return CONV_EINVAL;
-    const hipError_t e = launch_maxpool(N, C, H, W, win, stride, dtype, in, out, (hipStream_t)stream);
+    const hipError_t e = launch_maxpool(N, C, H, W, win, stride, dtype, false, false, in, out, (hipStream_t)stream);
     if (e != hipSuccess) return hip_fail(e, "maxpool");
+    return CONV_OK;
+}
+
+int maxpool_fwd_layout(int32_t N, int32_t C, int32_t H, int32_t W, int32_t win, int32_t stride, int32_t dtype,
+                       int32_t in_nhwc, int32_t out_nhwc, const void* in, void* out, void* stream)
+{
+    if (dtype != CONV_F32 && dtype != CONV_F16 && dtype != CONV_BF16) return CONV_EDTYPE;
+    if (N < 1 || C < 1 || H < 1 || W < 1 || win < 1 || stride < 1 || win > H || win > W || !in || !out)
+        return CONV_EINVAL;
+    if ((double)N * C * (double)H * W >= 2147483648.0) return CONV_EINVAL;
+    const hipError_t e =
+        launch_maxpool(N, C, H, W, win, stride, dtype, in_nhwc != 0, out_nhwc != 0, in, out, (hipStream_t)stream);
+    if (e != hipSuccess) return hip_fail(e, "maxpool");
+    return CONV_OK;
+}
+
+int conv_convert_layout(int32_t A, int32_t B, int32_t S, int32_t dtype, const void* in, void* out, void* stream)
+{
+    if (dtype != CONV_F32 && dtype != CONV_F16 && dtype != CONV_BF16) return CONV_EDTYPE;
+    if (A < 1 || B < 1 || S < 1 || A > 65535 || !in || !out || in == out) return CONV_EINVAL;
+    if ((double)A * B * (double)S >= 2147483648.0 || (S + 31) / 32 > 2147483647 || (B + 31) / 32 > 65535) return CONV_EINVAL;
+    const hipError_t e = launch_transpose(A, B, S, dtype_size(dtype), in, out, (hipStream_t)stream);
+    if (e != hipSuccess) return hip_fail(e, "convert_layout");
     return CONV_OK;
 }
 

@@ -20,7 +20,8 @@ __global__ __launch_bounds__(256) void split_reduce_kernel(ConvArgs a)
     if (a.relu) x = x > 0.0f ? x : 0.0f;
     uint32_t n_img, pix;
     a.dOHW.divmod(p, n_img, pix);
-    ((elem_t*)a.out)[((size_t)n_img * a.K + k) * a.OHW + pix] = Prec<DT>::from_f32(x);
+    const size_t o = a.out_nhwc ? (size_t)p * a.K + k : ((size_t)n_img * a.K + k) * a.OHW + pix;
+    ((elem_t*)a.out)[o] = Prec<DT>::from_f32(x);
 }
 
 hipError_t launch_split_reduce(const ConvArgs& a, int dtype, hipStream_t s)
@@ -36,25 +37,39 @@ hipError_t launch_split_reduce(const ConvArgs& a, int dtype, hipStream_t s)
 }
 
 // Per-channel max over a win x win window, stride `stride`, no padding.  The 16-bit formats are widened to fp32 for the
-// comparison (exact and order preserving) and the winning stored pattern is written back unchanged.
+// comparison (exact and order preserving) and the winning stored pattern is written back unchanged.  Input and output
+// may each be channel-planar ([N][C][H][W]) or channel-innermost ([N][H][W][C]); one thread per output element in the
+// order of the output layout, so the pool can double as the layout conversion between two layers.
 template <int DT>
 __global__ __launch_bounds__(256) void maxpool_kernel(const typename Prec<DT>::elem_t* __restrict__ in,
-                                                      typename Prec<DT>::elem_t* __restrict__ out, int NC, int H, int W,
-                                                      int OH, int OW, int win, int stride, FastDiv dOHW, FastDiv dOW)
+                                                      typename Prec<DT>::elem_t* __restrict__ out, int N, int C, int H, int W,
+                                                      int OH, int OW, int win, int stride, int in_nhwc, int out_nhwc,
+                                                      FastDiv dOHW, FastDiv dOW, FastDiv dC)
 {
     typedef typename Prec<DT>::elem_t elem_t;
-    const size_t total = (size_t)NC * OH * OW;
+    const size_t total = (size_t)N * C * OH * OW;
     const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
     if (i >= total) return;
-    uint32_t nc, rem, oy, ox;
-    dOHW.divmod((uint32_t)i, nc, rem);
-    dOW.divmod(rem, oy, ox);
-    const elem_t* src = in + ((size_t)nc * H + (size_t)oy * stride) * W + (size_t)ox * stride;
+    uint32_t n, c, oy, ox;
+    if (out_nhwc) {
+        uint32_t pix, rem;
+        dC.divmod((uint32_t)i, pix, c);
+        dOHW.divmod(pix, n, rem);
+        dOW.divmod(rem, oy, ox);
+    } else {
+        uint32_t nc, rem;
+        dOHW.divmod((uint32_t)i, nc, rem);
+        dOW.divmod(rem, oy, ox);
+        dC.divmod(nc, n, c);
+    }
+    const size_t sy = in_nhwc ? (size_t)W * C : (size_t)W, sx = in_nhwc ? (size_t)C : 1;
+    const elem_t* src = in_nhwc ? in + (((size_t)n * H + (size_t)oy * stride) * W + (size_t)ox * stride) * C + c
+                                : in + (((size_t)n * C + c) * H + (size_t)oy * stride) * W + (size_t)ox * stride;
     elem_t best = src[0];
     float bestf = Prec<DT>::to_f32(best);
     for (int r = 0; r < win; ++r)
         for (int s = 0; s < win; ++s) {
-            const elem_t v = src[(size_t)r * W + s];
+            const elem_t v = src[r * sy + s * sx];
             const float vf = Prec<DT>::to_f32(v);
             if (vf > bestf) {
                 bestf = vf;
@@ -64,27 +79,61 @@ __global__ __launch_bounds__(256) void maxpool_kernel(const typename Prec<DT>::e
     out[i] = best;
 }
 
-hipError_t launch_maxpool(int N, int C, int H, int W, int win, int stride, int dtype, const void* in, void* out,
-                          hipStream_t s)
+hipError_t launch_maxpool(int N, int C, int H, int W, int win, int stride, int dtype, bool in_nhwc, bool out_nhwc,
+                          const void* in, void* out, hipStream_t s)
 {
     const int OH = (H - win) / stride + 1, OW = (W - win) / stride + 1;
     const size_t total = (size_t)N * C * OH * OW;
     dim3 grid((unsigned)((total + 255) / 256));
-    const FastDiv dOHW = make_fastdiv((uint32_t)(OH * OW)), dOW = make_fastdiv((uint32_t)OW);
+    const FastDiv dOHW = make_fastdiv((uint32_t)(OH * OW)), dOW = make_fastdiv((uint32_t)OW), dC = make_fastdiv((uint32_t)C);
     switch (dtype) {
         case CONV_F32:
-            hipLaunchKernelGGL(maxpool_kernel<CONV_F32>, grid, dim3(256), 0, s, (const float*)in, (float*)out, N * C, H,
-                               W, OH, OW, win, stride, dOHW, dOW);
+            hipLaunchKernelGGL(maxpool_kernel<CONV_F32>, grid, dim3(256), 0, s, (const float*)in, (float*)out, N, C, H, W, OH,
+                               OW, win, stride, (int)in_nhwc, (int)out_nhwc, dOHW, dOW, dC);
             break;
         case CONV_F16:
-            hipLaunchKernelGGL(maxpool_kernel<CONV_F16>, grid, dim3(256), 0, s, (const uint16_t*)in, (uint16_t*)out,
-                               N * C, H, W, OH, OW, win, stride, dOHW, dOW);
+            hipLaunchKernelGGL(maxpool_kernel<CONV_F16>, grid, dim3(256), 0, s, (const uint16_t*)in, (uint16_t*)out, N, C, H,
+                               W, OH, OW, win, stride, (int)in_nhwc, (int)out_nhwc, dOHW, dOW, dC);
             break;
         default:
-            hipLaunchKernelGGL(maxpool_kernel<CONV_BF16>, grid, dim3(256), 0, s, (const uint16_t*)in, (uint16_t*)out,
-                               N * C, H, W, OH, OW, win, stride, dOHW, dOW);
+            hipLaunchKernelGGL(maxpool_kernel<CONV_BF16>, grid, dim3(256), 0, s, (const uint16_t*)in, (uint16_t*)out, N, C, H,
+                               W, OH, OW, win, stride, (int)in_nhwc, (int)out_nhwc, dOHW, dOW, dC);
             break;
     }
+    return hipGetLastError();
+}
+
+// out[a][s][b] = in[a][b][s]: 32x32 tiles through LDS so that both the reads (along s) and the writes (along b) are
+// contiguous.  This is the explicit data-format conversion of the paper (Section 3, "Graph-level Optimizations"):
+// [N][C][HW] <-> [N][HW][C] for activations and [K][C][RS] -> [K][RS][C] for filters.
+template <typename E>
+__global__ __launch_bounds__(256) void transpose_kernel(const E* __restrict__ in, E* __restrict__ out, int B, int S)
+{
+    __shared__ E tile[32][33];
+    const int a = blockIdx.z, b0 = blockIdx.y * 32, s0 = blockIdx.x * 32;
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;  // 32 x 8
+    const E* src = in + (size_t)a * B * S;
+    E* dst = out + (size_t)a * B * S;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int b = b0 + ty + 8 * j, s = s0 + tx;
+        if (b < B && s < S) tile[ty + 8 * j][tx] = src[(size_t)b * S + s];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int s = s0 + ty + 8 * j, b = b0 + tx;
+        if (b < B && s < S) dst[(size_t)s * B + b] = tile[tx][ty + 8 * j];
+    }
+}
+
+hipError_t launch_transpose(int A, int B, int S, int esize, const void* in, void* out, hipStream_t s)
+{
+    dim3 grid((unsigned)((S + 31) / 32), (unsigned)((B + 31) / 32), (unsigned)A);
+    if (esize == 4)
+        hipLaunchKernelGGL(transpose_kernel<uint32_t>, grid, dim3(256), 0, s, (const uint32_t*)in, (uint32_t*)out, B, S);
+    else
+        hipLaunchKernelGGL(transpose_kernel<uint16_t>, grid, dim3(256), 0, s, (const uint16_t*)in, (uint16_t*)out, B, S);
     return hipGetLastError();
 }
 

@@ -76,11 +76,13 @@ struct ConvArgs {
     int SP4;  // ceil(S/4): 4-column vectors per window row (s-vector gather)
     int QP;   // C*R*4*SP4: reduction extent with window rows padded to a multiple of 4 columns
     int relu;
+    int out_nhwc;  // output is [N][OH][OW][K] instead of [N][K][OH][OW]
     uint32_t in_bytes, filt_bytes, out_bytes;  // extents for the hardware bounds check of tile loads
     int nsplit;           // number of reduction splits (gridDim.z)
     int steps_per_split;  // reduction steps (of the kernel's own step size) per split
     FastDiv dRS, dS, dOHW, dOW, dHW, dW;
     FastDiv dRSP, dSP, dRSP4, dSP4;  // by R*SP, SP = 4*SP4, R*SP4, SP4
+    FastDiv dC;                      // by C (channel-innermost reduction axis)
 };
 
 struct Variant;
@@ -100,7 +102,7 @@ struct Variant {
     LaunchFn launch;
 };
 
-enum { FAM_IGEMM = 0, FAM_POINTWISE = 1, FAM_FIRSTLAYER = 2, FAM_WINDOW = 3, FAM_FC = 4 };
+enum { FAM_IGEMM = 0, FAM_POINTWISE = 1, FAM_FIRSTLAYER = 2, FAM_WINDOW = 3, FAM_FC = 4, FAM_NHWC = 5 };
 
 // Each kernel file appends its variants.
 void register_igemm_f32(std::vector<Variant>& out);
@@ -110,14 +112,18 @@ void register_ugemm_f32(std::vector<Variant>& out);
 void register_ugemm_f16(std::vector<Variant>& out);
 void register_ugemm_bf16(std::vector<Variant>& out);
 void register_fc(std::vector<Variant>& out);
+void register_nhwc_f16(std::vector<Variant>& out);
+void register_nhwc_bf16(std::vector<Variant>& out);
 void register_wconv_f32(std::vector<Variant>& out);
 void register_wconv_f16(std::vector<Variant>& out);
 void register_wconv_bf16(std::vector<Variant>& out);
 
 // Split-reduction second pass and the max-pool helper (aux_kernels.hip).
 hipError_t launch_split_reduce(const ConvArgs& a, int dtype, hipStream_t s);
-hipError_t launch_maxpool(int N, int C, int H, int W, int win, int stride, int dtype, const void* in, void* out,
-                          hipStream_t s);
+hipError_t launch_maxpool(int N, int C, int H, int W, int win, int stride, int dtype, bool in_nhwc, bool out_nhwc,
+                          const void* in, void* out, hipStream_t s);
+// out[a][s][b] = in[a][b][s] for elements of `esize` bytes (2 or 4): the layout conversions of tensors and filters
+hipError_t launch_transpose(int A, int B, int S, int esize, const void* in, void* out, hipStream_t s);
 
 // Device ceilings measured in place (probe_kernels.hip).
 hipError_t probe_mfma(int dtype, int block, float* sink, hipStream_t s, double* tflops);

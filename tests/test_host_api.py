@@ -52,7 +52,7 @@ def test_out_shape_of_benchmark_configs():
 
 
 @pytest.mark.parametrize("field,value", [("N", 0), ("C", 0), ("H", 0), ("W", -1), ("K", 0), ("R", 0), ("S", 0),
-                                         ("stride", 0), ("pad", -1), ("flags", 2)])
+                                         ("stride", 0), ("pad", -1), ("flags", 16)])
 def test_invalid_descriptor_fields(field, value):
     d = B.make_desc(1, 3, 8, 8, 4, 3, 3, 1, 1)
     setattr(d, field, value)
