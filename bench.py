@@ -139,6 +139,56 @@ def layer_report(w, launches=100, batches=5, rotate_mb=0):
     return rep
 
 
+def stack_report(dtype, batch=20, reps=50):
+    """The five-layer stack end to end (all operations enqueued back to back, one synchronisation at the end):
+    every layer in [N][C][H][W], and with the data format chosen per layer (channel-innermost where it pays)."""
+    import torch
+
+    from paper_1611_06945_amd import binding as B
+    from paper_1611_06945_amd import workloads as wl
+    from paper_1611_06945_amd.stack import ConvStack
+
+    layers = wl.config5_layers(batch, dtype)
+    shapes = [w.shape for w in layers]
+    gen = [w.generate() for w in layers]
+    tdt = {wl.F16: torch.float16, wl.BF16: torch.bfloat16}[dtype]
+
+    def up(a):
+        import numpy as np
+
+        if dtype == wl.BF16:
+            return torch.from_numpy(a.view(np.int16)).cuda().view(torch.bfloat16)
+        return torch.from_numpy(a).cuda()
+
+    x = up(gen[0]["in"])
+    filts = [up(g["filt"]) for g in gen]
+    biases = [torch.from_numpy(g["bias"]).cuda() for g in gen]
+    flops = sum(s.flops for s in shapes)
+    rep = {"dtype": wl.DTYPE_NAMES[dtype], "N": batch, "flops": flops}
+    for tag, formats in (("nchw", None), ("selected", "auto")):
+        st = ConvStack(shapes, dtype, pool_after=wl.STACK_POOL_AFTER, formats=formats)
+        st.autotune(x, filts, biases)
+        for _ in range(5):
+            st.run(x, filts, biases)
+        torch.cuda.synchronize()
+        per = []
+        for _ in range(5):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(reps):
+                st.run(x, filts, biases)
+            e1.record()
+            e1.synchronize()
+            per.append(e0.elapsed_time(e1) / reps)
+        ms = statistics.median(per)
+        rep[tag] = {"formats": st.formats, "ms": round(ms, 5), "gflops": round(flops / (ms * 1e-3) / 1e9, 1),
+                    "variants": [B.conv_variant_name(d, -1) for d in st.descs]}
+        if st.plan_times:
+            rep[tag]["planned_us"] = round(st.plan_times["total_us"], 2)
+        del st
+    return rep
+
+
 def cpu_baseline(w, budget_s=12.0):
     """The oracle as it stands, timed on this host's cores on the same workload (whole layer, repeated)."""
     import numpy as np
@@ -361,6 +411,9 @@ def main():
             log("%-26s %-44s %9.4f ms %10.1f GFLOP/s  mfma %.3f  hbm %.3f" % (
                 rep["layer"], rep["variant"], rep["ms"], rep["gflops"], rep["frac_mfma_peak"], rep["frac_hbm_peak"]))
         out["layers"] = layers
+        out["stack"] = stack_report(wl.F16)
+        log("stack f16: all-NCHW %.4f ms, formats selected %s %.4f ms" % (
+            out["stack"]["nchw"]["ms"], out["stack"]["selected"]["formats"], out["stack"]["selected"]["ms"]))
 
     if not a.no_cpu:
         out["cpu_baseline"] = cpu_baseline(w)

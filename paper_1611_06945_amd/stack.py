@@ -5,6 +5,16 @@ Scheduling, and Execution"): every ND-Array is allocated up front, the operation
 are issued in a topological order on one stream, and the outputs stay on the GPU.
 Here the graph is a straight line, so the order is the list order.  PyTorch only
 provides the device buffers; every operation is a call into libconvfwd.so.
+
+The stack can also apply the paper's second graph-level optimisation (Section 3,
+"Graph-level Optimizations"): choosing a data format per operation and inserting
+the conversions.  With `formats="auto"` every layer that has a channel-innermost
+kernel (fp16/bf16, C % 8 == 0, K % 8 == 0) is timed in both formats, the
+conversions are timed, and the cheapest assignment over the whole chain is found
+by dynamic programming.  A max-pool between two layers converts for free (it reads
+one layout and writes the other); elsewhere an explicit conversion is inserted.
+Filters of channel-innermost layers are repacked once in `prepare()`.  The
+stack's input and final output are always [N][C][H][W].
 """
 from __future__ import annotations
 
@@ -13,61 +23,218 @@ from typing import List, Optional, Sequence
 from . import binding as B
 from .workloads import ConvShape
 
+NCHW, NHWC = "nchw", "nhwc"
+
 
 class ConvStack:
     def __init__(self, shapes: Sequence[ConvShape], dtype: int, pool_after: Sequence[int] = (), relu: bool = True,
-                 pool_win: int = 3, pool_stride: int = 2):
-        """`pool_after` holds 1-based layer numbers that are followed by a max-pool."""
+                 pool_win: int = 3, pool_stride: int = 2, formats=None):
+        """`pool_after` holds 1-based layer numbers that are followed by a max-pool.  `formats`: None = every layer
+        in [N][C][H][W]; "auto" = decided by autotune(); or a list of "nchw"/"nhwc", one per layer."""
         import torch
 
         self.torch = torch
         self.shapes = list(shapes)
         self.dtype = dtype
+        self.relu = relu
         self.pool_after = set(pool_after)
         self.pool_win, self.pool_stride = pool_win, pool_stride
-        self.descs = [B.desc_of(s, dtype, relu=relu) for s in self.shapes]
-        tdt = {B.CONV_F32: torch.float32, B.CONV_F16: torch.float16, B.CONV_BF16: torch.bfloat16}[dtype]
-        self.conv_out: List = []
-        self.pool_out: List[Optional[object]] = []
+        self.tdt = {B.CONV_F32: torch.float32, B.CONV_F16: torch.float16, B.CONV_BF16: torch.bfloat16}[dtype]
+        n = len(self.shapes)
+        for i in range(n - 1):
+            got = self._pooled_shape(i) if (i + 1) in self.pool_after else self.shapes[i].out_shape()
+            want = self.shapes[i + 1].in_shape()
+            if tuple(got) != tuple(want):
+                raise ValueError("layer %d produces %s but layer %d expects %s" % (i + 1, tuple(got), i + 2, want))
+        self.auto = formats == "auto"
+        self.formats = [NCHW] * n if formats in (None, "auto") else list(formats)
+        if len(self.formats) != n or any(f not in (NCHW, NHWC) for f in self.formats):
+            raise ValueError("formats must name nchw or nhwc for each of the %d layers" % n)
+        for i, f in enumerate(self.formats):
+            if f == NHWC and not self.nhwc_capable(i):
+                raise ValueError("layer %d has no channel-innermost kernel" % (i + 1))
+        self.packed_filts: List[Optional[object]] = [None] * n
+        self.plan_times = None
+        self._build()
+
+    # ---- geometry --------------------------------------------------------------------------------------------------
+    def nhwc_capable(self, i: int) -> bool:
+        s = self.shapes[i]
+        return self.dtype != B.CONV_F32 and s.C % 8 == 0 and s.K % 8 == 0
+
+    def _pooled_shape(self, i: int):
+        s = self.shapes[i]
+        oh = (s.OH - self.pool_win) // self.pool_stride + 1
+        ow = (s.OW - self.pool_win) // self.pool_stride + 1
+        return (s.N, s.K, oh, ow)
+
+    def _handoff_layout(self, i: int) -> str:
+        """Layout of what layer i hands on: what the next layer consumes; [N][C][H][W] after the last layer."""
+        return self.formats[i + 1] if i + 1 < len(self.shapes) else NCHW
+
+    def _conv_out_layout(self, i: int) -> str:
+        """A channel-innermost kernel writes whatever layout is wanted next; the other kernels write [N][K][OH][OW].
+        When a pool follows, the pool converts, so the convolution keeps the layout of its own format."""
+        if self.formats[i] == NCHW:
+            return NCHW
+        return NHWC if (i + 1) in self.pool_after else self._handoff_layout(i)
+
+    def _build(self) -> None:
+        torch = self.torch
+        n = len(self.shapes)
+        self.descs, self.conv_out, self.pool_out, self.conv_layout, self.convert_out = [], [], [], [], []
         ws_bytes = 256
-        for i, (s, d) in enumerate(zip(self.shapes, self.descs)):
-            self.conv_out.append(torch.empty(s.out_shape(), dtype=tdt, device="cuda"))
-            if (i + 1) in self.pool_after:
-                oh = (s.OH - pool_win) // pool_stride + 1
-                ow = (s.OW - pool_win) // pool_stride + 1
-                self.pool_out.append(torch.empty((s.N, s.K, oh, ow), dtype=tdt, device="cuda"))
-            else:
-                self.pool_out.append(None)
+        for i, s in enumerate(self.shapes):
+            nh = self.formats[i] == NHWC
+            lay = self._conv_out_layout(i)
+            d = B.desc_of(s, self.dtype, relu=self.relu, in_nhwc=nh, out_nhwc=(lay == NHWC), filt_krsc=nh)
+            self.descs.append(d)
+            self.conv_layout.append(lay)
+            # buffers are flat in memory; the shape recorded here is the logical [N][K][OH][OW] one
+            self.conv_out.append(torch.empty(s.out_shape(), dtype=self.tdt, device="cuda"))
+            self.pool_out.append(torch.empty(self._pooled_shape(i), dtype=self.tdt, device="cuda")
+                                 if (i + 1) in self.pool_after else None)
+            # an explicit conversion is needed only where no pool follows and the layouts differ
+            need_cvt = self.pool_out[i] is None and lay != self._handoff_layout(i)
+            self.convert_out.append(torch.empty(s.out_shape(), dtype=self.tdt, device="cuda") if need_cvt else None)
             ws_bytes = max(ws_bytes, B.conv_workspace_bytes(d))
-            nxt = self.layer_output(i)
-            if i + 1 < len(self.shapes):
-                want = self.shapes[i + 1].in_shape()
-                if tuple(nxt.shape) != tuple(want):
-                    raise ValueError("layer %d produces %s but layer %d expects %s" % (i + 1, tuple(nxt.shape), i + 2, want))
+        self.in_convert = (torch.empty(self.shapes[0].in_shape(), dtype=self.tdt, device="cuda")
+                           if self.formats[0] == NHWC else None)
         self.workspace = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
 
     def layer_output(self, i: int):
-        """What layer i (0-based) hands to the next one: its pooled output if a pool follows, else its own."""
-        return self.pool_out[i] if self.pool_out[i] is not None else self.conv_out[i]
-
-    def autotune(self, x, filts, biases, stream=None) -> None:
-        cur = x
-        for i, d in enumerate(self.descs):
-            B.conv_autotune(d, cur, filts[i], biases[i], self.conv_out[i], self.workspace, self.workspace.numel(), stream)
-            self._pool(i, stream)
-            cur = self.layer_output(i)
-
-    def _pool(self, i: int, stream) -> None:
+        """What layer i (0-based) hands to the next one (device tensor, in layout `output_layout(i)`)."""
         if self.pool_out[i] is not None:
-            s = self.shapes[i]
-            B.maxpool_fwd(s.N, s.K, s.OH, s.OW, self.pool_win, self.pool_stride, self.dtype, self.conv_out[i],
-                          self.pool_out[i], stream)
+            return self.pool_out[i]
+        return self.convert_out[i] if self.convert_out[i] is not None else self.conv_out[i]
 
-    def run(self, x, filts, biases, stream=None):
-        """Enqueue every layer; returns the last layer's output tensor (not synchronised)."""
-        cur = x
+    def output_layout(self, i: int) -> str:
+        return self._handoff_layout(i)
+
+    # ---- one-time preparation ----------------------------------------------------------------------------------------
+    def prepare(self, filts, stream=None) -> None:
+        """Repack the filters of channel-innermost layers ([K][C][R][S] -> [K][R][S][C]); done once, not per run."""
+        for i, s in enumerate(self.shapes):
+            if self.formats[i] == NHWC:
+                self.packed_filts[i] = self.torch.empty_like(filts[i])
+                B.conv_convert_layout(s.K, s.C, s.R * s.S, self.dtype, filts[i], self.packed_filts[i], stream)
+            else:
+                self.packed_filts[i] = None
+
+    def _filt(self, i: int, filts):
+        if self.formats[i] == NHWC:
+            if self.packed_filts[i] is None:
+                raise RuntimeError("prepare(filts) must run before a stack with channel-innermost layers")
+            return self.packed_filts[i]
+        return filts[i]
+
+    # ---- execution ---------------------------------------------------------------------------------------------------
+    def _after_conv(self, i: int, stream) -> None:
+        s = self.shapes[i]
+        if self.pool_out[i] is not None:
+            B.maxpool_fwd_layout(s.N, s.K, s.OH, s.OW, self.pool_win, self.pool_stride, self.dtype,
+                                 self.conv_layout[i] == NHWC, self._handoff_layout(i) == NHWC, self.conv_out[i],
+                                 self.pool_out[i], stream)
+        elif self.convert_out[i] is not None:
+            if self.conv_layout[i] == NCHW:   # -> channel-innermost
+                B.conv_convert_layout(s.N, s.K, s.OH * s.OW, self.dtype, self.conv_out[i], self.convert_out[i], stream)
+            else:
+                B.conv_convert_layout(s.N, s.OH * s.OW, s.K, self.dtype, self.conv_out[i], self.convert_out[i], stream)
+
+    def _first_input(self, x, stream):
+        if self.in_convert is None:
+            return x
+        s = self.shapes[0]
+        B.conv_convert_layout(s.N, s.C, s.H * s.W, self.dtype, x, self.in_convert, stream)
+        return self.in_convert
+
+    def _walk(self, x, filts, biases, stream, tune: bool):
+        cur = self._first_input(x, stream)
         for i, d in enumerate(self.descs):
-            B.conv_fwd_ws(d, cur, filts[i], biases[i], self.conv_out[i], self.workspace, self.workspace.numel(), stream)
-            self._pool(i, stream)
+            call = B.conv_autotune if tune else B.conv_fwd_ws
+            call(d, cur, self._filt(i, filts), biases[i], self.conv_out[i], self.workspace, self.workspace.numel(), stream)
+            self._after_conv(i, stream)
             cur = self.layer_output(i)
         return cur
+
+    def run(self, x, filts, biases, stream=None):
+        """Enqueue every operation; returns the last layer's output tensor, [N][K][OH][OW] (not synchronised)."""
+        return self._walk(x, filts, biases, stream, tune=False)
+
+    def autotune(self, x, filts, biases, stream=None) -> None:
+        """Autotune every layer on real data; with formats="auto", first choose the formats."""
+        if self.auto:
+            self._choose_formats(x, filts, biases, stream)
+        self.prepare(filts, stream)
+        self._walk(x, filts, biases, stream, tune=True)
+
+    # ---- format selection --------------------------------------------------------------------------------------------
+    def _time_op(self, fn, reps: int = 20) -> float:
+        torch = self.torch
+        fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        e1.synchronize()
+        return e0.elapsed_time(e1) * 1e3 / reps
+
+    def _choose_formats(self, x, filts, biases, stream) -> None:
+        """Time each layer in each format (its best variant), each conversion and each pool, then pick per layer by
+        dynamic programming over the chain.  Data content does not matter for the timings; scratch tensors are used."""
+        torch = self.torch
+        n = len(self.shapes)
+        conv_t = [{} for _ in range(n)]      # (format, out layout) -> microseconds
+        glue_t = [{} for _ in range(n)]      # (conv out layout, handoff layout) -> microseconds of pool / conversion
+        for i, s in enumerate(self.shapes):
+            xin = torch.zeros(s.in_shape(), dtype=self.tdt, device="cuda")
+            f = torch.zeros(s.filt_shape(), dtype=self.tdt, device="cuda")
+            out = torch.empty(s.out_shape(), dtype=self.tdt, device="cuda")
+            for fmt in ((NCHW, NHWC) if self.nhwc_capable(i) else (NCHW,)):
+                for olay in ((NCHW, NHWC) if fmt == NHWC else (NCHW,)):
+                    d = B.desc_of(s, self.dtype, relu=self.relu, in_nhwc=fmt == NHWC, out_nhwc=olay == NHWC,
+                                  filt_krsc=fmt == NHWC)
+                    ws = torch.empty(max(256, B.conv_workspace_bytes(d)), dtype=torch.uint8, device="cuda")
+                    B.conv_autotune(d, xin, f, biases[i], out, ws, ws.numel(), stream)
+                    conv_t[i][(fmt, olay)] = B.conv_time_us(d, xin, f, biases[i], out, ws, ws.numel(), stream, launches=20)
+            pooled = (i + 1) in self.pool_after
+            dst = torch.empty(self._pooled_shape(i) if pooled else s.out_shape(), dtype=self.tdt, device="cuda")
+            for a in (NCHW, NHWC):
+                for b in (NCHW, NHWC):
+                    if pooled:
+                        glue_t[i][(a, b)] = self._time_op(lambda: B.maxpool_fwd_layout(
+                            s.N, s.K, s.OH, s.OW, self.pool_win, self.pool_stride, self.dtype, a == NHWC, b == NHWC, out, dst,
+                            stream))
+                    elif a == b:
+                        glue_t[i][(a, b)] = 0.0
+                    else:
+                        dims = (s.N, s.K, s.OH * s.OW) if a == NCHW else (s.N, s.OH * s.OW, s.K)
+                        glue_t[i][(a, b)] = self._time_op(lambda: B.conv_convert_layout(*dims, self.dtype, out, dst, stream))
+        s0 = self.shapes[0]
+        x_cvt = self._time_op(lambda: B.conv_convert_layout(
+            s0.N, s0.C, s0.H * s0.W, self.dtype, x, torch.empty_like(x), stream)) if self.nhwc_capable(0) else float("inf")
+        # best[i][fmt] = cheapest time of layers 0..i-1 plus glue, arriving at layer i with its input in layout fmt
+        best = [{NCHW: 0.0, NHWC: x_cvt}]
+        back = []
+        for i in range(n):
+            nxt, bk = {}, {}
+            for want in (NCHW, NHWC):            # layout handed on after layer i
+                if i == n - 1 and want != NCHW:
+                    continue
+                for (fmt, olay), t in conv_t[i].items():
+                    # a pool converts from olay to `want`; without a pool the kernel may write `want` itself
+                    total = best[i].get(fmt, float("inf")) + t + glue_t[i][(olay, want)]
+                    if total < nxt.get(want, float("inf")):
+                        nxt[want], bk[want] = total, (fmt, olay)
+            best.append(nxt)
+            back.append(bk)
+        want, chosen = NCHW, [None] * n
+        for i in range(n - 1, -1, -1):
+            fmt, _ = back[i][want]
+            chosen[i] = fmt
+            want = fmt
+        self.plan_times = {"conv_us": conv_t, "glue_us": glue_t, "input_convert_us": x_cvt, "total_us": best[n][NCHW]}
+        self.formats = chosen
+        self._build()

@@ -96,3 +96,53 @@ def test_config5_stack(dtype):
     e2e = oracle.max_normalised_error(to_host_f64(y, dtype), ref_chain)
     say("  end-to-end error vs the oracle's own chain: %.3g" % e2e)
     assert e2e <= 10 * TOL[dtype]
+
+
+def _to_nchw(t, layout, dtype):
+    """Logical [N][K][OH][OW] float64 view of a stack buffer stored in `layout`."""
+    host = to_host_f64(t, dtype)
+    if layout == "nhwc":
+        n, k, h, w = host.shape
+        host = np.ascontiguousarray(np.transpose(host.reshape(n, h, w, k), (0, 3, 1, 2)))
+    return host
+
+
+@pytest.mark.parametrize("formats", [["nchw", "nhwc", "nchw", "nhwc", "nhwc"], "auto"])
+@pytest.mark.parametrize("dtype", [wl.F16, wl.BF16])
+def test_config5_stack_with_format_selection(dtype, formats):
+    # the same five layers with channel-innermost formats where chosen: conversions by the pools, one explicit
+    # conversion (layer 3 -> 4 in the fixed assignment), repacked filters; every layer against the oracle
+    torch = torch_mod()
+    layers = wl.config5_layers(20, dtype)
+    shapes = [w.shape for w in layers]
+    stack = ConvStack(shapes, dtype, pool_after=wl.STACK_POOL_AFTER, formats=formats)
+    gen = [w.generate() for w in layers]
+    x = to_device(gen[0]["in"], dtype)
+    filts = [to_device(g["filt"], dtype) for g in gen]
+    biases = [to_device(g["bias"], wl.F32) for g in gen]
+    stack.autotune(x, filts, biases)
+    say("  formats: %s" % (stack.formats,))
+    if formats == "auto":
+        say("  planned total %.1f us" % stack.plan_times["total_us"])
+    else:
+        assert stack.formats == formats
+    assert stack.formats[0] == "nchw"  # three input channels: no channel-innermost kernel
+    y = stack.run(x, filts, biases)
+    torch.cuda.synchronize()
+    cur = wl.storage_to_f64(gen[0]["in"], dtype)
+    for i, s in enumerate(shapes):
+        ref = oracle.conv_fwd(cur, wl.storage_to_f64(gen[i]["filt"], dtype), gen[i]["bias"].astype(np.float64),
+                              stride=s.stride, pad=s.pad, relu=True)
+        got = _to_nchw(stack.conv_out[i], stack.conv_layout[i], dtype)
+        assert np.all(np.isfinite(got))
+        err = oracle.max_normalised_error(got, ref)
+        say("  layer %d (%s, %s) error %.3g" % (i + 1, stack.formats[i], B.conv_variant_name(stack.descs[i], -1), err))
+        assert err <= TOL[dtype], (i + 1, err)
+        handed = _to_nchw(stack.layer_output(i), stack.output_layout(i), dtype)
+        if stack.pool_out[i] is not None:
+            assert np.array_equal(handed, oracle.maxpool_fwd(got, win=3, stride=2)), "max-pool after layer %d" % (i + 1)
+        else:
+            assert np.array_equal(handed, got), "conversion after layer %d" % (i + 1)
+        cur = handed  # the next layer is judged on the GPU's own stored input
+    assert stack.output_layout(len(shapes) - 1) == "nchw"
+    assert np.array_equal(to_host_f64(y, dtype), cur)
