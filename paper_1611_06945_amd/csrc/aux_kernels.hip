@@ -79,10 +79,85 @@ __global__ __launch_bounds__(256) void maxpool_kernel(const typename Prec<DT>::e
     out[i] = best;
 }
 
+// The same pooling when input and output layouts differ: a tile of 32 channels x 32 output pixels of one image is
+// pooled by threads arranged along the INPUT's contiguous axis, parked in LDS, and written out by threads arranged
+// along the OUTPUT's contiguous axis, so that both sides of the conversion move contiguous runs.
+template <int DT, bool IN_NHWC>
+__global__ __launch_bounds__(256) void maxpool_xlayout_kernel(const typename Prec<DT>::elem_t* __restrict__ in,
+                                                              typename Prec<DT>::elem_t* __restrict__ out, int C, int H, int W,
+                                                              int OH, int OW, int win, int stride, FastDiv dOW)
+{
+    typedef typename Prec<DT>::elem_t elem_t;
+    __shared__ elem_t tile[32][33];  // [channel][pixel]
+    const int n = blockIdx.z, c0 = blockIdx.y * 32, p0 = blockIdx.x * 32, OHW = OH * OW;
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        // reading side: tx runs along the input's contiguous axis (channels for [N][H][W][C], pixels otherwise)
+        const int cl = IN_NHWC ? tx : ty + 8 * j, pl = IN_NHWC ? ty + 8 * j : tx;
+        const int c = c0 + cl, p = p0 + pl;
+        if (c < C && p < OHW) {
+            uint32_t oy, ox;
+            dOW.divmod((uint32_t)p, oy, ox);
+            const size_t sy = IN_NHWC ? (size_t)W * C : (size_t)W, sx = IN_NHWC ? (size_t)C : 1;
+            const elem_t* src = IN_NHWC ? in + (((size_t)n * H + (size_t)oy * stride) * W + (size_t)ox * stride) * C + c
+                                        : in + (((size_t)n * C + c) * H + (size_t)oy * stride) * W + (size_t)ox * stride;
+            elem_t best = src[0];
+            float bestf = Prec<DT>::to_f32(best);
+            for (int r = 0; r < win; ++r)
+                for (int s = 0; s < win; ++s) {
+                    const elem_t v = src[r * sy + s * sx];
+                    const float vf = Prec<DT>::to_f32(v);
+                    if (vf > bestf) {
+                        bestf = vf;
+                        best = v;
+                    }
+                }
+            tile[cl][pl] = best;
+        }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        // writing side: tx runs along the output's contiguous axis (the other one)
+        const int cl = IN_NHWC ? ty + 8 * j : tx, pl = IN_NHWC ? tx : ty + 8 * j;
+        const int c = c0 + cl, p = p0 + pl;
+        if (c < C && p < OHW) {
+            if (IN_NHWC)
+                out[((size_t)n * C + c) * OHW + p] = tile[cl][pl];
+            else
+                out[((size_t)n * OHW + p) * C + c] = tile[cl][pl];
+        }
+    }
+}
+
+template <int DT>
+void launch_maxpool_xlayout(int N, int C, int H, int W, int OH, int OW, int win, int stride, bool in_nhwc, const void* in,
+                            void* out, hipStream_t s)
+{
+    typedef typename Prec<DT>::elem_t elem_t;
+    dim3 grid((unsigned)((OH * OW + 31) / 32), (unsigned)((C + 31) / 32), (unsigned)N);
+    const FastDiv dOW = make_fastdiv((uint32_t)OW);
+    if (in_nhwc)
+        hipLaunchKernelGGL((maxpool_xlayout_kernel<DT, true>), grid, dim3(256), 0, s, (const elem_t*)in, (elem_t*)out, C, H, W,
+                           OH, OW, win, stride, dOW);
+    else
+        hipLaunchKernelGGL((maxpool_xlayout_kernel<DT, false>), grid, dim3(256), 0, s, (const elem_t*)in, (elem_t*)out, C, H, W,
+                           OH, OW, win, stride, dOW);
+}
+
 hipError_t launch_maxpool(int N, int C, int H, int W, int win, int stride, int dtype, bool in_nhwc, bool out_nhwc,
                           const void* in, void* out, hipStream_t s)
 {
     const int OH = (H - win) / stride + 1, OW = (W - win) / stride + 1;
+    if (in_nhwc != out_nhwc && N <= 65535 && (C + 31) / 32 <= 65535) {
+        switch (dtype) {
+            case CONV_F32: launch_maxpool_xlayout<CONV_F32>(N, C, H, W, OH, OW, win, stride, in_nhwc, in, out, s); break;
+            case CONV_F16: launch_maxpool_xlayout<CONV_F16>(N, C, H, W, OH, OW, win, stride, in_nhwc, in, out, s); break;
+            default: launch_maxpool_xlayout<CONV_BF16>(N, C, H, W, OH, OW, win, stride, in_nhwc, in, out, s); break;
+        }
+        return hipGetLastError();
+    }
     const size_t total = (size_t)N * C * OH * OW;
     dim3 grid((unsigned)((total + 255) / 256));
     const FastDiv dOHW = make_fastdiv((uint32_t)(OH * OW)), dOW = make_fastdiv((uint32_t)OW), dC = make_fastdiv((uint32_t)C);
