@@ -99,13 +99,6 @@ __global__ __launch_bounds__(CFG::NT) void wconv16_kernel(ConvArgs a)
     const __amdgpu_buffer_rsrc_t rin = make_rsrc(a.in, a.in_bytes);
     const __amdgpu_buffer_rsrc_t rfilt = make_rsrc(a.filt, a.filt_bytes);
 
-    // zero both patch slabs once: border and slack stay zero, real positions are overwritten by every chunk
-    {
-        uint4* z = (uint4*)Bs0;
-        const int n16 = (2 * b_elems * (int)sizeof(elem_t)) / 16;
-        for (int i = tid; i < n16; i += NT) z[i] = make_uint4(0, 0, 0, 0);
-    }
-
     // ---- staging plan of the patch slab: task = (input pixel of the band, channel octet) -----------------------
     // input rows iy in [iy_lo, iy_hi) of the image are the band's rows oy0-pad .. oy0-pad+in_rows-1 clipped to the image
     const int iy_first = oy0 - a.pad;
@@ -280,8 +273,14 @@ __global__ __launch_bounds__(CFG::NT) void wconv16_kernel(ConvArgs a)
     typedef std::integral_constant<int, TSPLIT> tap_mid;
     typedef std::integral_constant<int, RS> tap_last;
 
+    if (chunk_begin < chunk_end) load_chunk(chunk_begin);  // in flight while the slabs are cleared
+    // zero both patch slabs once: border and slack stay zero, real positions are overwritten by every chunk
+    {
+        uint4* z = (uint4*)Bs0;
+        const int n16 = (2 * b_elems * (int)sizeof(elem_t)) / 16;
+        for (int i = tid; i < n16; i += NT) z[i] = make_uint4(0, 0, 0, 0);
+    }
     if (chunk_begin < chunk_end) {
-        load_chunk(chunk_begin);
         __syncthreads();  // zero fill done before the first real write
         store_chunk(0);
         if constexpr (NAT) {
