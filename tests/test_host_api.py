@@ -213,3 +213,37 @@ def test_appendix_a_workload_list_is_the_papers_table(appendix_a):
         assert abs(s.flops - r["flops"]) <= 1e-5 * r["flops"]
     assert len({w.name for w in ws}) == 43
     assert len({w.seeds() for w in ws}) == 43
+
+
+def test_layout_entry_points_validate_before_any_gpu_call():
+    L = B.lib()
+    assert L.conv_convert_layout(0, 4, 4, 0, 256, 512, None) == B.CONV_EINVAL      # extent < 1
+    assert L.conv_convert_layout(2, 4, 4, 7, 256, 512, None) == B.CONV_EDTYPE
+    assert L.conv_convert_layout(2, 4, 4, 0, None, 512, None) == B.CONV_EINVAL
+    assert L.conv_convert_layout(2, 4, 4, 0, 256, 256, None) == B.CONV_EINVAL      # in place is not supported
+    assert L.conv_convert_layout(70000, 4, 4, 0, 256, 512, None) == B.CONV_EINVAL  # more outer slices than grid rows
+    assert L.maxpool_fwd_layout(1, 1, 2, 2, 3, 2, 0, 1, 0, 256, 512, None) == B.CONV_EINVAL  # window larger than input
+    assert L.maxpool_fwd_layout(1, 1, 5, 5, 3, 2, 9, 0, 1, 256, 512, None) == B.CONV_EDTYPE
+    assert L.maxpool_fwd_layout(1, 1, 5, 5, 3, 2, 0, 0, 1, None, 512, None) == B.CONV_EINVAL
+
+
+def test_layout_flags_select_only_channel_innermost_kernels():
+    from paper_1611_06945_amd.workloads import ConvShape
+
+    sh = ConvShape(2, 32, 13, 13, 64, 3, 3, 1, 1)
+    plain = B.desc_of(sh, 1)
+    nh = B.desc_of(sh, 1, in_nhwc=True, out_nhwc=True, filt_krsc=True)
+    names_plain = [B.conv_variant_name(plain, i) for i in range(B.conv_variant_count(plain))]
+    names_nh = [B.conv_variant_name(nh, i) for i in range(B.conv_variant_count(nh))]
+    assert names_plain and not any(n.startswith("nhwc_") for n in names_plain)
+    assert names_nh and all(n.startswith("nhwc_") for n in names_nh)
+    # the two descriptors are different cache keys: forcing a variant for one leaves the other alone
+    B.conv_force_variant(nh, 0)
+    try:
+        assert B.conv_variant_name(nh, -1) == names_nh[0]
+        assert B.conv_variant_name(plain, -1) in names_plain
+    finally:
+        B.conv_force_variant(nh, -1)
+    # fully connected shapes are offered the weight-streaming kernels
+    fc = B.desc_of(ConvShape(5, 256, 6, 6, 4096, 6, 6, 1, 0), 0)
+    assert B.conv_variant_name(fc, -1).startswith("fc_f32_")
