@@ -4,7 +4,6 @@
 namespace convfwd {
 
 #define H16CFG(MB, WM, WN, BM, BN, TK, AVEC) IgemmCfg<CONV_BF16, MB, WM, WN, BM, BN, TK, AVEC, MODE_GATHER>
-#define H16TAB(MB, WM, WN, BM, BN, TK, AVEC) IgemmCfg<CONV_BF16, MB, WM, WN, BM, BN, TK, AVEC, MODE_TABLE>
 
 void register_igemm_bf16(std::vector<Variant>& out)
 {
@@ -28,13 +27,6 @@ void register_igemm_bf16(std::vector<Variant>& out)
     igemm_register<H16CFG(32, 1, 4, 3, 1, 64, false)>(out, "igemm", FAM_IGEMM, 0, sk_one);  // M96  N128
     igemm_register<H16CFG(32, 2, 2, 1, 2, 64, false)>(out, "igemm", FAM_IGEMM, 0, sk_one);  // M64  N128
     igemm_register<H16CFG(32, 2, 2, 2, 1, 64, true)>(out, "igemm", FAM_IGEMM, 0, sk_few);   // M128 N64
-    // offset-table gather for layers without padding
-    igemm_register<H16TAB(32, 1, 4, 3, 1, 32, false)>(out, "tab", FAM_FIRSTLAYER, 2, sk_one);  // M96  N128
-    igemm_register<H16TAB(32, 2, 2, 1, 2, 32, false)>(out, "tab", FAM_FIRSTLAYER, 2, sk_one);  // M64  N128
-    igemm_register<H16TAB(32, 1, 4, 1, 1, 32, false)>(out, "tab", FAM_FIRSTLAYER, 2, sk_one);  // M32  N128
-    igemm_register<H16TAB(16, 1, 4, 1, 1, 32, false)>(out, "tab", FAM_FIRSTLAYER, 2, sk_one);  // M16  N64
-    igemm_register<H16TAB(32, 1, 4, 3, 1, 64, false)>(out, "tab", FAM_FIRSTLAYER, 2, sk_one);  // M96  N128 K64
-    igemm_register<H16TAB(32, 2, 2, 2, 2, 32, true)>(out, "tab", FAM_FIRSTLAYER, 2, sk_one);   // M128 N128
 }
 
 }  // namespace convfwd

@@ -34,19 +34,6 @@ void register_igemm_f32(std::vector<Variant>& out)
     igemm_register<F32CFG_K32(32, 2, 2, 1, 1, true, MODE_GATHER)>(out, "igemm", FAM_IGEMM, 0, sk_few);   // M64  N64
     igemm_register<F32CFG_K32(32, 2, 2, 1, 1, true, MODE_POINTWISE)>(out, "pw", FAM_POINTWISE, 2, sk_few);  // M64 N64
     igemm_register<F32CFG_K32(16, 4, 1, 1, 2, true, MODE_POINTWISE)>(out, "pw", FAM_POINTWISE, 2, sk_few);  // M64 N32
-    // s-vector gather for layers with few channels and wide windows (first layers)
-    igemm_register<F32CFG(32, 1, 4, 3, 1, false, MODE_SVEC)>(out, "fl", FAM_FIRSTLAYER, 2, sk_one);  // M96  N128
-    igemm_register<F32CFG(32, 2, 2, 1, 2, false, MODE_SVEC)>(out, "fl", FAM_FIRSTLAYER, 2, sk_one);  // M64  N128
-    igemm_register<F32CFG(32, 1, 4, 1, 1, false, MODE_SVEC)>(out, "fl", FAM_FIRSTLAYER, 2, sk_one);  // M32  N128
-    igemm_register<F32CFG(16, 1, 4, 1, 1, false, MODE_SVEC)>(out, "fl", FAM_FIRSTLAYER, 2, sk_one);  // M16  N64
-    igemm_register<F32CFG_K32(32, 1, 4, 3, 1, false, MODE_SVEC)>(out, "fl", FAM_FIRSTLAYER, 2, sk_one);  // M96 N128 K32
-    // offset-table gather for layers without padding (first layers with stride > 1, valid convolutions)
-    igemm_register<F32CFG(32, 1, 4, 3, 1, false, MODE_TABLE)>(out, "tab", FAM_FIRSTLAYER, 2, sk_one);  // M96  N128
-    igemm_register<F32CFG(32, 2, 2, 1, 2, false, MODE_TABLE)>(out, "tab", FAM_FIRSTLAYER, 2, sk_one);  // M64  N128
-    igemm_register<F32CFG(32, 1, 4, 1, 1, false, MODE_TABLE)>(out, "tab", FAM_FIRSTLAYER, 2, sk_one);  // M32  N128
-    igemm_register<F32CFG(16, 1, 4, 1, 1, false, MODE_TABLE)>(out, "tab", FAM_FIRSTLAYER, 2, sk_one);  // M16  N64
-    igemm_register<F32CFG(32, 2, 2, 2, 2, true, MODE_TABLE)>(out, "tab", FAM_FIRSTLAYER, 2, sk_one);   // M128 N128
-    igemm_register<F32CFG(32, 2, 2, 1, 1, true, MODE_TABLE)>(out, "tab", FAM_FIRSTLAYER, 2, sk_one);   // M64  N64
     // pointwise: 1x1, stride 1, pad 0 -- the input image is already the [C x HW] GEMM operand, 16-byte loads along pixels
     igemm_register<F32CFG(32, 2, 2, 2, 1, true, MODE_POINTWISE)>(out, "pw", FAM_POINTWISE, 2, sk_few);  // M128 N64
     igemm_register<F32CFG(32, 2, 2, 1, 2, true, MODE_POINTWISE)>(out, "pw", FAM_POINTWISE, 2, sk_few);  // M64  N128

@@ -174,14 +174,8 @@ __device__ __forceinline__ int acc_row(int v, int lane)
         return (lane >> 4) * 4 + v;
 }
 
-// MODE_SVEC: gather whose reduction axis is (c, r, s padded to a multiple of 4): a thread fetches four consecutive
-// window columns of its pixel with one 16-byte load.  With stride 4 (the 11x11 first layers) the lanes of a wave then
-// read one contiguous kilobyte instead of 64 scattered words.  fp32 only.
-// MODE_TABLE: gather for layers without padding: the offset c*H*W + r*W + s of every reduction index is the same for
-// all pixels, so it is tabulated once per workgroup in LDS and a patch element costs one LDS read, one add and one
-// load -- no divisions, no window-position bookkeeping, no bounds tests in the loop (any stride, any storage type).
-enum { MODE_GATHER = 0, MODE_POINTWISE = 1, MODE_SVEC = 2, MODE_TABLE = 3 };
-constexpr int kTableMax = 4096;  // longest reduction axis the offset table holds
+// MODE_GATHER: any descriptor.  MODE_POINTWISE: R = S = 1, stride 1, no padding (the image is the GEMM operand as it is).
+enum { MODE_GATHER = 0, MODE_POINTWISE = 1 };
 
 // ---------------------------------------------------------------------------
 // compile-time geometry of one variant
@@ -218,7 +212,6 @@ struct IgemmCfg {
     static_assert(CHW >= 1 && NCH >= 1 && NCH * GROUPS * CHW == TK, "gather chunks must tile the reduction step");
     static_assert(TK % VEC == 0, "vector loads along the reduction");
     static_assert(MODE != MODE_POINTWISE || (B_KMAJOR && (NT % (TN / 4) == 0)), "pointwise mode: fp32, fixed pixel vector");
-    static_assert(MODE != MODE_SVEC || (B_KMAJOR && !AVEC && (CHW % 4) == 0), "s-vector mode: fp32, element-wise filter loads");
 };
 
 // One reduction step of a wave: its BM x BN accumulator blocks advance by the TK reduction elements held in the LDS
@@ -404,7 +397,6 @@ __global__ __launch_bounds__(CFG::NT) void igemm_kernel(ConvArgs a)
 
     __shared__ __attribute__((aligned(16))) elem_t As[2][CFG::A_ELEMS];
     __shared__ __attribute__((aligned(16))) elem_t Bs[2][CFG::B_ELEMS];
-    __shared__ int q_off[(CFG::MODE == MODE_TABLE) ? kTableMax : 1];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
@@ -417,8 +409,7 @@ __global__ __launch_bounds__(CFG::NT) void igemm_kernel(ConvArgs a)
     const __amdgpu_buffer_rsrc_t rfilt = make_rsrc(a.filt, a.filt_bytes);
 
     // reduction steps of this split
-    const int Qeff = (CFG::MODE == MODE_SVEC) ? a.QP : a.Q;  // length of the reduction axis as this mode lays it out
-    const int total_steps = (Qeff + TK - 1) / TK;
+    const int total_steps = (a.Q + TK - 1) / TK;
     const int step_begin = blockIdx.z * a.steps_per_split;
     int step_end = step_begin + a.steps_per_split;
     if (step_end > total_steps) step_end = total_steps;
@@ -442,16 +433,6 @@ __global__ __launch_bounds__(CFG::NT) void igemm_kernel(ConvArgs a)
         } else {
             g_base = (int)n_img * a.C * a.HW + (int)rem;  // 1x1, stride 1, pad 0: pixel index == input index
         }
-    }
-
-    if constexpr (CFG::MODE == MODE_TABLE) {
-        for (int q = tid; q < a.Q; q += NT) {
-            uint32_t c, rs, r, sx;
-            a.dRS.divmod((uint32_t)q, c, rs);
-            a.dS.divmod(rs, r, sx);
-            q_off[q] = (int)c * a.HW + (int)r * a.W + (int)sx;
-        }
-        __syncthreads();
     }
 
     // ---- staging registers --------------------------------------------------------------------
@@ -479,33 +460,12 @@ __global__ __launch_bounds__(CFG::NT) void igemm_kernel(ConvArgs a)
                 const int v = i * NT + tid;
                 const bool in_tile = (i + 1 < planAs.loads || !planAs.last_guarded) ? true : (v < TM * TK);
                 const int row = v / TK, col = v % TK;
-                if constexpr (CFG::MODE == MODE_SVEC) {
-                    // column q' = (c, r, s') of the padded reduction axis; s' >= S is padding and reads as zero
-                    uint32_t c, rem, r, sp;
-                    a.dRSP.divmod((uint32_t)(q0 + col), c, rem);
-                    a.dSP.divmod(rem, r, sp);
-                    const bool ok = in_tile && (m0 + row < a.K) && ((int)c < a.C) && ((int)sp < a.S);
-                    a_sc[i] = buffer_load_elem<elem_t>(
-                        rfilt, ok ? (uint32_t)((m0 + row) * a.Q + (int)c * a.RS + (int)r * a.S + (int)sp) * ES : kOutOfRange);
-                } else {
-                    const bool ok = in_tile && (m0 + row < a.K) && (q0 + col < a.Q);
-                    a_sc[i] = buffer_load_elem<elem_t>(rfilt, ok ? (uint32_t)((m0 + row) * a.Q + q0 + col) * ES : kOutOfRange);
-                }
+                const bool ok = in_tile && (m0 + row < a.K) && (q0 + col < a.Q);
+                a_sc[i] = buffer_load_elem<elem_t>(rfilt, ok ? (uint32_t)((m0 + row) * a.Q + q0 + col) * ES : kOutOfRange);
             }
         }
         // patch tile
-        if constexpr (CFG::MODE == MODE_TABLE) {
-#pragma unroll
-            for (int j = 0; j < NCH; ++j) {
-                const int q = q0 + (g_grp + j * GROUPS) * CHW;
-#pragma unroll
-                for (int e = 0; e < CHW; ++e) {
-                    const bool ok = g_pvalid && (q + e < a.Q);
-                    const int off = q_off[ok ? q + e : 0];
-                    b_reg[j][e] = buffer_load_elem<elem_t>(rin, ok ? (uint32_t)(g_base + off) * ES : kOutOfRange);
-                }
-            }
-        } else if constexpr (CFG::MODE == MODE_GATHER) {
+        if constexpr (CFG::MODE == MODE_GATHER) {
 #pragma unroll
             for (int j = 0; j < NCH; ++j) {
                 const int q = q0 + (g_grp + j * GROUPS) * CHW;
@@ -528,50 +488,6 @@ __global__ __launch_bounds__(CFG::NT) void igemm_kernel(ConvArgs a)
                         if (ri == a.R) {
                             ri = 0;
                             off += a.HW - a.R * a.W;
-                        }
-                    }
-                }
-            }
-        } else if constexpr (CFG::MODE == MODE_SVEC) {
-            const int in_elems = (int)(a.in_bytes / ES);
-#pragma unroll
-            for (int j = 0; j < NCH; ++j) {
-                const int q = q0 + (g_grp + j * GROUPS) * CHW;  // a multiple of 4
-                uint32_t c, rem, r, sv;
-                a.dRSP4.divmod((uint32_t)q >> 2, c, rem);
-                a.dSP4.divmod(rem, r, sv);
-                int ci = (int)c, ri = (int)r, svi = (int)sv;
-#pragma unroll
-                for (int v4 = 0; v4 < CHW / 4; ++v4) {
-                    const int s0 = svi * 4;
-                    const bool row_ok = g_pvalid && (ci < a.C) && ((unsigned)(g_iy0 + ri) < (unsigned)a.H);
-                    const int idx = g_base + ci * a.HW + ri * a.W + s0;  // element index of the vector's first column
-                    bool ok[4];
-#pragma unroll
-                    for (int e = 0; e < 4; ++e)
-                        ok[e] = row_ok && (s0 + e < a.S) && ((unsigned)(g_ix0 + s0 + e) < (unsigned)a.W);
-                    // one 16-byte load when all four addresses lie inside the tensor (columns past the window or
-                    // the row end are real, finite neighbours and are masked below); element loads otherwise
-                    const bool vec_safe = row_ok && (g_ix0 + s0 >= 0) && (idx + 3 < in_elems);
-                    uint32_t w4[4] = {0u, 0u, 0u, 0u};
-                    if (vec_safe) {
-                        const u32x4 t = __builtin_amdgcn_raw_buffer_load_b128(rin, (int)((uint32_t)idx * ES), 0, 0);
-                        w4[0] = t.x; w4[1] = t.y; w4[2] = t.z; w4[3] = t.w;
-                    } else if (row_ok) {
-#pragma unroll
-                        for (int e = 0; e < 4; ++e)
-                            w4[e] = __builtin_amdgcn_raw_buffer_load_b32(
-                                rin, (int)(ok[e] ? (uint32_t)(idx + e) * ES : kOutOfRange), 0, 0);
-                    }
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) b_reg[j][v4 * 4 + e] = ok[e] ? __builtin_bit_cast(elem_t, w4[e]) : (elem_t)0;
-                    ++svi;
-                    if (svi == a.SP4) {
-                        svi = 0;
-                        ++ri;
-                        if (ri == a.R) {
-                            ri = 0;
-                            ++ci;
                         }
                     }
                 }
@@ -672,7 +588,7 @@ __global__ __launch_bounds__(CFG::NT) void igemm_kernel(ConvArgs a)
 template <class CFG>
 hipError_t igemm_launch(const Variant& v, ConvArgs& a, hipStream_t s)
 {
-    const int total_steps = ((CFG::MODE == MODE_SVEC ? a.QP : a.Q) + CFG::TK - 1) / CFG::TK;
+    const int total_steps = (a.Q + CFG::TK - 1) / CFG::TK;
     a.nsplit = v.split;
     a.steps_per_split = (total_steps + v.split - 1) / v.split;
     dim3 grid((unsigned)((a.P + CFG::TN - 1) / CFG::TN), (unsigned)((a.K + CFG::TM - 1) / CFG::TM), (unsigned)v.split);
@@ -686,14 +602,6 @@ bool igemm_valid(const Variant& v, const conv_desc& d, int OH, int OW)
     if (d.dtype != CFG::DT) return false;
     const long long Q = (long long)d.C * d.R * d.S, P = (long long)d.N * OH * OW;
     if (CFG::AVEC && (Q % CFG::VEC) != 0) return false;
-    if (CFG::MODE == MODE_TABLE) {
-        if (d.pad != 0 || Q > kTableMax) return false;
-        if (d.R == 1 && d.S == 1 && d.stride == 1) return false;  // the pointwise variants cover this
-    }
-    if (CFG::MODE == MODE_SVEC) {
-        if (d.S < 3) return false;  // nothing to vectorise
-        if ((long long)d.C * d.R * ((d.S + 3) / 4 * 4) >= (1LL << 30)) return false;
-    }
     if (CFG::MODE == MODE_POINTWISE) {
         if (d.R != 1 || d.S != 1 || d.stride != 1 || d.pad != 0 || ((d.H * d.W) % 4) != 0) return false;
     }
@@ -704,8 +612,7 @@ bool igemm_valid(const Variant& v, const conv_desc& d, int OH, int OW)
     const long long pcap = ((P + 63) / 64) * 64;
     if (CFG::TN > pcap) return false;
     // a split must leave every part at least two reduction steps
-    const long long Qlay = CFG::MODE == MODE_SVEC ? (long long)d.C * d.R * ((d.S + 3) / 4 * 4) : Q;
-    const long long steps = (Qlay + CFG::TK - 1) / CFG::TK;
+    const long long steps = (Q + CFG::TK - 1) / CFG::TK;
     if (v.split > 1 && steps < 2LL * v.split) return false;
     if (v.split > 1 && (long long)d.K * P * 4 >= (1LL << 32)) return false;  // one split's partial sums: 32-bit offsets
     if (d.K > 65535LL * CFG::TM) return false;
