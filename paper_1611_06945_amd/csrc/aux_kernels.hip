@@ -1,7 +1,29 @@
 // Second pass of split-reduction variants, and the max-pool helper.
+#include <map>
+#include <mutex>
+#include <utility>
+
 #include "igemm_kernel.h"
 
 namespace convfwd {
+
+hipError_t ensure_dynamic_lds(const void* kernel, size_t bytes)
+{
+    static std::mutex mu;
+    static std::map<std::pair<int, const void*>, size_t> raised;  // (device, kernel) -> limit already set
+    if (bytes <= 48 * 1024) return hipSuccess;                    // within the default limit
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    std::lock_guard<std::mutex> g(mu);
+    size_t& have = raised[std::make_pair(dev, kernel)];
+    if (bytes > have) {
+        e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+        if (e != hipSuccess) return e;
+        have = bytes;
+    }
+    return hipSuccess;
+}
 
 // out[n,k,pix] = cvt(act(bias[k] + sum_z ws[z][k][p])), z in ascending order so the result does not depend on
 // scheduling (no floating-point atomics anywhere).  One thread per output element, pixels fastest.

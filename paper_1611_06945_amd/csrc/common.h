@@ -118,6 +118,10 @@ void register_wconv_f32(std::vector<Variant>& out);
 void register_wconv_f16(std::vector<Variant>& out);
 void register_wconv_bf16(std::vector<Variant>& out);
 
+// Raises a kernel's dynamic-LDS limit to `bytes` on the current device when it is not already that high (once per
+// device and kernel; safe to call from several threads).
+hipError_t ensure_dynamic_lds(const void* kernel, size_t bytes);
+
 // Split-reduction second pass and the max-pool helper (aux_kernels.hip).
 hipError_t launch_split_reduce(const ConvArgs& a, int dtype, hipStream_t s);
 hipError_t launch_maxpool(int N, int C, int H, int W, int win, int stride, int dtype, bool in_nhwc, bool out_nhwc,

@@ -239,13 +239,8 @@ template <class CFG, int PADMODE>
 hipError_t nhwc_launch(const Variant& v, ConvArgs& a, hipStream_t s)
 {
     constexpr size_t lds = nhwc_lds_bytes<CFG>();
-    static bool raised = false;  // once per process and kernel
-    if (lds > 48 * 1024 && !raised) {
-        const hipError_t e = hipFuncSetAttribute((const void*)nhwc_kernel<CFG, PADMODE>,
-                                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-        raised = true;
-    }
+    const hipError_t e = ensure_dynamic_lds((const void*)nhwc_kernel<CFG, PADMODE>, lds);
+    if (e != hipSuccess) return e;
     const int total_steps = (a.Q + CFG::TK - 1) / CFG::TK;
     a.nsplit = v.split;
     a.steps_per_split = (total_steps + v.split - 1) / v.split;

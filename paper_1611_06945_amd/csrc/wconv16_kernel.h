@@ -379,13 +379,8 @@ template <class CFG>
 hipError_t wconv16_launch(const Variant& v, ConvArgs& a, hipStream_t s)
 {
     const size_t lds = wconv16_lds_bytes<CFG>(a.H, a.W, a.pad, a.OH, a.OW);
-    static size_t lds_allowed = 0;
-    if (lds > lds_allowed) {
-        const hipError_t e = hipFuncSetAttribute((const void*)wconv16_kernel<CFG>,
-                                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-        lds_allowed = lds;
-    }
+    const hipError_t e = ensure_dynamic_lds((const void*)wconv16_kernel<CFG>, lds);
+    if (e != hipSuccess) return e;
     const Wconv16Geom g = wconv16_geom<CFG>(a.W, a.pad, a.OH, a.OW);
     const int total_chunks = a.C / CFG::CB;
     a.nsplit = v.split;

@@ -277,13 +277,8 @@ template <class CFG>
 hipError_t wconv_launch(const Variant& v, ConvArgs& a, hipStream_t s)
 {
     const size_t lds = wconv_lds_bytes<CFG>(a.H, a.W, a.pad);
-    static size_t lds_allowed = 0;  // raised once per process and kernel when a launch needs more than the default
-    if (lds > lds_allowed) {
-        const hipError_t e = hipFuncSetAttribute((const void*)wconv_kernel<CFG>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                                 (int)lds);
-        if (e != hipSuccess) return e;
-        lds_allowed = lds;
-    }
+    const hipError_t e = ensure_dynamic_lds((const void*)wconv_kernel<CFG>, lds);
+    if (e != hipSuccess) return e;
     const int total_chunks = a.C / CFG::CB;
     a.nsplit = v.split;
     a.steps_per_split = (total_chunks + v.split - 1) / v.split;
