@@ -64,7 +64,9 @@ void wconv_kernel(ConvArgs a)
     float* const Bs0 = smem + 2 * TM * LDA;          // [2][CB*PLANE]
     const int b_elems = CB * PLANE;
 
-    const int tid = threadIdx.x, lane = tid & 63, w = (tid >> 6) & 3, wn = tid >> 8, li = lane & 15, g = lane >> 4;
+    const int tid = threadIdx.x, lane = tid & 63, li = lane & 15, g = lane >> 4;
+    // wave-uniform by construction; saying so keeps the per-wave decisions below on the scalar unit
+    const int w = __builtin_amdgcn_readfirstlane((tid >> 6) & 3), wn = __builtin_amdgcn_readfirstlane(tid >> 8);
     const int nb0 = wn * NBW;  // first pixel block of this wave
     const int ntiles = (a.OHW + TNP - 1) / TNP;
     const int img = blockIdx.x / ntiles, ntile = blockIdx.x - img * ntiles;
@@ -114,12 +116,21 @@ void wconv_kernel(ConvArgs a)
 #pragma unroll
     for (int i = 0; i < LB; ++i) {
         const int v = i * NT + tid;
+        // the vector's first element by division, the other three by stepping (x, y, channel) with carries
+        uint32_t cl, pix, y, x;
+        a.dHW.divmod((uint32_t)(4 * v), cl, pix);
+        a.dW.divmod(pix, y, x);
+        int ci = (int)cl, yi = (int)y, xi = (int)x;
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-            uint32_t cl, pix, y, x;
-            a.dHW.divmod((uint32_t)(4 * v + e), cl, pix);
-            a.dW.divmod(pix, y, x);
-            b_idx[i][e] = v < nvecB ? (int)cl * PLANE + ((int)y + a.pad) * PW + (int)x + a.pad : -1;
+            b_idx[i][e] = v < nvecB ? ci * PLANE + (yi + a.pad) * PW + xi + a.pad : -1;
+            if (++xi == a.W) {
+                xi = 0;
+                if (++yi == a.H) {
+                    yi = 0;
+                    ++ci;
+                }
+            }
         }
     }
 
@@ -236,23 +247,38 @@ void wconv_kernel(ConvArgs a)
             }
         __syncthreads();
         constexpr int NE = (16 * TNP + NT - 1) / NT;  // outputs of this 16-row block per thread
+        // element j*NT + tid of the [16][TNP] block: row and column by one division, then by stepping
+        int rowj[NE], colj[NE];
+        {
+            int row = tid / TNP, col = tid - row * TNP;
+#pragma unroll
+            for (int j = 0; j < NE; ++j) {
+                rowj[j] = row;
+                colj[j] = col;
+                row += NT / TNP;
+                col += NT % TNP;
+                if (col >= TNP) {
+                    col -= TNP;
+                    ++row;
+                }
+            }
+        }
         float bs[NE];
 #pragma unroll
         for (int j = 0; j < NE; ++j) {  // all bias values first: one round trip instead of one per output
-            const int e = j * NT + tid;
-            bs[j] = buffer_load_elem<float>(rbias, (e < 16 * TNP && !split) ? (uint32_t)(m0 + mb * 16 + e / TNP) * 4u : kOutOfRange);
+            const bool in_block = ((j + 1) * NT <= 16 * TNP) ? true : (j * NT + tid < 16 * TNP);
+            bs[j] = buffer_load_elem<float>(rbias, (in_block && !split) ? (uint32_t)(m0 + mb * 16 + rowj[j]) * 4u : kOutOfRange);
         }
 #pragma unroll
         for (int j = 0; j < NE; ++j) {
-            const int e = j * NT + tid;
-            const int idx = e < 16 * TNP ? e : 0;
-            const int row = idx / TNP, col = idx % TNP;
-            float x = red[row * TNP + col];
-            x += red[(16 + row) * TNP + col];
-            x += red[(32 + row) * TNP + col];
-            x += red[(48 + row) * TNP + col];
-            const int k = m0 + mb * 16 + row, n = n0 + col;
-            const bool ok = e < 16 * TNP && k < a.K && n < a.OHW;
+            const bool in_block = ((j + 1) * NT <= 16 * TNP) ? true : (j * NT + tid < 16 * TNP);
+            const int idx = in_block ? j * NT + tid : 0;
+            float x = red[idx];
+            x += red[16 * TNP + idx];
+            x += red[32 * TNP + idx];
+            x += red[48 * TNP + idx];
+            const int k = m0 + mb * 16 + rowj[j], n = n0 + colj[j];
+            const bool ok = in_block && k < a.K && n < a.OHW;
             if (split) {
                 buffer_store_elem<float>(x, rws, ok ? (uint32_t)(k * a.P + img * a.OHW + n) * 4u : kOutOfRange);
             } else {
