@@ -52,6 +52,7 @@ State& state()
         register_nhwc_f16(s->variants);
         register_nhwc_bf16(s->variants);
         register_wconv_f32(s->variants);
+        register_wino_f32(s->variants);
         register_wconv_f16(s->variants);
         register_wconv_bf16(s->variants);
         for (size_t i = 0; i < s->variants.size(); ++i) s->by_name[s->variants[i].name] = (int)i;
@@ -118,6 +119,7 @@ std::vector<int> valid_list(State& st, const conv_desc& d, int OH, int OW)
 
 size_t ws_bytes_of(const Variant& v, const conv_desc& d, int OH, int OW)
 {
+    if (v.ws_extra) return v.ws_extra(v, d, OH, OW);
     if (v.split <= 1) return 0;
     return (size_t)v.split * (size_t)d.K * (size_t)d.N * OH * OW * sizeof(float);
 }
@@ -130,6 +132,7 @@ double heuristic_cost(const Variant& v, const conv_desc& d, int OH, int OW)
 {
     const double P = (double)d.N * OH * OW, Q = (double)d.C * d.R * d.S;
     if (v.family == FAM_FC) return 1.0 + std::abs(v.tm - 4);  // weight streaming: always ahead of the MFMA tiles when valid
+    if (v.family == FAM_WINOGRAD) return 1.0e30;              // chosen by measurement only
     const double tiles = std::ceil(d.K / (double)v.tm) * std::ceil(P / (double)v.tn) * v.split;
     const double steps = std::ceil(std::ceil(Q / v.tk) / v.split);
     const double wg_per_cu = (v.tm * v.tn >= 128 * 128) ? 1.0 : (v.tm * v.tn >= 64 * 128) ? 2.0 : 3.0;

@@ -83,11 +83,13 @@ struct ConvArgs {
     FastDiv dRS, dS, dOHW, dOW, dHW, dW;
     FastDiv dRSP, dSP, dRSP4, dSP4;  // by R*SP, SP = 4*SP4, R*SP4, SP4
     FastDiv dC;                      // by C (channel-innermost reduction axis)
+    FastDiv dX, dY, dZ;              // set by the launcher of the kernel family that needs them
 };
 
 struct Variant;
 typedef hipError_t (*LaunchFn)(const Variant& v, ConvArgs& a, hipStream_t s);
 typedef bool (*ValidFn)(const Variant& v, const conv_desc& d, int OH, int OW);
+typedef size_t (*WorkspaceFn)(const Variant& v, const conv_desc& d, int OH, int OW);
 
 // One compiled kernel configuration (the paper's "variant + tuning parameters").
 struct Variant {
@@ -100,9 +102,10 @@ struct Variant {
     int specificity;   // higher = written for a narrower class of shapes (heuristic tie-break)
     ValidFn valid;
     LaunchFn launch;
+    WorkspaceFn ws_extra = nullptr;  // workspace the variant needs beyond split partial sums (null: none)
 };
 
-enum { FAM_IGEMM = 0, FAM_POINTWISE = 1, FAM_FIRSTLAYER = 2, FAM_WINDOW = 3, FAM_FC = 4, FAM_NHWC = 5 };
+enum { FAM_IGEMM = 0, FAM_POINTWISE = 1, FAM_FIRSTLAYER = 2, FAM_WINDOW = 3, FAM_FC = 4, FAM_NHWC = 5, FAM_WINOGRAD = 6 };
 
 // Each kernel file appends its variants.
 void register_igemm_f32(std::vector<Variant>& out);
@@ -117,6 +120,7 @@ void register_nhwc_bf16(std::vector<Variant>& out);
 void register_wconv_f32(std::vector<Variant>& out);
 void register_wconv_f16(std::vector<Variant>& out);
 void register_wconv_bf16(std::vector<Variant>& out);
+void register_wino_f32(std::vector<Variant>& out);
 
 // Raises a kernel's dynamic-LDS limit to `bytes` on the current device when it is not already that high (once per
 // device and kernel; safe to call from several threads).

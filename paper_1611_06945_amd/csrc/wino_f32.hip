@@ -1,0 +1,22 @@
+// Instantiations of the Winograd F(2x2, 3x3) kernel (fp32, 3x3 stride-1 layers).
+#include "wino_kernel.h"
+
+namespace convfwd {
+
+void register_wino_f32(std::vector<Variant>& out)
+{
+    //                    MBLK NBLK XW LBE     TM x TT tiles, planes per wave, staging slots per thread
+    wino_register<WinoCfg<2, 3, 2, 1>>(out);
+    wino_register<WinoCfg<2, 3, 2, 2>>(out);
+    wino_register<WinoCfg<2, 2, 2, 1>>(out);
+    wino_register<WinoCfg<2, 2, 2, 2>>(out);
+    wino_register<WinoCfg<4, 2, 2, 1>>(out);
+    wino_register<WinoCfg<4, 2, 2, 2>>(out);
+    wino_register<WinoCfg<2, 4, 2, 1>>(out);
+    wino_register<WinoCfg<2, 4, 2, 2>>(out);
+    wino_register<WinoCfg<1, 2, 2, 1>>(out);
+    wino_register<WinoCfg<1, 3, 2, 1>>(out);
+    wino_register<WinoCfg<3, 2, 2, 1>>(out);
+}
+
+}  // namespace convfwd
