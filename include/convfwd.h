@@ -81,8 +81,9 @@ double conv_flops(const conv_desc* desc);
 
 /*
  * Bytes of device workspace with which every variant valid for `desc` can run
- * (split-reduction variants keep fp32 partial sums there).  conv_fwd() needs
- * none.  Returns 0 for an invalid descriptor.
+ * (split-reduction variants keep fp32 partial sums there, the Winograd variants
+ * the transformed filters).  conv_fwd() needs none.  Returns 0 for an invalid
+ * descriptor.
  */
 size_t conv_workspace_bytes(const conv_desc* desc);
 
@@ -95,11 +96,14 @@ int conv_fwd(const conv_desc* desc, const void* in, const void* filt, const floa
              void* stream);
 
 /*
- * As conv_fwd, but may also pick a split-reduction variant (paper, Section 3
- * "Variant Selection and Autotuning": several variants per operation), whose
- * partial sums go to `workspace` (device memory, 256-byte aligned, contents
- * undefined afterwards) and are then reduced in a fixed order, so results are
- * bit-reproducible.  If `workspace_bytes` is too small for the selected variant
+ * As conv_fwd, but may also pick a variant that needs scratch memory (paper,
+ * Section 3 "Variant Selection and Autotuning": several variants per
+ * operation): a split-reduction variant, whose partial sums go to `workspace`
+ * (device memory, 256-byte aligned, contents undefined afterwards) and are then
+ * reduced in a fixed order, or, for fp32 3x3 stride-1 layers, a Winograd
+ * F(2x2,3x3) variant (the algorithm the paper names as its main open topic,
+ * Section 4 "Experimental Results"), which first writes the transformed filters
+ * there.  Results are bit-reproducible either way.  If `workspace_bytes` is too small for the selected variant
  * the best variant that fits is used instead; CONV_EWORKSPACE only if a forced
  * variant does not fit.
  */
@@ -129,7 +133,7 @@ int conv_variant_count(const conv_desc* desc);
  */
 int conv_variant_name(const conv_desc* desc, int idx, char* buf, size_t n);
 
-/* Workspace bytes variant `idx` of `desc` needs (0 for unsplit variants); negative conv_status on error. */
+/* Workspace bytes variant `idx` of `desc` needs (0 for unsplit direct variants); negative conv_status on error. */
 long long conv_variant_workspace(const conv_desc* desc, int idx);
 
 /* Force variant `idx` for this exact descriptor in later conv_fwd/conv_fwd_ws calls (tests run every variant this

@@ -5,18 +5,18 @@ namespace convfwd {
 
 void register_wino_f32(std::vector<Variant>& out)
 {
-    //                    MBLK NBLK XW LBE     TM x TT tiles, planes per wave, staging slots per thread
-    wino_register<WinoCfg<2, 3, 2, 1>>(out);
-    wino_register<WinoCfg<2, 3, 2, 2>>(out);
-    wino_register<WinoCfg<2, 2, 2, 1>>(out);
-    wino_register<WinoCfg<2, 2, 2, 2>>(out);
-    wino_register<WinoCfg<4, 2, 2, 1>>(out);
-    wino_register<WinoCfg<4, 2, 2, 2>>(out);
-    wino_register<WinoCfg<2, 4, 2, 1>>(out);
-    wino_register<WinoCfg<2, 4, 2, 2>>(out);
-    wino_register<WinoCfg<1, 2, 2, 1>>(out);
-    wino_register<WinoCfg<1, 3, 2, 1>>(out);
-    wino_register<WinoCfg<3, 2, 2, 1>>(out);
+    //                    MBLK NBLK XW LBE CB     TM x TT tiles, planes per wave, staging slots per thread, channels per step
+    wino_register<WinoCfg<2, 3, 2, 1, 8>>(out);
+    wino_register<WinoCfg<2, 3, 2, 2, 8>>(out);
+    wino_register<WinoCfg<3, 2, 2, 1, 8>>(out);
+    wino_register<WinoCfg<3, 2, 2, 2, 8>>(out);
+    wino_register<WinoCfg<2, 2, 2, 1, 8>>(out);
+    wino_register<WinoCfg<2, 2, 2, 2, 8>>(out);
+    wino_register<WinoCfg<2, 2, 2, 1, 16>>(out);
+    wino_register<WinoCfg<1, 2, 2, 1, 16>>(out);
+    wino_register<WinoCfg<1, 3, 2, 1, 8>>(out);
+    wino_register<WinoCfg<4, 2, 2, 1, 8>>(out);
+    wino_register<WinoCfg<2, 4, 2, 2, 8>>(out);
 }
 
 }  // namespace convfwd

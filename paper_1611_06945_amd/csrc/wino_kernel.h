@@ -8,12 +8,13 @@
 //     M[xi][k][t] = sum_c U[xi][k][c] * V[xi][c][t],    xi = 0..15, t = tile index over (image, tile row, tile column)
 // with 2.25 times fewer multiplications than the direct form.  On this GPU the fp32 MFMA rate is what bounds the direct
 // kernels while the vector ALU, LDS and L2 have slack, so the transforms are done inside the product kernel:
-//   * U = G g G^T is computed once per call by a small kernel into the workspace, laid out [C/8][16][8][K'] (K' = K rounded
-//     up to a multiple of 4) so that the slab a workgroup needs per step is 128 contiguous runs of TM floats;
-//   * a workgroup owns TM output channels x TT consecutive tiles and walks the input channels 8 at a time.  Per step
+//   * U = G g G^T is computed once per call by a small kernel into the workspace, laid out so that a lane's MFMA
+//     operands of one step are one contiguous 8- or 16-byte load.  Every plane xi belongs to exactly one wave, so the
+//     transformed filters go from global memory straight into that wave's registers: no LDS staging;
+//   * a workgroup owns TM output channels x TT consecutive tiles and walks the input channels CB at a time.  Per step
 //     the input rows its tiles touch are copied into LDS with their zero border (coalesced loads, the positions are the
 //     same in every step), each (tile, channel) is transformed by one thread (32 additions) into V[xi][channel][tile],
-//     and every wave multiplies its share of the 16 xi planes: per plane MBLK x NBLK blocks of 16x16, two MFMAs each;
+//     and every wave multiplies its share of the 16 xi planes: per plane MBLK x NBLK blocks of 16x16, CB/4 MFMAs each;
 //   * at the end the 16 planes meet in LDS, each (channel, tile) is transformed back by one thread (24 additions) and
 //     its 2x2 outputs leave with bias and activation applied.
 // Every sum is taken in a fixed order: results are bit-reproducible.  Products of small integers stay exact (the
@@ -26,24 +27,20 @@
 
 namespace convfwd {
 
-template <int MBLK_, int NBLK_, int XW_, int LBE_>
+template <int MBLK_, int NBLK_, int XW_, int LBE_, int CB_>
 struct WinoCfg {
-    static constexpr int MBLK = MBLK_, NBLK = NBLK_, XW = XW_, LBE = LBE_;
+    static constexpr int MBLK = MBLK_, NBLK = NBLK_, XW = XW_, LBE = LBE_, CB = CB_;
     static constexpr int WAVES = 16 / XW;        // every wave owns XW of the 16 transform planes
     static constexpr int NT = 64 * WAVES;
     static constexpr int TM = 16 * MBLK;         // output channels per workgroup
     static constexpr int TT = 16 * NBLK;         // tiles (2x2 output blocks) per workgroup
-    static constexpr int CB = 8;                 // input channels per step
-    // LDS operand buffers are [16 planes][8 channels][rows]: the 16 lanes that feed one channel of an MFMA read 16
-    // consecutive floats, and the row pitch is 16 mod 32 so that the four channel groups of a wave use different banks
-    static constexpr int AP = TM + (TM % 32 == 0 ? 16 : 0);
+    static constexpr int HN = CB / 4;            // MFMAs per block and step (4 channels each)
+    // The transformed tiles are [16 planes][CB channels][tiles] in LDS: the 16 lanes that feed one channel of an MFMA
+    // read 16 consecutive floats, and the pitch is 16 mod 32 so that the four channel groups of a wave use different banks
     static constexpr int VP = TT + (TT % 32 == 0 ? 16 : 0);
-    static constexpr int A_FLOATS = 16 * CB * AP;  // one buffer of transformed filters [16][8][AP]
-    static constexpr int V_FLOATS = 16 * CB * VP;  // one buffer of transformed tiles   [16][8][VP]
-    static constexpr int A_VECS = 16 * CB * TM / 4;  // 16-byte vectors of one step's filter slab
+    static constexpr int V_FLOATS = 16 * CB * VP;  // one buffer of transformed tiles
     static constexpr int MP = TT + 4;            // row pitch of the plane buffer of the epilogue (4 mod 8: conflict-free writes)
-    static constexpr CoopPlan planA = coop_plan(NT, A_VECS);
-    static_assert(16 % XW == 0 && TT * CB <= NT, "one transform task per thread");
+    static_assert(16 % XW == 0 && (CB == 8 || CB == 16) && TT * CB <= NT, "one transform task per thread");
 };
 
 struct WinoGeom {
@@ -52,8 +49,7 @@ struct WinoGeom {
     int tiles;       // N * tiles_img
     int nr_max;      // tile rows (of any images) one workgroup's tiles can touch
     int PWL;         // floats per staged input row: 2*TW + 2 (even)
-    int raw_chan;    // floats per channel of the staged rows: nr_max * 4 * PWL, padded to 4 mod 32 so that the 8 channels
-                     // x 2 neighbouring tiles read together by 16 lanes fall on 16 different pairs of LDS banks
+    int raw_chan;    // floats per channel of the staged rows: nr_max * 4 * PWL, padded to 4 mod 32
 };
 
 template <class CFG>
@@ -75,51 +71,76 @@ template <class CFG>
 size_t wino_lds_bytes(int N, int OH, int OW)
 {
     const WinoGeom g = wino_geom<CFG>(N, OH, OW);
-    const size_t pipe = sizeof(float) * (2 * (size_t)CFG::A_FLOATS + 2 * (size_t)CFG::V_FLOATS + 2 * (size_t)CFG::CB * g.raw_chan);
+    const size_t pipe = sizeof(float) * (2 * (size_t)CFG::V_FLOATS + 2 * (size_t)CFG::CB * g.raw_chan);
     const size_t epi = sizeof(float) * 16 * (size_t)CFG::TM * CFG::MP;
     return pipe > epi ? pipe : epi;
 }
 
-// ConvArgs::dX, dY, dZ carry the divisions by TW, TH and TH*TW for this family.
-
 __host__ __device__ inline int wino_kpitch(int K) { return (K + 3) & ~3; }
 
-// U[c/8][xi][c%8][k] = (G g G^T)[xi / 4][xi % 4] of filter (k, c), rows K' = wino_kpitch(K) floats long;
-// G = [1 0 0; 1/2 1/2 1/2; 1/2 -1/2 1/2; 0 0 1].  A workgroup transforms 32 output channels x 8 input channels: the
-// 32 x 72 filter values are read as contiguous runs into LDS, and each thread then owns one (k, c) with k along the lanes,
-// so that reads and writes of global memory are both made of contiguous runs.
-__global__ __launch_bounds__(256) void wino_filter_kernel(const float* __restrict__ filt, float* __restrict__ U, int K, int C)
+// ConvArgs::dX, dY, dZ carry the divisions by TW, TH and TH*TW for this family.
+
+// Filter transform.  With HN = CB/4 and K' = wino_kpitch(K), the workspace holds
+//     U[c / CB][xi][q][k][h] = (G g G^T)[xi / 4][xi % 4] of filter (k, c),   c % CB = q + 4*h,  q = 0..3, h = 0..HN-1
+// (G = [1 0 0; 1/2 1/2 1/2; 1/2 -1/2 1/2; 0 0 1]): MFMA lane group q of a wave consumes channel q + 4*h in its h-th MFMA
+// of a step, so the HN values it needs for one output channel are adjacent.  A workgroup (32 output channels x 4 lane
+// groups) transforms 32 x CB filters: their values are read as contiguous runs into LDS, all loads in flight at once,
+// and thread (k, q) then writes the HN adjacent values of each plane as one vector, k along the lanes.
+template <int CB>
+__global__ __launch_bounds__(128) void wino_filter_kernel(const float* __restrict__ filt, float* __restrict__ U, int K, int C)
 {
-    __shared__ float g_s[32 * 73];  // row pitch 73: the lanes' strided reads fall on different banks
+    constexpr int HN = CB / 4, ROW = CB * 9 + 1;  // odd row pitch: the lanes' strided reads fall on different banks
+    constexpr int NLOAD = 32 * CB * 9 / 128;
+    __shared__ float g_s[32 * ROW];
     const int tid = threadIdx.x;
     const int k0 = blockIdx.x * 32, cb = blockIdx.y;
-    for (int e = tid; e < 32 * 72; e += 256) {
-        const int kl = e / 72, j = e - kl * 72;
-        g_s[kl * 73 + j] = (k0 + kl < K) ? filt[((size_t)(k0 + kl) * C + cb * 8) * 9 + j] : 0.0f;
+    float v[NLOAD];
+#pragma unroll
+    for (int i = 0; i < NLOAD; ++i) {
+        const int e = i * 128 + tid;
+        const int kl = e / (CB * 9), j = e - kl * (CB * 9);
+        v[i] = (k0 + kl < K) ? filt[((size_t)(k0 + kl) * C + cb * CB) * 9 + j] : 0.0f;
+    }
+#pragma unroll
+    for (int i = 0; i < NLOAD; ++i) {
+        const int e = i * 128 + tid;
+        const int kl = e / (CB * 9), j = e - kl * (CB * 9);
+        g_s[kl * ROW + j] = v[i];
     }
     __syncthreads();
-    const int kl = tid & 31, c8 = tid >> 5;
+    const int kl = tid & 31, q = tid >> 5;
     if (k0 + kl >= K) return;
-    const float* g = g_s + kl * 73 + c8 * 9;
-    float gg[4][3];
-#pragma unroll
-    for (int j = 0; j < 3; ++j) {
-        const float g0 = g[j], g1 = g[3 + j], g2 = g[6 + j];
-        gg[0][j] = g0;
-        gg[1][j] = 0.5f * ((g0 + g2) + g1);
-        gg[2][j] = 0.5f * ((g0 + g2) - g1);
-        gg[3][j] = g2;
-    }
     const size_t kp = (size_t)wino_kpitch(K);
-    float* dst = U + ((size_t)cb * 16 * 8 + c8) * kp + k0 + kl;
-    const size_t plane = 8 * kp;
+    float u[16][HN];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const float a0 = gg[i][0], a1 = gg[i][1], a2 = gg[i][2];
-        dst[(4 * i + 0) * plane] = a0;
-        dst[(4 * i + 1) * plane] = 0.5f * ((a0 + a2) + a1);
-        dst[(4 * i + 2) * plane] = 0.5f * ((a0 + a2) - a1);
-        dst[(4 * i + 3) * plane] = a2;
+    for (int h = 0; h < HN; ++h) {
+        const float* g = g_s + kl * ROW + (q + 4 * h) * 9;
+        float gg[4][3];
+#pragma unroll
+        for (int j = 0; j < 3; ++j) {
+            const float g0 = g[j], g1 = g[3 + j], g2 = g[6 + j];
+            gg[0][j] = g0;
+            gg[1][j] = 0.5f * ((g0 + g2) + g1);
+            gg[2][j] = 0.5f * ((g0 + g2) - g1);
+            gg[3][j] = g2;
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const float a0 = gg[i][0], a1 = gg[i][1], a2 = gg[i][2];
+            u[4 * i + 0][h] = a0;
+            u[4 * i + 1][h] = 0.5f * ((a0 + a2) + a1);
+            u[4 * i + 2][h] = 0.5f * ((a0 + a2) - a1);
+            u[4 * i + 3][h] = a2;
+        }
+    }
+    float* dst = U + (((size_t)cb * 16 * 4 + q) * kp + k0 + kl) * HN;
+    const size_t plane = 4 * kp * HN;
+#pragma unroll
+    for (int xi = 0; xi < 16; ++xi) {
+        if constexpr (HN == 2)
+            *(float2*)&dst[xi * plane] = make_float2(u[xi][0], u[xi][1]);
+        else
+            *(float4*)&dst[xi * plane] = make_float4(u[xi][0], u[xi][1], u[xi][2], u[xi][3]);
     }
 }
 
@@ -127,40 +148,44 @@ template <class CFG>
 __global__ __launch_bounds__(CFG::NT) void wino_kernel(ConvArgs a)
 {
     constexpr int MBLK = CFG::MBLK, NBLK = CFG::NBLK, XW = CFG::XW, LBE = CFG::LBE, NT = CFG::NT, TM = CFG::TM, TT = CFG::TT;
-    constexpr int CB = CFG::CB, A_FLOATS = CFG::A_FLOATS, V_FLOATS = CFG::V_FLOATS, MP = CFG::MP, AP = CFG::AP, VP = CFG::VP;
-    constexpr int A_VECS = CFG::A_VECS;
-    constexpr CoopPlan planA = CFG::planA;
+    constexpr int CB = CFG::CB, HN = CFG::HN, V_FLOATS = CFG::V_FLOATS, MP = CFG::MP, VP = CFG::VP;
     constexpr uint32_t kFar = 0x80000000u;  // tensors stay below 2 GiB: this offset plus any in-range scalar offset is out of range
     typedef Mma<CONV_F32, 16> mma_t;
     extern __shared__ __attribute__((aligned(16))) float smem[];
 
     const WinoGeom geo = wino_geom<CFG>(a.N, a.OH, a.OW);
-    const int TW = geo.TW, PWL = geo.PWL, raw_chan = geo.raw_chan;
-    float* const As0 = smem;                      // [2][16][8][AP]
-    float* const Vs0 = As0 + 2 * A_FLOATS;        // [2][16][8][VP]
-    float* const Rs0 = Vs0 + 2 * V_FLOATS;        // [2][8][raw_chan]: rows [nr_max][4][PWL] per channel
+    const int PWL = geo.PWL, raw_chan = geo.raw_chan;
+    float* const Vs0 = smem;                      // [2][16][CB][VP]
+    float* const Rs0 = Vs0 + 2 * V_FLOATS;        // [2][CB][raw_chan]: rows [nr_max][4][PWL] per channel
 
     const int tid = threadIdx.x, lane = tid & 63, li = lane & 15, kq = lane >> 4;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int t0 = blockIdx.x * TT, m0 = blockIdx.y * TM;
+    // Workgroup -> (channel tile, tile group).  Workgroups are dealt round-robin to the 8 XCDs, each with its own L2, so the
+    // ids an XCD receives (id % 8 fixed) are mapped to one contiguous run of the order "groups of 3 channel tiles; within a
+    // group all tile groups; within a tile group the 3 channel tiles": an XCD then touches about 3 channel tiles of the
+    // transformed filters and an eighth-to-a-quarter of the images instead of everything.
+    int t0, m0;
+    {
+        const int KT = (a.K + TM - 1) / TM, TN = (geo.tiles + TT - 1) / TT, total = KT * TN;
+        const int x = blockIdx.x & 7, j = blockIdx.x >> 3;
+        const int s = x * (total >> 3) + (x < (total & 7) ? x : (total & 7)) + j;  // runs in XCD order, sized as the hardware deals them
+        const int per_group = 3 * TN;
+        const int g = s / per_group, rem = s - g * per_group;
+        const int gs = (KT - 3 * g) < 3 ? (KT - 3 * g) : 3;
+        const int tg = rem / gs, kk = rem - tg * gs;
+        t0 = tg * TT;
+        m0 = (3 * g + kk) * TM;
+    }
     const int chunks = a.C / CB;
 
     const __amdgpu_buffer_rsrc_t rin = make_rsrc(a.in, a.in_bytes);
     const int kp = wino_kpitch(a.K);
     const __amdgpu_buffer_rsrc_t ru = make_rsrc(a.ws, (uint32_t)kp * (uint32_t)a.C * 64u);
 
-    // ---- transformed filters: per step 16 planes x 8 channels x TM consecutive floats, moved as 16-byte vectors ---------
-    uint32_t u_off[planA.loads];
-    int u_lds[planA.loads];
-#pragma unroll
-    for (int i = 0; i < planA.loads; ++i) {
-        const int v = i * NT + tid;
-        const int pc = v / (TM / 4), r4 = v % (TM / 4);  // (plane, channel) pair and group of four rows
-        const bool in_tile = (i + 1 < planA.loads || !planA.last_guarded) ? true : (v < A_VECS);
-        u_off[i] = in_tile ? (uint32_t)(pc * kp + m0 + 4 * r4) * 4u : kFar;
-        u_lds[i] = in_tile ? pc * AP + 4 * r4 : -1;
-    }
-    const uint32_t u_step = (uint32_t)kp * 512u;     // bytes between two steps' slabs
+    // ---- transformed filters: lane (li, kq) of the wave that owns plane xi loads U[step][xi][kq][m0 + mb*16 + li][0..HN) ----
+    const uint32_t u_off = (uint32_t)(((wave * XW * 4 + kq) * kp + m0 + li) * HN) * 4u;
+    const uint32_t u_plane = (uint32_t)(4 * kp * HN) * 4u;   // bytes between two planes
+    const uint32_t u_step = (uint32_t)kp * (uint32_t)(64 * CB);  // bytes between two steps
 
     // ---- input rows: the tile rows g_first .. g_last (index n*TH + ty) each need 4 input rows; element = (row, x) ----
     uint32_t g_first, t_in_row;
@@ -183,20 +208,35 @@ __global__ __launch_bounds__(CFG::NT) void wino_kernel(ConvArgs a)
     }
     const uint32_t chan_bytes = (uint32_t)a.HW * 4u;
 
-    // Two register sets: set (j & 1) carries the transformed filters of step j and the input rows of step j + 1 from
-    // global memory to LDS.  They are loaded at the top of step j - 2 and written to LDS in step j - 1, so more than a
-    // full step lies between a load and its first use (the transformed filters usually come from the memory-side
-    // cache, not from L2).
-    uint4 a_reg[2][planA.loads];
+    // Register sets are named by step parity.  Filter fragments of step j are loaded at the top of step j - 1; the input
+    // rows of step j are loaded at the top of step j - 3 and written to LDS in step j - 2 (transformed in step j - 1).
+    // All loads in the loop are unconditional: past the last step they fall outside the tensors (and read as zero) or on
+    // data that is never used.  A conditional load would force every later wait to assume it was skipped, i.e. to wait
+    // for everything in flight.
+    float af[2][XW][MBLK][HN], bf[2][XW][NBLK][HN];
     float r_reg[2][LBE][CB];
 
     auto load_filters = [&](auto setc, int chunk) {
         constexpr int set = decltype(setc)::value;
+        const uint32_t soff = (uint32_t)chunk * u_step;
 #pragma unroll
-        for (int i = 0; i < planA.loads; ++i) {
-            const u32x4 t = __builtin_amdgcn_raw_buffer_load_b128(ru, (int)u_off[i], (int)((uint32_t)chunk * u_step), 0);
-            a_reg[set][i] = make_uint4(t.x, t.y, t.z, t.w);
-        }
+        for (int x = 0; x < XW; ++x)
+#pragma unroll
+            for (int mb = 0; mb < MBLK; ++mb) {
+                const uint32_t off = u_off + (uint32_t)x * u_plane + (uint32_t)(mb * 16 * HN) * 4u;
+                if constexpr (HN == 2) {
+                    const float2 t = __builtin_bit_cast(float2, __builtin_amdgcn_raw_buffer_load_b64(ru, (int)off, (int)soff, 0));
+                    af[set][x][mb][0] = t.x;
+                    af[set][x][mb][1] = t.y;
+                } else {
+                    // (the whole vector is cast at once: a bit cast of a single vector element reads element 0)
+                    const float4 t = __builtin_bit_cast(float4, __builtin_amdgcn_raw_buffer_load_b128(ru, (int)off, (int)soff, 0));
+                    af[set][x][mb][0] = t.x;
+                    af[set][x][mb][1] = t.y;
+                    af[set][x][mb][2] = t.z;
+                    af[set][x][mb][3] = t.w;
+                }
+            }
     };
     auto load_rows = [&](auto setc, int chunk) {
         constexpr int set = decltype(setc)::value;
@@ -208,21 +248,17 @@ __global__ __launch_bounds__(CFG::NT) void wino_kernel(ConvArgs a)
                 r_reg[set][i][c] = __builtin_bit_cast(
                     float, __builtin_amdgcn_raw_buffer_load_b32(rin, (int)r_goff[i], (int)(c0_bytes + (uint32_t)c * chan_bytes), 0));
     };
-    auto store_filters = [&](auto setc, auto bufc) {
-        constexpr int set = decltype(setc)::value, buf = decltype(bufc)::value;
-        float* As = As0 + buf * A_FLOATS;
-#pragma unroll
-        for (int i = 0; i < planA.loads; ++i) {
-            if (u_lds[i] >= 0) *(uint4*)&As[u_lds[i]] = a_reg[set][i];
-        }
-    };
     auto store_rows = [&](auto setc, auto bufc) {
         constexpr int set = decltype(setc)::value, buf = decltype(bufc)::value;
 #pragma unroll
         for (int i = 0; i < LBE; ++i) {
             if (r_lds[i] >= 0) {
+                float* dst = Rs0 + buf * CB * raw_chan + r_lds[i];
 #pragma unroll
-                for (int c = 0; c < CB; ++c) Rs0[(buf * CB + c) * raw_chan + r_lds[i]] = r_reg[set][i][c];
+                for (int c = 0; c < CB; ++c) {
+                    *dst = r_reg[set][i][c];
+                    dst += raw_chan;
+                }
             }
         }
     };
@@ -289,32 +325,26 @@ __global__ __launch_bounds__(CFG::NT) void wino_kernel(ConvArgs a)
 #pragma unroll
                 for (int v = 0; v < 4; ++v) acc[x][mb][nb][v] = 0.0f;
 
-    // lane (li, kq) feeds row / column li of a block with channel kq (first MFMA) and kq + 4 (second MFMA);
-    // two fragment sets, named by step parity like the LDS buffers
-    float2 af[2][XW][MBLK], bf[2][XW][NBLK];
-    auto read_frags = [&](auto bufc) {
+    // lane (li, kq) feeds column li of a block with channel kq + 4*h in the h-th MFMA of a step
+    auto read_tiles = [&](auto bufc) {
         constexpr int buf = decltype(bufc)::value;
-        const float* As = As0 + buf * A_FLOATS + (wave * XW * CB + kq) * AP + li;
         const float* Vs = Vs0 + buf * V_FLOATS + (wave * XW * CB + kq) * VP + li;
 #pragma unroll
-        for (int x = 0; x < XW; ++x) {
-#pragma unroll
-            for (int mb = 0; mb < MBLK; ++mb)
-                af[buf][x][mb] = make_float2(As[x * CB * AP + mb * 16], As[(x * CB + 4) * AP + mb * 16]);
+        for (int x = 0; x < XW; ++x)
 #pragma unroll
             for (int nb = 0; nb < NBLK; ++nb)
-                bf[buf][x][nb] = make_float2(Vs[x * CB * VP + nb * 16], Vs[(x * CB + 4) * VP + nb * 16]);
-        }
+#pragma unroll
+                for (int h = 0; h < HN; ++h) bf[buf][x][nb][h] = Vs[(x * CB + 4 * h) * VP + nb * 16];
     };
-    // The step's products as NU units: unit u = (reduction element h, plane x, block mb, block nb), h outermost, so that
+    // The step's products as NU units: unit u = (reduction group h, plane x, block mb, block nb), h outermost, so that
     // consecutive MFMAs write different accumulators.
-    constexpr int NB1 = XW * MBLK * NBLK, NU = 2 * NB1;
+    constexpr int NB1 = XW * MBLK * NBLK, NU = HN * NB1;
     auto mma_range = [&](auto bufc, auto u0c, auto u1c) {
         constexpr int buf = decltype(bufc)::value, U0 = decltype(u0c)::value, U1 = decltype(u1c)::value;
 #pragma unroll
         for (int u = U0; u < U1; ++u) {
             const int h = u / NB1, x = (u % NB1) / (MBLK * NBLK), mb = (u % (MBLK * NBLK)) / NBLK, nb = u % NBLK;
-            acc[x][mb][nb] = mma_t::run(h ? af[buf][x][mb].y : af[buf][x][mb].x, h ? bf[buf][x][nb].y : bf[buf][x][nb].x, acc[x][mb][nb]);
+            acc[x][mb][nb] = mma_t::run(af[buf][x][mb][h], bf[buf][x][nb][h], acc[x][mb][nb]);
         }
     };
     typedef std::integral_constant<int, 0> c0_t;
@@ -324,15 +354,13 @@ __global__ __launch_bounds__(CFG::NT) void wino_kernel(ConvArgs a)
     typedef std::integral_constant<int, NU> u_c;
 
     // ---- pipeline -----------------------------------------------------------------------------------------------------
-    // entering step i: As[i&1], Vs[i&1] hold step i and fragment set i&1 was read from them; Rs[(i+1)&1] holds the rows of
-    // step i+1; register set (i+1)&1 holds the filters of step i+1 and the rows of step i+2.
+    // entering step i: Vs[i&1] holds the transformed tiles of step i and fragment set bf[i&1] was read from it; af[i&1]
+    // is in flight or loaded; Rs[(i+1)&1] holds the rows of step i+1; r_reg[(i+1)&1] holds the rows of step i+2.
     load_filters(c0_t{}, 0);
     load_rows(c0_t{}, 0);
-    load_filters(c1_t{}, 1);
     load_rows(c1_t{}, 1);
     for (int i = tid; i < 2 * CB * raw_chan; i += NT) Rs0[i] = 0.0f;  // border and unused rows stay zero for the whole kernel
     __syncthreads();
-    store_filters(c0_t{}, c0_t{});
     store_rows(c0_t{}, c0_t{});
     store_rows(c1_t{}, c1_t{});
     load_rows(c1_t{}, 2);
@@ -340,7 +368,7 @@ __global__ __launch_bounds__(CFG::NT) void wino_kernel(ConvArgs a)
     transform_read(c0_t{});
     transform_write(c0_t{});
     __syncthreads();
-    read_frags(c0_t{});
+    read_tiles(c0_t{});
 
     // One step, one barrier.  The products of step i surround the LDS traffic that prepares steps i+1 and i+2, and the
     // last quarter of them runs after the barrier, behind the reads of the next step's fragments.
@@ -348,25 +376,19 @@ __global__ __launch_bounds__(CFG::NT) void wino_kernel(ConvArgs a)
         constexpr int buf = decltype(bufc)::value;
         typedef std::integral_constant<int, buf ^ 1> other_t;
         const bool nxt = i + 1 < chunks, nxt2 = i + 2 < chunks;
-        // Issued unconditionally: past the last step the loads fall outside the tensors (and read as zero) or on data
-        // that is never used.  A conditional load would force the waits below to assume it was skipped, i.e. to wait
-        // for everything in flight, and the two-step distance between load and use would be lost.
-        load_filters(bufc, i + 2);
+        load_filters(other_t{}, i + 1);
         load_rows(bufc, i + 3);
         if (nxt) transform_read(other_t{});
         __builtin_amdgcn_sched_barrier(0);
         mma_range(bufc, c0_t{}, u_a{});
         __builtin_amdgcn_sched_barrier(0);
-        if (nxt) {
-            transform_write(other_t{});
-            store_filters(other_t{}, other_t{});
-        }
+        if (nxt) transform_write(other_t{});
         if (nxt2) store_rows(other_t{}, bufc);
         __builtin_amdgcn_sched_barrier(0);
         mma_range(bufc, u_a{}, u_b{});
         __builtin_amdgcn_sched_barrier(0);  // the products above cover the completion of the LDS writes before the barrier
         __syncthreads();
-        if (nxt) read_frags(other_t{});
+        if (nxt) read_tiles(other_t{});
         __builtin_amdgcn_sched_barrier(0);
         mma_range(bufc, u_b{}, u_c{});
     };
@@ -454,11 +476,11 @@ hipError_t wino_launch(const Variant& v, ConvArgs& a, hipStream_t s)
     a.dX = make_fastdiv((uint32_t)g.TW);
     a.dY = make_fastdiv((uint32_t)g.TH);
     a.dZ = make_fastdiv((uint32_t)g.tiles_img);
-    hipLaunchKernelGGL(wino_filter_kernel, dim3((unsigned)((a.K + 31) / 32), (unsigned)(a.C / 8)), dim3(256), 0, s, (const float*)a.filt,
-                       a.ws, a.K, a.C);
+    hipLaunchKernelGGL(wino_filter_kernel<CFG::CB>, dim3((unsigned)((a.K + 31) / 32), (unsigned)(a.C / CFG::CB)), dim3(128), 0, s,
+                       (const float*)a.filt, a.ws, a.K, a.C);
     hipError_t e2 = hipGetLastError();
     if (e2 != hipSuccess) return e2;
-    dim3 grid((unsigned)((g.tiles + CFG::TT - 1) / CFG::TT), (unsigned)((a.K + CFG::TM - 1) / CFG::TM));
+    dim3 grid((unsigned)(((g.tiles + CFG::TT - 1) / CFG::TT) * ((a.K + CFG::TM - 1) / CFG::TM)));
     hipLaunchKernelGGL(wino_kernel<CFG>, grid, dim3(CFG::NT), lds, s, a);
     return hipGetLastError();
 }
@@ -475,9 +497,9 @@ bool wino_valid(const Variant& v, const conv_desc& d, int OH, int OW)
     // offsets are formed in 32 bits next to an out-of-range marker: input and transformed filters below 2 GiB
     if ((long long)d.N * (d.C + 3 * CFG::CB) * d.H * d.W * 4 >= (1LL << 31)) return false;  // the pipeline looks three steps ahead
     if ((long long)wino_kpitch(d.K) * d.C * 64 >= (1LL << 31)) return false;
-    if (d.C / 8 > 65535) return false;
+    if (d.C / CFG::CB > 65535) return false;
     if ((long long)d.N * g.tiles_img >= (1LL << 30)) return false;
-    if (d.K > 65535LL * CFG::TM) return false;
+    if ((long long)((d.K + CFG::TM - 1) / CFG::TM) * ((g.tiles + CFG::TT - 1) / CFG::TT) >= (1LL << 31)) return false;
     return true;
 }
 
@@ -486,7 +508,7 @@ void wino_register(std::vector<Variant>& out)
 {
     Variant v;
     char buf[96];
-    snprintf(buf, sizeof buf, "wino_f32_M%dT%d_x%d_e%d", CFG::TM, CFG::TT, CFG::XW, CFG::LBE);
+    snprintf(buf, sizeof buf, "wino_f32_M%dT%d_x%d_c%d_e%d", CFG::TM, CFG::TT, CFG::XW, CFG::CB, CFG::LBE);
     v.name = buf;
     v.dtype = CONV_F32;
     v.split = 1;

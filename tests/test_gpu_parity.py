@@ -121,7 +121,12 @@ def test_identity_and_shifted_delta_filters(dtype):
                           relu=False, use_bias=False)
         for vi, name in enumerate(case.variant_names()):
             got = to_host_f64(case.run(variant=vi), dtype)
-            assert np.array_equal(got, case.ref()), (name, r0, s0)
+            if name.startswith("wino_"):
+                # the Winograd variants add and subtract neighbouring inputs before multiplying: on arbitrary floats a
+                # delta filter comes back within round-off, not bit for bit (a wrong orientation would be a gross error)
+                assert oracle.max_normalised_error(got, case.ref()) <= TOL[dtype], (name, r0, s0)
+            else:
+                assert np.array_equal(got, case.ref()), (name, r0, s0)
     f = np.zeros(shape.filt_shape(), dtype=np.float32)
     for c in range(16):
         f[c, c, 1, 1] = 1.0
