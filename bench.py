@@ -406,6 +406,22 @@ def main():
         n = B.conv_variant_count(r.desc)
         direct = [(B.conv_variant_time_us(r.desc, i), B.conv_variant_name(r.desc, i)) for i in range(n)]
         direct = [x for x in direct if not x[1].startswith("wino_") and x[0] > 0]
+        # the same layer with the filters handed over in the Winograd domain (the transform is then a conversion done
+        # once, ahead of time, as the paper does for constant weights): an extra figure, never the headline value
+        pre = B.desc_of(sh, w.dtype, relu=True, filt_winograd=True)
+        pre_names = [B.conv_variant_name(pre, i) for i in range(B.conv_variant_count(pre))]
+        if variant in pre_names:
+            x, f, b, o = r.sets[0]
+            u = torch.empty(B.conv_transformed_filter_bytes(pre), dtype=torch.uint8, device="cuda")
+            B.conv_transform_filters(pre, f, u)
+            B.conv_force_variant(pre, pre_names.index(variant))
+            try:
+                us = min(B.conv_time_us(pre, x, u, b, o, None, 0, launches=200) for _ in range(3))
+            finally:
+                B.conv_force_variant(pre, -1)
+            roof["pretransformed_filters"] = {"us": round(us, 2), "tflops": round(sh.flops / (us * 1e-6) / 1e12, 2),
+                                              "frac": round(sh.flops / (us * 1e-6) / 1e12 / PEAK_TFLOPS[dt], 5),
+                                              "frac_executed": round(executed / (us * 1e-6) / 1e12 / PEAK_TFLOPS[dt], 5)}
         if direct:
             t_us, nm = min(direct)
             roof["best_direct"] = {"variant": nm, "tuner_us": round(t_us, 2),

@@ -50,7 +50,13 @@ enum {
      * any other combination of these bits gives CONV_ENOVARIANT.  conv_convert_layout() converts tensors. */
     CONV_FLAG_IN_NHWC = 2u,
     CONV_FLAG_OUT_NHWC = 4u,
-    CONV_FLAG_FILT_KRSC = 8u
+    CONV_FLAG_FILT_KRSC = 8u,
+    /* Filters handed over in the Winograd F(2x2,3x3) domain, as written by conv_transform_filters() for the same
+     * descriptor (without this bit): at inference the weights are constants, so the filter transform is one of the
+     * conversions the paper does ahead of time (Section 3, "Graph-level Optimizations").  Only the Winograd variants
+     * serve such a descriptor (fp32, 3x3, stride 1, pad <= 1, C % 8 == 0; otherwise CONV_ENOVARIANT), and they then
+     * need no workspace.  Not combinable with the channel-innermost bits. */
+    CONV_FLAG_FILT_WINOGRAD = 16u
 };
 
 typedef enum {
@@ -196,6 +202,17 @@ int maxpool_fwd_layout(int32_t N, int32_t C, int32_t H, int32_t W, int32_t win, 
  * `stream`.  CONV_EINVAL for NULL/aliased pointers, extents < 1, A > 65535 or 2^31 or more elements.
  */
 int conv_convert_layout(int32_t A, int32_t B, int32_t S, int32_t dtype, const void* in, void* out, void* stream);
+
+/*
+ * Filter transform of the Winograd F(2x2,3x3) variants as an explicit, separately timed conversion: U = G g G^T for
+ * every (output channel, input channel) pair of the KCRS filter tensor `filt` (device, 16-byte aligned), written to
+ * `out` (device, 256-byte aligned, conv_transformed_filter_bytes(desc) bytes, layout private to the library), which
+ * is then passed as `filt` of a descriptor with CONV_FLAG_FILT_WINOGRAD set.  `desc` is the layer's descriptor with or
+ * without that bit.  conv_transformed_filter_bytes returns 0, conv_transform_filters CONV_ENOVARIANT, when no
+ * Winograd variant serves the descriptor; CONV_EINVAL for NULL or misaligned pointers.  Enqueued on `stream`.
+ */
+size_t conv_transformed_filter_bytes(const conv_desc* desc);
+int conv_transform_filters(const conv_desc* desc, const void* filt, void* out, void* stream);
 
 /*
  * Measured ceilings of the device, for reporting next to the published peaks (the paper's own practice of timing on

@@ -18,7 +18,7 @@ _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG, "libconvfwd.so")
 
 CONV_F32, CONV_F16, CONV_BF16 = 0, 1, 2
-CONV_FLAG_RELU, CONV_FLAG_IN_NHWC, CONV_FLAG_OUT_NHWC, CONV_FLAG_FILT_KRSC = 1, 2, 4, 8
+CONV_FLAG_RELU, CONV_FLAG_IN_NHWC, CONV_FLAG_OUT_NHWC, CONV_FLAG_FILT_KRSC, CONV_FLAG_FILT_WINOGRAD = 1, 2, 4, 8, 16
 CONV_OK, CONV_EINVAL, CONV_EDTYPE, CONV_EWORKSPACE, CONV_EHIP, CONV_ENOVARIANT, CONV_EIO = 0, -1, -2, -3, -4, -5, -6
 
 
@@ -99,6 +99,10 @@ def lib() -> ctypes.CDLL:
         L.conv_probe_mfma_peak.restype = ctypes.c_int
         L.conv_probe_stream_bandwidth.argtypes = [vp, vp, ctypes.c_size_t, vp, ctypes.POINTER(ctypes.c_double)]
         L.conv_probe_stream_bandwidth.restype = ctypes.c_int
+        L.conv_transformed_filter_bytes.argtypes = [dp]
+        L.conv_transformed_filter_bytes.restype = ctypes.c_size_t
+        L.conv_transform_filters.argtypes = [dp, vp, vp, vp]
+        L.conv_transform_filters.restype = ctypes.c_int
         L.conv_strerror.argtypes = [ctypes.c_int]
         L.conv_strerror.restype = ctypes.c_char_p
         _lib = L
@@ -110,10 +114,11 @@ def make_desc(N, C, H, W, K, R, S, stride=1, pad=0, dtype=CONV_F32, relu=False, 
     return conv_desc(N, C, H, W, K, R, S, stride, pad, dtype, f)
 
 
-def desc_of(shape, dtype=CONV_F32, relu=True, in_nhwc=False, out_nhwc=False, filt_krsc=False) -> conv_desc:
+def desc_of(shape, dtype=CONV_F32, relu=True, in_nhwc=False, out_nhwc=False, filt_krsc=False, filt_winograd=False) -> conv_desc:
     """conv_desc from a workloads.ConvShape (optionally with channel-innermost tensor formats)."""
     flags = ((CONV_FLAG_RELU if relu else 0) | (CONV_FLAG_IN_NHWC if in_nhwc else 0) |
-             (CONV_FLAG_OUT_NHWC if out_nhwc else 0) | (CONV_FLAG_FILT_KRSC if filt_krsc else 0))
+             (CONV_FLAG_OUT_NHWC if out_nhwc else 0) | (CONV_FLAG_FILT_KRSC if filt_krsc else 0) |
+             (CONV_FLAG_FILT_WINOGRAD if filt_winograd else 0))
     return make_desc(shape.N, shape.C, shape.H, shape.W, shape.K, shape.R, shape.S, shape.stride, shape.pad, dtype,
                      flags=flags)
 
@@ -240,6 +245,15 @@ def maxpool_fwd_layout(N, C, H, W, win, stride, dtype, in_nhwc, out_nhwc, inp, o
 def conv_convert_layout(A, Bdim, S, dtype, inp, out, stream=None) -> None:
     """out[a][s][b] = in[a][b][s]: (N,C,H*W) NCHW->NHWC, (N,H*W,C) NHWC->NCHW, (K,C,R*S) KCRS->KRSC."""
     _check(lib().conv_convert_layout(A, Bdim, S, dtype, _ptr(inp), _ptr(out), _stream(stream)), "conv_convert_layout")
+
+
+def conv_transformed_filter_bytes(desc) -> int:
+    return int(lib().conv_transformed_filter_bytes(ctypes.byref(desc)))
+
+
+def conv_transform_filters(desc, filt, out, stream=None) -> None:
+    """KCRS filters -> Winograd-domain filters for a descriptor with CONV_FLAG_FILT_WINOGRAD."""
+    _check(lib().conv_transform_filters(ctypes.byref(desc), _ptr(filt), _ptr(out), _stream(stream)), "conv_transform_filters")
 
 
 def conv_probe_mfma_peak(dtype: int, block: int, scratch, stream=None) -> float:

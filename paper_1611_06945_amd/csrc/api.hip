@@ -70,7 +70,7 @@ int hip_fail(hipError_t e, const char* what)
 }
 
 constexpr uint32_t kLayoutFlags = CONV_FLAG_IN_NHWC | CONV_FLAG_OUT_NHWC | CONV_FLAG_FILT_KRSC;
-constexpr uint32_t kKnownFlags = CONV_FLAG_RELU | kLayoutFlags;
+constexpr uint32_t kKnownFlags = CONV_FLAG_RELU | kLayoutFlags | CONV_FLAG_FILT_WINOGRAD;
 
 // Validation shared by every entry point; fills OH/OW.
 int check_desc(const conv_desc* d, int& OH, int& OW)
@@ -110,8 +110,11 @@ std::vector<int> valid_list(State& st, const conv_desc& d, int OH, int OW)
     std::vector<int> r;
     // descriptors with channel-innermost tensors are served by the kernels written for them, and only those
     const bool layout = (d.flags & kLayoutFlags) != 0;
+    const bool wino_filters = (d.flags & CONV_FLAG_FILT_WINOGRAD) != 0;
+    if (layout && wino_filters) return r;
     for (size_t i = 0; i < st.variants.size(); ++i) {
         if ((st.variants[i].family == FAM_NHWC) != layout) continue;
+        if (wino_filters && st.variants[i].family != FAM_WINOGRAD) continue;
         if (st.variants[i].valid(st.variants[i], d, OH, OW)) r.push_back((int)i);
     }
     return r;
@@ -204,6 +207,7 @@ void fill_args(ConvArgs& a, const conv_desc& d, int OH, int OW, const void* in, 
     a.RS = d.R * d.S;
     a.relu = (d.flags & CONV_FLAG_RELU) ? 1 : 0;
     a.out_nhwc = (d.flags & CONV_FLAG_OUT_NHWC) ? 1 : 0;
+    a.filt_wino = (d.flags & CONV_FLAG_FILT_WINOGRAD) ? 1 : 0;
     a.in_bytes = (uint32_t)((uint64_t)d.N * d.C * d.H * d.W * dtype_size(d.dtype));
     a.filt_bytes = (uint32_t)((uint64_t)d.K * d.C * d.R * d.S * dtype_size(d.dtype));
     a.out_bytes = (uint32_t)((uint64_t)d.N * d.K * OH * OW * dtype_size(d.dtype));
@@ -606,6 +610,31 @@ int conv_convert_layout(int32_t A, int32_t B, int32_t S, int32_t dtype, const vo
     if ((double)A * B * (double)S >= 2147483648.0 || (S + 31) / 32 > 2147483647 || (B + 31) / 32 > 65535) return CONV_EINVAL;
     const hipError_t e = launch_transpose(A, B, S, dtype_size(dtype), in, out, (hipStream_t)stream);
     if (e != hipSuccess) return hip_fail(e, "convert_layout");
+    return CONV_OK;
+}
+
+size_t conv_transformed_filter_bytes(const conv_desc* desc)
+{
+    int OH, OW;
+    if (check_desc(desc, OH, OW)) return 0;
+    conv_desc d = *desc;
+    d.flags = (d.flags & ~kLayoutFlags) | CONV_FLAG_FILT_WINOGRAD;
+    if (desc->flags & kLayoutFlags) return 0;
+    State& st = state();
+    std::lock_guard<std::mutex> g(st.mu);
+    if (valid_list(st, d, OH, OW).empty()) return 0;
+    return wino_transformed_filter_bytes(d.K, d.C);
+}
+
+int conv_transform_filters(const conv_desc* desc, const void* filt, void* out, void* stream)
+{
+    int OH, OW;
+    const int rc = check_desc(desc, OH, OW);
+    if (rc) return rc;
+    if (!filt || !out || !aligned16(filt) || (((uintptr_t)out) & 255u) || filt == out) return CONV_EINVAL;
+    if (conv_transformed_filter_bytes(desc) == 0) return CONV_ENOVARIANT;
+    const hipError_t e = launch_wino_filter_transform((const float*)filt, (float*)out, desc->K, desc->C, (hipStream_t)stream);
+    if (e != hipSuccess) return hip_fail(e, "transform_filters");
     return CONV_OK;
 }
 

@@ -77,6 +77,7 @@ struct ConvArgs {
     int QP;   // C*R*4*SP4: reduction extent with window rows padded to a multiple of 4 columns
     int relu;
     int out_nhwc;  // output is [N][OH][OW][K] instead of [N][K][OH][OW]
+    int filt_wino; // `filt` already holds the Winograd-domain filters (no transform kernel, no workspace)
     uint32_t in_bytes, filt_bytes, out_bytes;  // extents for the hardware bounds check of tile loads
     int nsplit;           // number of reduction splits (gridDim.z)
     int steps_per_split;  // reduction steps (of the kernel's own step size) per split
@@ -132,6 +133,9 @@ hipError_t launch_maxpool(int N, int C, int H, int W, int win, int stride, int d
                           const void* in, void* out, hipStream_t s);
 // out[a][s][b] = in[a][b][s] for elements of `esize` bytes (2 or 4): the layout conversions of tensors and filters
 hipError_t launch_transpose(int A, int B, int S, int esize, const void* in, void* out, hipStream_t s);
+// Winograd filter transform in the layout of the 8-channel-step variants (wino_f32.hip); bytes = 16 * K' * C * 4
+hipError_t launch_wino_filter_transform(const float* filt, float* out, int K, int C, hipStream_t s);
+size_t wino_transformed_filter_bytes(int K, int C);
 
 // Device ceilings measured in place (probe_kernels.hip).
 hipError_t probe_mfma(int dtype, int block, float* sink, hipStream_t s, double* tflops);

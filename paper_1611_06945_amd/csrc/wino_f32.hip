@@ -19,4 +19,12 @@ void register_wino_f32(std::vector<Variant>& out)
     wino_register<WinoCfg<2, 4, 2, 2, 8>>(out);
 }
 
+hipError_t launch_wino_filter_transform(const float* filt, float* out, int K, int C, hipStream_t s)
+{
+    hipLaunchKernelGGL(wino_filter_kernel<8>, dim3((unsigned)((K + 31) / 32), (unsigned)(C / 8)), dim3(128), 0, s, filt, out, K, C);
+    return hipGetLastError();
+}
+
+size_t wino_transformed_filter_bytes(int K, int C) { return (size_t)16 * wino_kpitch(K) * C * sizeof(float); }
+
 }  // namespace convfwd

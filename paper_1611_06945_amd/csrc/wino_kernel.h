@@ -461,6 +461,7 @@ __global__ __launch_bounds__(CFG::NT) void wino_kernel(ConvArgs a)
 template <class CFG>
 size_t wino_ws_bytes(const Variant& v, const conv_desc& d, int OH, int OW)
 {
+    if (d.flags & CONV_FLAG_FILT_WINOGRAD) return 0;  // the caller hands the transformed filters over
     return (size_t)16 * wino_kpitch(d.K) * d.C * sizeof(float);
 }
 
@@ -476,10 +477,14 @@ hipError_t wino_launch(const Variant& v, ConvArgs& a, hipStream_t s)
     a.dX = make_fastdiv((uint32_t)g.TW);
     a.dY = make_fastdiv((uint32_t)g.TH);
     a.dZ = make_fastdiv((uint32_t)g.tiles_img);
-    hipLaunchKernelGGL(wino_filter_kernel<CFG::CB>, dim3((unsigned)((a.K + 31) / 32), (unsigned)(a.C / CFG::CB)), dim3(128), 0, s,
-                       (const float*)a.filt, a.ws, a.K, a.C);
-    hipError_t e2 = hipGetLastError();
-    if (e2 != hipSuccess) return e2;
+    if (a.filt_wino) {
+        a.ws = (float*)const_cast<void*>(a.filt);  // already in the Winograd domain
+    } else {
+        hipLaunchKernelGGL(wino_filter_kernel<CFG::CB>, dim3((unsigned)((a.K + 31) / 32), (unsigned)(a.C / CFG::CB)), dim3(128), 0, s,
+                           (const float*)a.filt, a.ws, a.K, a.C);
+        const hipError_t e2 = hipGetLastError();
+        if (e2 != hipSuccess) return e2;
+    }
     dim3 grid((unsigned)(((g.tiles + CFG::TT - 1) / CFG::TT) * ((a.K + CFG::TM - 1) / CFG::TM)));
     hipLaunchKernelGGL(wino_kernel<CFG>, grid, dim3(CFG::NT), lds, s, a);
     return hipGetLastError();
@@ -490,6 +495,7 @@ bool wino_valid(const Variant& v, const conv_desc& d, int OH, int OW)
 {
     if (d.dtype != CONV_F32 || d.R != 3 || d.S != 3 || d.stride != 1 || d.pad > 1) return false;
     if ((d.C % CFG::CB) != 0) return false;
+    if ((d.flags & CONV_FLAG_FILT_WINOGRAD) && CFG::CB != 8) return false;  // the hand-over layout is that of the 8-channel step
     const WinoGeom g = wino_geom<CFG>(d.N, OH, OW);
     // every (input row of the workgroup's tile rows, x) needs a staging slot
     if ((long long)g.nr_max * 4 * d.W > (long long)CFG::NT * CFG::LBE) return false;

@@ -12,7 +12,7 @@ from paper_1611_06945_amd import binding as B
 from paper_1611_06945_amd import workloads as wl
 from paper_1611_06945_amd.workloads import ConvShape
 
-from gpu_util import TOL, DeviceCase, empty_out
+from gpu_util import TOL, DeviceCase, empty_out, to_host_f64, torch_mod
 from test_gpu_parity import assert_bit_exact, int_case, random_case, say
 
 pytestmark = pytest.mark.gpu
@@ -106,3 +106,31 @@ def test_not_offered_outside_its_domain():
         desc = B.desc_of(shape, dtype, relu=True)
         names = [B.conv_variant_name(desc, i) for i in range(B.conv_variant_count(desc))]
         assert names and not any(n.startswith("wino_") for n in names), (shape, dtype)
+
+
+def test_filters_handed_over_in_the_winograd_domain():
+    """conv_transform_filters + CONV_FLAG_FILT_WINOGRAD: same bits as the in-call transform, no workspace needed."""
+    torch = torch_mod()
+    for shape in [ConvShape(3, 16, 13, 13, 38, 3, 3, 1, 1), ConvShape(2, 24, 14, 10, 64, 3, 3, 1, 0)]:
+        case = random_case(shape, wl.F32, 1000)
+        pre = B.desc_of(shape, wl.F32, relu=True, filt_winograd=True)
+        nbytes = B.conv_transformed_filter_bytes(case.desc)
+        assert nbytes == B.conv_transformed_filter_bytes(pre) > 0
+        # poisoned: rows K..K' of the format are never written and must not matter
+        u = torch.full((nbytes // 4,), float("nan"), dtype=torch.float32, device="cuda")
+        B.conv_transform_filters(case.desc, case.d_filt, u)
+        names_pre = [B.conv_variant_name(pre, i) for i in range(B.conv_variant_count(pre))]
+        assert names_pre
+        plain_names = case.variant_names()
+        for vi, name in enumerate(names_pre):
+            say("  %s with pre-transformed filters on %s" % (name, shape))
+            out = empty_out(shape.out_shape(), wl.F32)
+            B.conv_force_variant(pre, vi)
+            try:
+                B.conv_fwd(pre, case.d_in, u, case.d_bias, out)   # no workspace
+                torch.cuda.synchronize()
+            finally:
+                B.conv_force_variant(pre, -1)
+            ref = case.run(variant=plain_names.index(name))       # the same variant transforming in the call
+            assert np.array_equal(out.cpu().numpy(), ref.cpu().numpy()), name
+            assert case.error(out) <= TOL[wl.F32]

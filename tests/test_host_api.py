@@ -52,7 +52,7 @@ def test_out_shape_of_benchmark_configs():
 
 
 @pytest.mark.parametrize("field,value", [("N", 0), ("C", 0), ("H", 0), ("W", -1), ("K", 0), ("R", 0), ("S", 0),
-                                         ("stride", 0), ("pad", -1), ("flags", 16)])
+                                         ("stride", 0), ("pad", -1), ("flags", 32)])
 def test_invalid_descriptor_fields(field, value):
     d = B.make_desc(1, 3, 8, 8, 4, 3, 3, 1, 1)
     setattr(d, field, value)
@@ -247,3 +247,47 @@ def test_layout_flags_select_only_channel_innermost_kernels():
     # fully connected shapes are offered the weight-streaming kernels
     fc = B.desc_of(ConvShape(5, 256, 6, 6, 4096, 6, 6, 1, 0), 0)
     assert B.conv_variant_name(fc, -1).startswith("fc_f32_")
+
+
+def test_winograd_variants_and_the_transformed_filter_format():
+    from paper_1611_06945_amd.workloads import ConvShape
+
+    sh = ConvShape(20, 256, 13, 13, 384, 3, 3, 1, 1)
+    plain = B.desc_of(sh, 0)
+    names = [B.conv_variant_name(plain, i) for i in range(B.conv_variant_count(plain))]
+    wino = [i for i, n in enumerate(names) if n.startswith("wino_")]
+    assert wino, names
+    # they keep the transformed filters (16 values per filter) in the caller's workspace ...
+    assert all(B.conv_variant_workspace(plain, i) == 16 * 384 * 256 * 4 for i in wino)
+    assert B.conv_workspace_bytes(plain) >= 16 * 384 * 256 * 4
+    # ... and are chosen by measurement only: without a tuned entry the direct kernels stay selected
+    assert not B.conv_variant_name(plain, -1).startswith("wino_")
+    # filters handed over in the Winograd domain: only those variants, no workspace, its own cache key
+    pre = B.desc_of(sh, 0, filt_winograd=True)
+    names_pre = [B.conv_variant_name(pre, i) for i in range(B.conv_variant_count(pre))]
+    assert names_pre and all(n.startswith("wino_") and "_c8_" in n for n in names_pre)
+    assert all(B.conv_variant_workspace(pre, i) == 0 for i in range(len(names_pre)))
+    assert B.conv_workspace_bytes(pre) == 0
+    assert B.conv_transformed_filter_bytes(plain) == B.conv_transformed_filter_bytes(pre) == 16 * 384 * 256 * 4
+    # K is padded to a multiple of 4 in that format
+    assert B.conv_transformed_filter_bytes(B.desc_of(ConvShape(1, 8, 9, 9, 10, 3, 3, 1, 1), 0)) == 16 * 12 * 8 * 4
+    L = B.lib()
+    for sh2, dt, kw in [(ConvShape(2, 16, 13, 13, 40, 3, 3, 1, 1), 1, {}),              # 16-bit storage
+                        (ConvShape(2, 16, 13, 13, 40, 5, 5, 1, 2), 0, {}),              # 5x5
+                        (ConvShape(2, 16, 13, 13, 40, 3, 3, 2, 1), 0, {}),              # stride 2
+                        (ConvShape(2, 12, 13, 13, 40, 3, 3, 1, 1), 0, {})]:             # C % 8 != 0
+        d = B.desc_of(sh2, dt, **kw)
+        assert B.conv_transformed_filter_bytes(d) == 0
+        assert L.conv_transform_filters(ctypes.byref(d), 256, 512, None) == B.CONV_ENOVARIANT
+        dw = B.desc_of(sh2, dt, filt_winograd=True)
+        assert B.conv_variant_count(dw) == 0
+        assert L.conv_fwd(ctypes.byref(dw), 256, 512, None, 1024, None) == B.CONV_ENOVARIANT
+    # not combinable with the channel-innermost formats
+    both = B.desc_of(sh, 0, filt_winograd=True, in_nhwc=True, filt_krsc=True)
+    assert B.conv_variant_count(both) == 0
+    assert B.conv_transformed_filter_bytes(B.desc_of(sh, 0, in_nhwc=True, filt_krsc=True)) == 0
+    # pointer checks come before any GPU call
+    assert L.conv_transform_filters(ctypes.byref(plain), None, 512, None) == B.CONV_EINVAL
+    assert L.conv_transform_filters(ctypes.byref(plain), 256, 520, None) == B.CONV_EINVAL   # output not 256-byte aligned
+    assert L.conv_transform_filters(ctypes.byref(plain), 256, 256, None) == B.CONV_EINVAL   # in place
+    assert L.conv_transform_filters(None, 256, 512, None) == B.CONV_EINVAL
