@@ -16,6 +16,8 @@ void register_wconv_f32(std::vector<Variant>& out)
     wconv_register<WCFG(3, 3, 1, 1, 11, 4, 1)>(out, sk);
     wconv_register<WCFG(3, 3, 1, 2, 13, 2, 2)>(out, sk);
     wconv_register<WCFG(3, 3, 1, 1, 13, 2, 2)>(out, sk);
+    // pixel tiles of half a 13x13 or 14x14 image: twice the workgroups for small batches without a split reduction
+    wconv_register<WCFG(3, 3, 1, 1, 6, 2, 2)>(out, sk);
 }
 
 }  // namespace convfwd

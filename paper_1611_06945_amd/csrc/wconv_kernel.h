@@ -324,7 +324,7 @@ bool wconv_valid(const Variant& v, const conv_desc& d, int OH, int OW)
     if (wconv_lds_bytes<CFG>(d.H, d.W, d.pad) > 160 * 1024) return false;
     const long long ntiles = (OHW + CFG::TNP - 1) / CFG::TNP;
     if (OHW * 10 < ntiles * CFG::TNP * 7) return false;  // at least 70 % of the pixel columns must be real
-    if (ntiles > 1 && CFG::LB <= 4) return false;
+    if (ntiles > 1 && CFG::LB <= 4 && CFG::NB > 8) return false;  // small-image variants tile the pixels only with their small tiles
     const int chunks = d.C / CFG::CB;
     if (v.split > 1 && chunks < 2 * v.split) return false;
     const long long P = (long long)d.N * OHW;
