@@ -36,8 +36,17 @@ __global__ __launch_bounds__(256) void split_reduce_kernel(ConvArgs a)
     if (i >= total) return;
     const uint32_t k = (uint32_t)(i / (size_t)a.P);
     const uint32_t p = (uint32_t)(i - (size_t)k * a.P);
+    // the partial sums are fetched eight at a time, all loads in flight before the first addition (a loop of load-then-add
+    // would pay one memory latency per split); the additions keep the ascending order
     float x = 0.0f;
-    for (int z = 0; z < a.nsplit; ++z) x += a.ws[(size_t)z * total + i];
+    for (int z0 = 0; z0 < a.nsplit; z0 += 8) {
+        float v[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) v[j] = (z0 + j < a.nsplit) ? a.ws[(size_t)(z0 + j) * total + i] : 0.0f;
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+            if (z0 + j < a.nsplit) x += v[j];
+    }
     if (a.bias) x += a.bias[k];
     if (a.relu) x = x > 0.0f ? x : 0.0f;
     uint32_t n_img, pix;
