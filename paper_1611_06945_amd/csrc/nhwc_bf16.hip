@@ -17,6 +17,10 @@ void register_nhwc_bf16(std::vector<Variant>& out)
     nhwc_register<NH16CFG(2, 2, 1, 1, 32)>(out, sk_all);   // M64  N64
     nhwc_register<NH16CFG(1, 4, 1, 1, 64)>(out, sk_all);   // M32  N128
     nhwc_register<NH16CFG(1, 4, 3, 1, 64)>(out, sk_few);   // M96  N128
+    // eight waves per workgroup: the same tiles with more waves to cover the latency of the staging loads
+    nhwc_register<NH16CFG(2, 4, 2, 1, 64)>(out, sk_few);   // M128 N128, waves of 64x32
+    nhwc_register<NH16CFG(4, 2, 1, 2, 64)>(out, sk_few);   // M128 N128, waves of 32x64
+    nhwc_register<NH16CFG(2, 4, 1, 1, 64)>(out, sk_few);   // M64  N128, waves of 32x32
 }
 
 }  // namespace convfwd
