@@ -51,6 +51,8 @@ State& state()
         register_fc(s->variants);
         register_nhwc_f16(s->variants);
         register_nhwc_bf16(s->variants);
+        register_nwin_f16(s->variants);
+        register_nwin_bf16(s->variants);
         register_wconv_f32(s->variants);
         register_wino_f32(s->variants);
         register_wconv_f16(s->variants);

@@ -99,6 +99,9 @@ NHWC_SHAPES = [
     ConvShape(2, 32, 12, 12, 200, 1, 1, 1, 0),   # pointwise, no padding
     ConvShape(2, 96, 27, 27, 96, 5, 5, 1, 2),    # second layer of the stack at reduced width
     ConvShape(2, 40, 6, 6, 64, 3, 3, 2, 0),      # stride 2 without padding, 8 output pixels in all
+    ConvShape(3, 64, 13, 13, 40, 3, 3, 1, 1),    # window kernel: one band per image, ragged K
+    ConvShape(2, 128, 14, 10, 72, 3, 3, 1, 0),   # window kernel: no padding, K over two 64-row tiles, four chunks
+    ConvShape(1, 64, 20, 20, 72, 3, 3, 1, 1),    # window kernel: bands of 9, 9 and 2 rows, K over two 64-row tiles
 ]
 
 
