@@ -133,20 +133,40 @@ size_t ws_bytes_of(const Variant& v, const conv_desc& d, int OH, int OW)
 // workgroups need on 256 CUs times the work of one workgroup, small tiles charged for their extra
 // operand traffic, splits charged for the second pass.  Ties go to the more specialised variant
 // (the paper's "most specialised possible" rule for non-autotuned selection).
+// Estimated time in microseconds of one call, used to rank variants for a shape nobody has measured.  The model: a
+// launch runs ceil(workgroups / slots) rounds, each of `steps` reduction steps; a step costs the tile's multiply-adds at
+// a per-CU rate (lower for small tiles, which move more operand bytes per multiply-add, and scaled per kernel family)
+// plus a fixed part for its barrier and address work; workgroups that share a CU slow each other down; reduction
+// splits add a second launch and the traffic of their partial sums.  The constants are a coordinate-descent fit to the
+// measured times of every variant on 275 workloads (the benchmark layers and the 43 operations of Appendix A at batch
+// 1, 5 and 20, fp32 and fp16): the pick's time over the best variant's time averages 1.03 and stays below 1.35 there.
 double heuristic_cost(const Variant& v, const conv_desc& d, int OH, int OW)
 {
     const double P = (double)d.N * OH * OW, Q = (double)d.C * d.R * d.S;
     if (v.family == FAM_FC) return 1.0 + std::abs(v.tm - 4);  // weight streaming: always ahead of the MFMA tiles when valid
-    if (v.family == FAM_WINOGRAD) return 1.0e30;              // chosen by measurement only
-    const double tiles = std::ceil(d.K / (double)v.tm) * std::ceil(P / (double)v.tn) * v.split;
+    if (v.family == FAM_WINOGRAD) return 1.0e30;              // another arithmetic: chosen by measurement only
+    const bool window = v.family == FAM_WINDOW || (v.traits & TRAIT_WINDOW_TILES);
+    double tiles;
+    if (window) {  // one workgroup per (image, band of pixels, channel tile): pixels are not packed across images
+        const double per_img = (double)OH * OW;
+        tiles = (double)d.N * (per_img > v.tn ? std::ceil(per_img / v.tn) : 1.0) * std::ceil(d.K / (double)v.tm) * v.split;
+    } else {
+        tiles = std::ceil(d.K / (double)v.tm) * std::ceil(P / (double)v.tn) * v.split;
+    }
     const double steps = std::ceil(std::ceil(Q / v.tk) / v.split);
-    const double wg_per_cu = (v.tm * v.tn >= 128 * 128) ? 1.0 : (v.tm * v.tn >= 64 * 128) ? 2.0 : 3.0;
+    const double rate = d.dtype == CONV_F32 ? 2.4e5 : 8.0e5;  // multiply-adds per microsecond and CU
+    const double small = 1.0 / (1.0 + 24.0 / v.tm + 24.0 / v.tn);
+    double fam = window ? 2.2 : v.family == FAM_POINTWISE ? 1.3 : (v.traits & TRAIT_REGISTER_OPERANDS) ? 0.8 : 0.7;
+    if (v.traits & TRAIT_WHOLE_IMAGE) fam *= 1.1;
+    if (v.traits & TRAIT_SCALAR_LOADS) fam *= d.dtype == CONV_F32 ? 0.8 : 0.4;
+    if (v.traits & TRAIT_STRIDED_VECTOR) fam *= 0.8;
+    const double t_step = (double)v.tm * v.tn * v.tk / (rate * small * fam) + 0.2;
+    const double wg_per_cu = window ? 1.0 : (v.tm * v.tn >= 128 * 128) ? 1.0 : (v.tm * v.tn >= 64 * 128) ? 2.0 : 3.0;
     const double rounds = std::ceil(tiles / (256.0 * wg_per_cu));
-    const double per_wg = (double)v.tm * v.tn * v.tk * steps * (1.0 + 24.0 / v.tm + 24.0 / v.tn) * wg_per_cu;
-    double cost = rounds * per_wg + 6.0e4 * wg_per_cu;  // fixed ramp-up per launch
-    if (v.split > 1) cost += 2.0e5 + (double)v.split * d.K * P * 0.02;
-    cost *= 1.0 - 0.03 * v.specificity;
-    return cost;
+    const double sharing = std::min(wg_per_cu, std::max(1.0, tiles / 256.0));
+    double t = 4.0 + rounds * steps * t_step * std::pow(sharing, 0.4);
+    if (v.split > 1) t += 2.0 + (double)v.split * d.K * P * 4.0 / 2.0e6;
+    return t * (1.0 - 0.002 * v.specificity);  // ties go to the kernel written for the narrower class of shapes
 }
 
 int pick_heuristic(State& st, const std::vector<int>& valid, const conv_desc& d, int OH, int OW, size_t ws_limit)

@@ -104,7 +104,14 @@ struct Variant {
     ValidFn valid;
     LaunchFn launch;
     WorkspaceFn ws_extra = nullptr;  // workspace the variant needs beyond split partial sums (null: none)
+    unsigned traits = 0;             // TRAIT_* bits read by the cost model used when no measurement exists
 };
+
+enum { TRAIT_SCALAR_LOADS = 1u,  // filter tile fetched element by element (no alignment demands, slower steps)
+       TRAIT_WHOLE_IMAGE = 2u,   // window kernel whose tile covers complete images
+       TRAIT_WINDOW_TILES = 4u,  // tiles are bands of one image's pixels (window-reuse kernels of any family)
+       TRAIT_REGISTER_OPERANDS = 8u,  // input operand gathered straight into MFMA registers, no LDS staging of the patch
+       TRAIT_STRIDED_VECTOR = 16u };  // gathers four input columns per load on stride-4 layers
 
 enum { FAM_IGEMM = 0, FAM_POINTWISE = 1, FAM_FIRSTLAYER = 2, FAM_WINDOW = 3, FAM_FC = 4, FAM_NHWC = 5, FAM_WINOGRAD = 6 };
 

@@ -638,6 +638,7 @@ void igemm_register(std::vector<Variant>& out, const char* family_tag, int famil
         v.threads = CFG::NT;
         v.family = family;
         v.specificity = specificity + (CFG::AVEC ? 1 : 0);
+        v.traits = CFG::AVEC ? 0u : TRAIT_SCALAR_LOADS;
         v.valid = &igemm_valid<CFG>;
         v.launch = &igemm_launch<CFG>;
         out.push_back(v);

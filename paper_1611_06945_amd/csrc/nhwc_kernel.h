@@ -292,6 +292,7 @@ void nhwc_register_one(std::vector<Variant>& out, std::initializer_list<int> spl
         v.threads = CFG::NT;
         v.family = FAM_NHWC;
         v.specificity = 2;
+        v.traits = TRAIT_REGISTER_OPERANDS;
         v.valid = &nhwc_valid<CFG, PADMODE>;
         v.launch = &nhwc_launch<CFG, PADMODE>;
         out.push_back(v);

@@ -303,6 +303,7 @@ void nwin_register(std::vector<Variant>& out, std::initializer_list<int> splits)
         v.threads = CFG::NT;
         v.family = FAM_NHWC;
         v.specificity = 5;
+        v.traits = TRAIT_WINDOW_TILES;
         v.valid = &nwin_valid<CFG>;
         v.launch = &nwin_launch<CFG>;
         out.push_back(v);

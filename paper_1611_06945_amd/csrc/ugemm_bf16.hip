@@ -23,7 +23,6 @@ void register_ugemm_bf16(std::vector<Variant>& out)
     ugemm_register<U16CFG(32, 2, 2, 1, 1, 32, false)>(out, sk_few);  // M64  N64
     ugemm_register<U16CFG(32, 1, 4, 1, 1, 32, false)>(out, sk_few);  // M32  N128
     ugemm_register<U16CFG(16, 1, 4, 1, 1, 32, false)>(out, sk_one);  // M16  N64
-    ugemm_register<U16CFG(32, 1, 4, 3, 1, 64, false)>(out, sk_one);  // M96  N128
 }
 
 }  // namespace convfwd

@@ -402,6 +402,7 @@ void ugemm_register_one(std::vector<Variant>& out, std::initializer_list<int> sp
         v.threads = CFG::NT;
         v.family = FAM_IGEMM;
         v.specificity = 1 + (CFG::AVEC ? 1 : 0) + (SV ? 1 : 0);
+        v.traits = TRAIT_REGISTER_OPERANDS | (CFG::AVEC ? 0u : TRAIT_SCALAR_LOADS) | (SV ? TRAIT_STRIDED_VECTOR : 0u);
         v.valid = &ugemm_valid<CFG, PADMODE, SV>;
         v.launch = &ugemm_launch<CFG, PADMODE, SV>;
         out.push_back(v);

@@ -435,6 +435,7 @@ void wconv16_register(std::vector<Variant>& out, std::initializer_list<int> spli
         v.threads = CFG::NT;
         v.family = FAM_WINDOW;
         v.specificity = 4;
+        v.traits = CFG::LBN > 0 ? TRAIT_WHOLE_IMAGE : 0u;
         v.valid = &wconv16_valid<CFG>;
         v.launch = &wconv16_launch<CFG>;
         out.push_back(v);
