@@ -55,6 +55,8 @@ State& state()
         register_nwin_bf16(s->variants);
         register_wconv_f32(s->variants);
         register_wino_f32(s->variants);
+        register_swin_f16(s->variants);
+        register_swin_bf16(s->variants);
         register_wconv_f16(s->variants);
         register_wconv_bf16(s->variants);
         for (size_t i = 0; i < s->variants.size(); ++i) s->by_name[s->variants[i].name] = (int)i;
