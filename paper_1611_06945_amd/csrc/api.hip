@@ -147,6 +147,15 @@ double heuristic_cost(const Variant& v, const conv_desc& d, int OH, int OW)
     const double P = (double)d.N * OH * OW, Q = (double)d.C * d.R * d.S;
     if (v.family == FAM_FC) return 1.0 + std::abs(v.tm - 4);  // weight streaming: always ahead of the MFMA tiles when valid
     if (v.family == FAM_WINOGRAD) return 1.0e30;              // another arithmetic: chosen by measurement only
+    if (v.family == FAM_FIRSTLAYER) {
+        // persistent workgroups, one per CU and channel tile, walking over tiles of v.tn pixels of one image: a start-up
+        // that grows with the filter rows a workgroup re-lays, then a time per tile (measured on the 11x11 stride-4 and
+        // 7x7 stride-2 first layers at batch 5 and 20)
+        const double tiles = (double)d.N * std::ceil((double)OH * OW / v.tn), ktiles = std::ceil(d.K / (double)v.tm);
+        const double wgs = std::max(1.0, std::min(std::floor(256.0 / ktiles), tiles));
+        const double per_tile = 1.5 + (0.5 + 0.026 * v.tm) * v.tk / 416.0;
+        return 1.0 + 0.068 * v.tm + std::ceil(tiles / wgs) * per_tile;
+    }
     const bool window = v.family == FAM_WINDOW || (v.traits & TRAIT_WINDOW_TILES);
     double tiles;
     if (window) {  // one workgroup per (image, band of pixels, channel tile): pixels are not packed across images
