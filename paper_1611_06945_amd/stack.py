@@ -161,6 +161,23 @@ class ConvStack:
         """Enqueue every operation; returns the last layer's output tensor, [N][K][OH][OW] (not synchronised)."""
         return self._walk(x, filts, biases, stream, tune=False)
 
+    def capture(self, x, filts, biases):
+        """Record one run of the stack (every convolution, pool and conversion, on the given tensors) into a HIP graph
+        by stream capture and return it; `graph.replay()` then launches the whole chain with one call.  Variants must be
+        selected (autotune or cache) before: the captured launches are those of the selection at capture time.  The
+        result of a replay is in the same buffers as after `run` (`layer_output(len(shapes) - 1)`)."""
+        torch = self.torch
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            self.run(x, filts, biases)      # once outside the capture: kernel attributes are set on a first launch
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            self.run(x, filts, biases)
+        return graph
+
     def autotune(self, x, filts, biases, stream=None) -> None:
         """Autotune every layer on real data; with formats="auto", first choose the formats."""
         if self.auto:

@@ -146,3 +146,46 @@ def test_config5_stack_with_format_selection(dtype, formats):
         cur = handed  # the next layer is judged on the GPU's own stored input
     assert stack.output_layout(len(shapes) - 1) == "nchw"
     assert np.array_equal(to_host_f64(y, dtype), cur)
+
+
+@pytest.mark.parametrize("formats", [None, ["nchw", "nhwc", "nhwc", "nhwc", "nhwc"]])
+def test_config5_stack_as_hip_graph(formats):
+    """The stack recorded into a HIP graph must reproduce the eagerly enqueued stack bit for bit, on every replay: the
+    graph is replayed several times with eager runs, buffer poisoning and synchronisations in between."""
+    torch = torch_mod()
+    dtype = wl.F16
+    layers = wl.config5_layers(5, dtype)
+    shapes = [w.shape for w in layers]
+    stack = ConvStack(shapes, dtype, pool_after=wl.STACK_POOL_AFTER, formats=formats)
+    gen = [w.generate() for w in layers]
+    x = to_device(gen[0]["in"], dtype)
+    filts = [to_device(g["filt"], dtype) for g in gen]
+    biases = [to_device(g["bias"], wl.F32) for g in gen]
+    stack.autotune(x, filts, biases)
+    last = len(shapes) - 1
+
+    def snapshot():
+        torch.cuda.synchronize()
+        return [to_host_stored(stack.layer_output(i), dtype).copy() for i in range(len(shapes))]
+
+    def poison():
+        for i in range(len(shapes)):
+            for t in (stack.conv_out[i], stack.pool_out[i], stack.convert_out[i]):
+                if t is not None:
+                    t.fill_(float("nan"))
+
+    stack.run(x, filts, biases)
+    eager = snapshot()
+    assert np.all(np.isfinite(wl.storage_to_f64(eager[last], dtype)))
+    graph = stack.capture(x, filts, biases)
+    for rep in range(4):
+        poison()
+        if rep % 2:
+            stack.run(x, filts, biases)     # eager work of the same program between replays
+            torch.cuda.synchronize()
+            poison()
+        graph.replay()
+        got = snapshot()
+        for i in range(len(shapes)):
+            assert np.array_equal(got[i], eager[i]), "replay %d, layer %d differs from the eager run" % (rep, i + 1)
+    say("  %s: 4 graph replays identical to the eager run" % (stack.formats,))
