@@ -21,7 +21,7 @@ void register_wino_f32(std::vector<Variant>& out)
 
 hipError_t launch_wino_filter_transform(const float* filt, float* out, int K, int C, hipStream_t s)
 {
-    hipLaunchKernelGGL(wino_filter_kernel<8>, dim3((unsigned)((K + 31) / 32), (unsigned)(C / 8)), dim3(128), 0, s, filt, out, K, C);
+    hipLaunchKernelGGL(wino_filter_kernel<8>, dim3((unsigned)((K + 31) / 32), (unsigned)(C / 8)), dim3(256), 0, s, filt, out, K, C);
     return hipGetLastError();
 }
 

@@ -83,37 +83,38 @@ __host__ __device__ inline int wino_kpitch(int K) { return (K + 3) & ~3; }
 // Filter transform.  With HN = CB/4 and K' = wino_kpitch(K), the workspace holds
 //     U[c / CB][xi][q][k][h] = (G g G^T)[xi / 4][xi % 4] of filter (k, c),   c % CB = q + 4*h,  q = 0..3, h = 0..HN-1
 // (G = [1 0 0; 1/2 1/2 1/2; 1/2 -1/2 1/2; 0 0 1]): MFMA lane group q of a wave consumes channel q + 4*h in its h-th MFMA
-// of a step, so the HN values it needs for one output channel are adjacent.  A workgroup (32 output channels x 4 lane
-// groups) transforms 32 x CB filters: their values are read as contiguous runs into LDS, all loads in flight at once,
-// and thread (k, q) then writes the HN adjacent values of each plane as one vector, k along the lanes.
+// of a step, so the HN values it needs for one output channel are adjacent.  A workgroup transforms 32 x CB filters,
+// one per thread: their values are read as contiguous runs into LDS, all loads in flight at once, and the threads are
+// ordered (h, k, q) so that a wave's stores of one plane are one contiguous run.
 template <int CB>
-__global__ __launch_bounds__(128) void wino_filter_kernel(const float* __restrict__ filt, float* __restrict__ U, int K, int C)
+__global__ __launch_bounds__(32 * CB) void wino_filter_kernel(const float* __restrict__ filt, float* __restrict__ U, int K, int C)
 {
+    // one thread per filter (k, c): thread = h + HN*kl + 32*HN*q, so that a wave's stores of one plane are one contiguous run
     constexpr int HN = CB / 4, ROW = CB * 9 + 1;  // odd row pitch: the lanes' strided reads fall on different banks
-    constexpr int NLOAD = 32 * CB * 9 / 128;
+    constexpr int NTH = 32 * CB;
+    constexpr int NLOAD = 32 * CB * 9 / NTH;
     __shared__ float g_s[32 * ROW];
     const int tid = threadIdx.x;
     const int k0 = blockIdx.x * 32, cb = blockIdx.y;
     float v[NLOAD];
 #pragma unroll
     for (int i = 0; i < NLOAD; ++i) {
-        const int e = i * 128 + tid;
+        const int e = i * NTH + tid;
         const int kl = e / (CB * 9), j = e - kl * (CB * 9);
         v[i] = (k0 + kl < K) ? filt[((size_t)(k0 + kl) * C + cb * CB) * 9 + j] : 0.0f;
     }
 #pragma unroll
     for (int i = 0; i < NLOAD; ++i) {
-        const int e = i * 128 + tid;
+        const int e = i * NTH + tid;
         const int kl = e / (CB * 9), j = e - kl * (CB * 9);
         g_s[kl * ROW + j] = v[i];
     }
     __syncthreads();
-    const int kl = tid & 31, q = tid >> 5;
+    const int h = tid % HN, kl = (tid / HN) & 31, q = tid / (32 * HN);
     if (k0 + kl >= K) return;
     const size_t kp = (size_t)wino_kpitch(K);
-    float u[16][HN];
-#pragma unroll
-    for (int h = 0; h < HN; ++h) {
+    float u[16];
+    {
         const float* g = g_s + kl * ROW + (q + 4 * h) * 9;
         float gg[4][3];
 #pragma unroll
@@ -127,21 +128,16 @@ __global__ __launch_bounds__(128) void wino_filter_kernel(const float* __restric
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const float a0 = gg[i][0], a1 = gg[i][1], a2 = gg[i][2];
-            u[4 * i + 0][h] = a0;
-            u[4 * i + 1][h] = 0.5f * ((a0 + a2) + a1);
-            u[4 * i + 2][h] = 0.5f * ((a0 + a2) - a1);
-            u[4 * i + 3][h] = a2;
+            u[4 * i + 0] = a0;
+            u[4 * i + 1] = 0.5f * ((a0 + a2) + a1);
+            u[4 * i + 2] = 0.5f * ((a0 + a2) - a1);
+            u[4 * i + 3] = a2;
         }
     }
-    float* dst = U + (((size_t)cb * 16 * 4 + q) * kp + k0 + kl) * HN;
+    float* dst = U + (((size_t)cb * 16 * 4 + q) * kp + k0 + kl) * HN + h;
     const size_t plane = 4 * kp * HN;
 #pragma unroll
-    for (int xi = 0; xi < 16; ++xi) {
-        if constexpr (HN == 2)
-            *(float2*)&dst[xi * plane] = make_float2(u[xi][0], u[xi][1]);
-        else
-            *(float4*)&dst[xi * plane] = make_float4(u[xi][0], u[xi][1], u[xi][2], u[xi][3]);
-    }
+    for (int xi = 0; xi < 16; ++xi) dst[xi * plane] = u[xi];
 }
 
 template <class CFG>
@@ -480,7 +476,7 @@ hipError_t wino_launch(const Variant& v, ConvArgs& a, hipStream_t s)
     if (a.filt_wino) {
         a.ws = (float*)const_cast<void*>(a.filt);  // already in the Winograd domain
     } else {
-        hipLaunchKernelGGL(wino_filter_kernel<CFG::CB>, dim3((unsigned)((a.K + 31) / 32), (unsigned)(a.C / CFG::CB)), dim3(128), 0, s,
+        hipLaunchKernelGGL(wino_filter_kernel<CFG::CB>, dim3((unsigned)((a.K + 31) / 32), (unsigned)(a.C / CFG::CB)), dim3(32 * CFG::CB), 0, s,
                            (const float*)a.filt, a.ws, a.K, a.C);
         const hipError_t e2 = hipGetLastError();
         if (e2 != hipSuccess) return e2;
