@@ -291,3 +291,35 @@ def test_winograd_variants_and_the_transformed_filter_format():
     assert L.conv_transform_filters(ctypes.byref(plain), 256, 520, None) == B.CONV_EINVAL   # output not 256-byte aligned
     assert L.conv_transform_filters(ctypes.byref(plain), 256, 256, None) == B.CONV_EINVAL   # in place
     assert L.conv_transform_filters(None, 256, 512, None) == B.CONV_EINVAL
+
+
+def test_strided_window_variants_for_first_layers():
+    """The first-layer window kernel is offered exactly where its staging fits (host-side validity, no GPU needed), needs no
+    workspace, and is what an unmeasured 16-bit first layer gets."""
+    from paper_1611_06945_amd.workloads import ConvShape
+
+    def names_of(sh, dt):
+        d = B.desc_of(sh, dt)
+        return d, [B.conv_variant_name(d, i) for i in range(B.conv_variant_count(d))]
+
+    for dt, tag in ((1, "f16"), (2, "bf16")):
+        d, names = names_of(ConvShape(20, 3, 227, 227, 96, 11, 11, 4, 0), dt)
+        swin = [i for i, n in enumerate(names) if n.startswith("swin_%s_11x11s4_c3_" % tag)]
+        assert [names[i] for i in swin] == ["swin_%s_11x11s4_c3_M96N128" % tag, "swin_%s_11x11s4_c3_M32N128" % tag], names
+        assert all(B.conv_variant_workspace(d, i) == 0 for i in swin)
+        assert B.conv_variant_name(d, -1) == "swin_%s_11x11s4_c3_M96N128" % tag
+        d7, names7 = names_of(ConvShape(5, 3, 224, 224, 64, 7, 7, 2, 3), dt)
+        assert [n for n in names7 if n.startswith("swin_")] == ["swin_%s_7x7s2_c3_M64N128" % tag, "swin_%s_7x7s2_c3_M32N128" % tag]
+        assert B.conv_variant_name(d7, -1).startswith("swin_")
+    # channel tiles that would be mostly empty are not offered: K = 40 fits the 32- and 64-row tiles, not the 96-row one
+    _, n40 = names_of(ConvShape(3, 3, 23, 63, 40, 11, 11, 4, 0), 1)
+    assert [n for n in n40 if n.startswith("swin_")] == ["swin_f16_11x11s4_c3_M64N128", "swin_f16_11x11s4_c3_M32N128"]
+    for sh, dt in [(ConvShape(20, 3, 227, 227, 96, 11, 11, 4, 0), 0),     # fp32 storage
+                   (ConvShape(20, 4, 227, 227, 96, 11, 11, 4, 0), 1),     # four channels
+                   (ConvShape(20, 3, 227, 227, 96, 11, 11, 2, 0), 1),     # another stride
+                   (ConvShape(20, 3, 227, 227, 96, 9, 9, 4, 0), 1),       # another window
+                   (ConvShape(20, 3, 63, 63, 96, 11, 11, 4, 0), 1),       # short output rows: a tile would span too many
+                   (ConvShape(1, 3, 227, 600, 96, 11, 11, 4, 0), 1),      # rows longer than a staged row
+                   (ConvShape(20, 3, 227, 227, 96, 11, 11, 4, 11), 1)]:   # padding as wide as the window
+        _, names = names_of(sh, dt)
+        assert names and not any(n.startswith("swin_") for n in names), (sh, dt)
