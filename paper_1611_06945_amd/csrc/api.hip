@@ -153,8 +153,8 @@ double heuristic_cost(const Variant& v, const conv_desc& d, int OH, int OW)
         // 7x7 stride-2 first layers at batch 5 and 20)
         const double tiles = (double)d.N * std::ceil((double)OH * OW / v.tn), ktiles = std::ceil(d.K / (double)v.tm);
         const double wgs = std::max(1.0, std::min(std::floor(256.0 / ktiles), tiles));
-        const double per_tile = 1.5 + (0.5 + 0.026 * v.tm) * v.tk / 416.0;
-        return 1.0 + 0.068 * v.tm + std::ceil(tiles / wgs) * per_tile;
+        const double per_tile = 1.3 + (0.5 + 0.0156 * v.tm) * v.tk / 416.0;  // two tiles of a workgroup run side by side
+        return 1.05 + 0.058 * v.tm + std::ceil(tiles / wgs) * per_tile;
     }
     const bool window = v.family == FAM_WINDOW || (v.traits & TRAIT_WINDOW_TILES);
     double tiles;

@@ -12,8 +12,9 @@
 //     the patch operand's padding taps are cleared as well, so a non-finite input value reaches only the outputs
 //     whose window holds it;
 //   * a tile is 128 consecutive output pixels of one image (any row length: a tile may span several output rows),
-//     one 32-pixel block per wave, all TM channels per wave; the workgroup walks over tiles (persistent), the input rows
-//     of the next tile are fetched while the current one is multiplied, the filters are staged once;
+//     one 32-pixel block per wave, all TM channels per wave.  The workgroup is persistent and made of two groups of 4
+//     waves, each walking over its own tiles in its own patch buffer (a second wave per SIMD to issue while the first
+//     waits): a group fetches the rows of its next tile while it multiplies; the filters are staged once, by all waves;
 //   * zero padding and rows or columns past the image are zero elements of the staged rows.
 #pragma once
 
@@ -31,9 +32,10 @@ struct Swin16Cfg {
     static_assert(ST_ == 2 || ST_ == 4, "operand groups must stay dword aligned");
     static_assert(PITCH_ % 4 == 0, "staged rows keep the groups' alignment");
     static constexpr int DT = DT_, C = C_, R = R_, S = S_, ST = ST_, TMB = TMB_, IRMAX = IRMAX_, PITCH = PITCH_;
-    static constexpr int NT = 256, WAVES = 4;
+    static constexpr int CWAVES = 4;                 // waves of a group: one 32-pixel block each
+    static constexpr int WAVES = 8, NT = 64 * WAVES; // two groups, each on its own tile and patch buffer; all waves re-lay the filters
     static constexpr int TM = 32 * TMB;              // output channels per workgroup
-    static constexpr int TN = 32 * WAVES;            // pixels per tile
+    static constexpr int TN = 32 * CWAVES;           // pixels per tile
     static constexpr int SQ = (S + 3) / 4;           // groups of 4 taps per filter row
     static constexpr int NROW = C * R;               // (filter row, channel) pairs: "lines" of the reduction
     static constexpr int NPAIR = (NROW + 1) / 2;     // the two lane halves of an MFMA take the lines 2t and 2t+1
@@ -41,7 +43,7 @@ struct Swin16Cfg {
     static constexpr int KP = KSTEPS * 16;           // padded reduction length
     static constexpr int LDA = KP + 8;               // filter row pitch: rows 16-byte aligned, conflict-free 16-byte reads
     static constexpr int SROWS = C * IRMAX;          // staged rows of one tile, [input row][channel]
-    static constexpr int RR_W = (IRMAX + WAVES - 1) / WAVES;    // input rows per wave (each in all C channels)
+    static constexpr int RR_W = (IRMAX + CWAVES - 1) / CWAVES;  // input rows per wave (each in all C channels)
     static constexpr int ROWS_W = RR_W * C;          // staged rows per wave
     static constexpr int B_ELEMS = (SROWS + 1) * PITCH;  // one patch buffer; the last row stays zero
 };
@@ -58,7 +60,7 @@ __global__ __launch_bounds__(CFG::NT) void swin16_kernel(ConvArgs a)
 {
     typedef uint16_t elem_t;
     constexpr int DT = CFG::DT, C = CFG::C, R = CFG::R, S = CFG::S, ST = CFG::ST, TMB = CFG::TMB, PITCH = CFG::PITCH;
-    constexpr int NT = CFG::NT, WAVES = CFG::WAVES, TM = CFG::TM, TN = CFG::TN, SQ = CFG::SQ, NROW = CFG::NROW;
+    constexpr int NT = CFG::NT, WAVES = CFG::CWAVES, TM = CFG::TM, TN = CFG::TN, SQ = CFG::SQ, NROW = CFG::NROW;
     constexpr int KSTEPS = CFG::KSTEPS, KP = CFG::KP, LDA = CFG::LDA, ROWS_W = CFG::ROWS_W, RR_W = CFG::RR_W, IRMAX = CFG::IRMAX;
     constexpr int SROWS = CFG::SROWS, B_ELEMS = CFG::B_ELEMS, Q = C * R * S;
     typedef Mma<DT, 32> mma_t;
@@ -68,7 +70,9 @@ __global__ __launch_bounds__(CFG::NT) void swin16_kernel(ConvArgs a)
     elem_t* const Bs0 = As + TM * LDA;             // [2][B_ELEMS]
     float* const bias_s = (float*)(Bs0 + 2 * B_ELEMS);  // [TM]
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int grp = __builtin_amdgcn_readfirstlane(tid >> 8);        // wave group: tiles t_begin + grp, + 2, ... in patch buffer grp
+    const int wave = __builtin_amdgcn_readfirstlane((tid >> 6) & 3);  // wave of the group
     const int li = lane & 31, h = lane >> 5;
     const int m0 = blockIdx.y * TM;
     const int tiles = a.N * (int)a.dX.d;           // dX divides by the tiles of one image
@@ -118,7 +122,7 @@ __global__ __launch_bounds__(CFG::NT) void swin16_kernel(ConvArgs a)
     // row rr = w + 4k, channel c, staged row rr*C + c.  Returns the slots (bit i) fetched one element early.
     auto load_rows = [&](int tile, stage_t& st_reg) -> uint32_t {
         int img, p0, row0;
-        tile_rows(tile < t_end ? tile : 0, img, p0, row0);
+        tile_rows(tile < t_end ? tile : t_begin, img, p0, row0);
         const bool live = tile < t_end;
         const int iy_w = row0 * ST - a.pad + wave;
         const int origin_w = img * C * a.HW + iy_w * a.W - a.pad;  // element index of staged column 0, k = 0, c = 0
@@ -159,12 +163,10 @@ __global__ __launch_bounds__(CFG::NT) void swin16_kernel(ConvArgs a)
         }
     };
 
-    // the first two tiles' rows are in flight while the filters are staged
-    int tile = t_begin;
-    stage_t st_a, st_b;
-    uint32_t sh_a = 0, sh_b = 0;
-    sh_a = load_rows(tile, st_a);
-    sh_b = load_rows(tile + 1, st_b);
+    // each group's first tile is in flight while the filters are staged
+    int tile = t_begin + grp;
+    stage_t st_a;
+    uint32_t sh_a = load_rows(tile, st_a);
 
     // ---- filters: KCRS rows -> [TM][KP] -------------------------------------------------------------------------
     // Reduction element kk = 16*j + 8*half + 4*g + e of MFMA step j belongs to line 2t + half (line = r*C + c) and
@@ -174,6 +176,8 @@ __global__ __launch_bounds__(CFG::NT) void swin16_kernel(ConvArgs a)
         static_assert(S % 4 == 0 || S % 4 == 3, "a filter row's last group holds 3 or 4 taps");
         constexpr int GS = KP / 4;
         static_assert(GS <= 128, "two filter rows per pass of the workgroup");
+        constexpr int MR = NT / 128;  // filter rows per pass of the workgroup (even: a thread's rows keep their parity)
+        static_assert(MR % 2 == 0 && TM % MR == 0, "rows per pass");
         const int gs = tid & 127, mrow = __builtin_amdgcn_readfirstlane(tid >> 7);
         const int j = gs >> 2, gh = (gs >> 1) & 1, g = gs & 1;
         const int i2 = 2 * j + g, t = i2 / SQ, sq = i2 - t * SQ;
@@ -183,16 +187,16 @@ __global__ __launch_bounds__(CFG::NT) void swin16_kernel(ConvArgs a)
         const int src = (fc * R + fr) * S + 4 * sq;                 // first tap of the group in the filter row
         const bool three = S - 4 * sq < 4;
         // The group's 8 bytes start at element m*Q + src, even or odd: they are cut out of three aligned dwords (a
-        // misaligned dword load runs at a fraction of the rate).  The rows of a thread are two apart, so m*Q keeps its
+        // misaligned dword load runs at a fraction of the rate).  The rows of a thread are MR apart, so m*Q keeps its
         // parity pm and the cut is the same for every row: vector part 2*((src+pm) & ~1), scalar part 2*(m*Q & ~1).
         const int pm = ((m0 + mrow) * Q) & 1;
         const int par = (pm + src) & 1;
         const uint32_t v0 = g_ok ? (uint32_t)((src + pm) & ~1) * 2u : kFarOffset;
-        constexpr int NIT = TM / 2;
+        constexpr int NIT = TM / MR;
         u32x3 f[NIT];
 #pragma unroll
         for (int it = 0; it < NIT; ++it) {
-            const int m = m0 + mrow + 2 * it;
+            const int m = m0 + mrow + MR * it;
             const uint32_t soff = m < a.K ? (uint32_t)((m * Q) & ~1) * 2u : kFarScalar;
             f[it] = __builtin_bit_cast(u32x3, __builtin_amdgcn_raw_buffer_load_b96(rfilt, (int)v0, (int)soff, 0));
         }
@@ -211,24 +215,25 @@ __global__ __launch_bounds__(CFG::NT) void swin16_kernel(ConvArgs a)
             for (int it = 0; it < NIT; ++it) {
                 const uint32_t lo = __builtin_amdgcn_alignbit(f[it].y, f[it].x, sh);
                 const uint32_t hi = __builtin_amdgcn_alignbit(f[it].z, f[it].y, sh);
-                *(uint2*)&As[(mrow + 2 * it) * LDA + 4 * gs] = make_uint2(lo, hi & mhi);
+                *(uint2*)&As[(mrow + MR * it) * LDA + 4 * gs] = make_uint2(lo, hi & mhi);
             }
         }
     }
-    store_rows(0, st_a, sh_a);
-    store_rows(1, st_b, sh_b);
+    store_rows(grp, st_a, sh_a);
     __syncthreads();
 
     const __amdgpu_buffer_rsrc_t rout = make_rsrc(a.out, a.out_bytes);
 
     // lanes of the upper half whose line 2t+1 does not exist (odd number of lines) clear that operand
     const uint32_t last_pair_mask = (h && (NROW & 1)) ? 0u : 0xFFFFFFFFu;
-    int buf = 0;
-    for (; tile < t_end; ++tile) {
-        // rows of the tile after the next: they replace this tile's rows once every wave is done with them
+    const int buf = grp;
+    // Both groups make the same number of passes (the barriers are the workgroup's); a group without a tile idles.
+    for (int first = t_begin; first < t_end; first += 2, tile += 2) {
+        // rows of the group's next tile: they replace this tile's rows once the group is done with them
         const bool more = tile + 2 < t_end;
         if (more) sh_a = load_rows(tile + 2, st_a);
 
+        if (tile < t_end) {
         int img, p0, row0;
         tile_rows(tile, img, p0, row0);
         const int p = p0 + wave * 32 + li;
@@ -319,9 +324,11 @@ __global__ __launch_bounds__(CFG::NT) void swin16_kernel(ConvArgs a)
                     if (p_ok) vo += e == 3 ? step5 : step1;
                 }
             }
+        }
+        if (first + 2 >= t_end) break;  // no group has a further tile
         __syncthreads();
         if (more) store_rows(buf, st_a, sh_a);
-        buf ^= 1;
+        __syncthreads();
     }
 }
 
