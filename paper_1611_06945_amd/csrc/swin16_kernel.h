@@ -5,7 +5,7 @@
 // element is fetched dozens of times, two bytes at a time, and the loop waits on those fetches.  Here the input rows a
 // tile of output pixels touches are copied into LDS once (paper, Section 5 "Related Work": overlapping windows share
 // the copy) and every operand is an LDS read:
-//   * the reduction runs over (channel, filter row, group of 4 taps): a filter row of S taps is padded to 4*SQ, so a
+//   * the reduction runs over (filter row, channel, group of 4 taps): a filter row of S taps is padded to 4*SQ, so a
 //     lane's 8 reduction elements of one MFMA are two groups, each 4 consecutive input columns of one input row,
 //     ST*ox + 4*g .. +3: contiguous in the staged row and aligned (8 bytes for stride 4, 4 bytes for stride 2);
 //   * the filters are re-laid once per workgroup into [TM][KP] with zeros in the padding taps and stay in LDS;
