@@ -106,16 +106,19 @@ __global__ __launch_bounds__(CFG::NT) void nhwc_kernel(ConvArgs a)
     const int a_lds0 = row0 * LDA + koct * 8;   // + i * A_RSTEP * LDA
     const int b_lds0 = row0 * LDB + koct * 8;   // + i * B_PSTEP * LDB
 
-    uint4 a_vec[A_LOADS], b_vec[B_LOADS];
+    // two register sets: the loads of step t+3 are issued while those of step t+2 are still in flight (an L2 round trip
+    // under load outlasts one step of a 128x128x64 tile about four times; with one set in flight the step waits for it)
+    uint4 a_vec[2][A_LOADS], b_vec[2][B_LOADS];
 
-    auto load_tiles = [&](int step) {
+    auto load_tiles = [&](auto setc, int step) {
+        constexpr int set = decltype(setc)::value;
         const int q = step * TK + koct * 8;     // this thread's reduction index in this step
         const bool k_ok = q < a.Q;              // vectors never straddle the end: Q is a multiple of 8
         const uint32_t a_soff = (uint32_t)(step * TK) * 2u;
 #pragma unroll
         for (int i = 0; i < A_LOADS; ++i) {
             const u32x4 t = __builtin_amdgcn_raw_buffer_load_b128(rfilt, (int)(k_ok ? a_voff[i] : kFarOffset), (int)a_soff, 0);
-            a_vec[i] = make_uint4(t.x, t.y, t.z, t.w);
+            a_vec[set][i] = make_uint4(t.x, t.y, t.z, t.w);
         }
         uint32_t tap, c, r, s;
         a.dC.divmod(k_ok ? (uint32_t)q : 0u, tap, c);
@@ -128,18 +131,18 @@ __global__ __launch_bounds__(CFG::NT) void nhwc_kernel(ConvArgs a)
             if constexpr (PADMODE == PAD_ROWCOL) far |= ((tapbad[i] >> s) | (tapbad[i] >> (16u + r))) & 1u;
             const uint32_t vo = (far << 31) | (b_voff[i] + koff);
             const u32x4 t = __builtin_amdgcn_raw_buffer_load_b128(rin, (int)vo, 0, 0);
-            b_vec[i] = make_uint4(t.x, t.y, t.z, t.w);
+            b_vec[set][i] = make_uint4(t.x, t.y, t.z, t.w);
         }
     };
 
-    auto store_tiles = [&](auto bufc) {
-        constexpr int buf = decltype(bufc)::value;
+    auto store_tiles = [&](auto bufc) {  // register set and LDS buffer have the step's parity
+        constexpr int buf = decltype(bufc)::value, set = buf;
         elem_t* As = As0 + buf * CFG::A_ELEMS;
         elem_t* Bs = Bs0 + buf * CFG::B_ELEMS;
 #pragma unroll
-        for (int i = 0; i < A_LOADS; ++i) *(uint4*)&As[a_lds0 + i * A_RSTEP * LDA] = a_vec[i];
+        for (int i = 0; i < A_LOADS; ++i) *(uint4*)&As[a_lds0 + i * A_RSTEP * LDA] = a_vec[set][i];
 #pragma unroll
-        for (int i = 0; i < B_LOADS; ++i) *(uint4*)&Bs[b_lds0 + i * B_PSTEP * LDB] = b_vec[i];
+        for (int i = 0; i < B_LOADS; ++i) *(uint4*)&Bs[b_lds0 + i * B_PSTEP * LDB] = b_vec[set][i];
     };
 
     acc_t acc[BM][BN];
@@ -164,18 +167,21 @@ __global__ __launch_bounds__(CFG::NT) void nhwc_kernel(ConvArgs a)
         if (more) store_tiles(std::integral_constant<int, buf ^ 1>{});
         __syncthreads();
         if (more) igemm_read_frags<CFG>(As0 + (buf ^ 1) * CFG::A_ELEMS, Bs0 + (buf ^ 1) * CFG::B_ELEMS, fn, fa_row0, fb_col0, kg);
-        if (step + 2 < step_end) load_tiles(step + 2);
+        // unconditional (a conditional load makes every later wait assume the worst): past the reduction's end the
+        // loads are pointed out of range, past a split's end they fetch the next split's data, which is not used
+        load_tiles(std::integral_constant<int, buf ^ 1>{}, step + 3);
         __builtin_amdgcn_sched_barrier(0);
         igemm_mma_range<CFG, NU - TAILU, NU>(fc, acc);
     };
 
     if (step_begin < step_end) {
         IgemmFrags<CFG> f0, f1;
-        load_tiles(step_begin);
+        load_tiles(std::integral_constant<int, 0>{}, step_begin);
         store_tiles(std::integral_constant<int, 0>{});
         __syncthreads();
         igemm_read_frags<CFG>(As0, Bs0, f0, fa_row0, fb_col0, kg);
-        if (step_begin + 1 < step_end) load_tiles(step_begin + 1);
+        load_tiles(std::integral_constant<int, 1>{}, step_begin + 1);
+        load_tiles(std::integral_constant<int, 0>{}, step_begin + 2);
         for (int step = step_begin; step < step_end; step += 2) {
             body(std::integral_constant<int, 0>{}, step, f0, f1);
             if (step + 1 < step_end) body(std::integral_constant<int, 1>{}, step + 1, f1, f0);
