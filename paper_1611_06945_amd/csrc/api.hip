@@ -116,8 +116,14 @@ std::vector<int> valid_list(State& st, const conv_desc& d, int OH, int OW)
     const bool layout = (d.flags & kLayoutFlags) != 0;
     const bool wino_filters = (d.flags & CONV_FLAG_FILT_WINOGRAD) != 0;
     if (layout && wino_filters) return r;
+    // ... except planar input and filters with a channel-innermost output, which some planar kernels can write
+    const bool planar_to_nhwc = (d.flags & kLayoutFlags) == CONV_FLAG_OUT_NHWC;
     for (size_t i = 0; i < st.variants.size(); ++i) {
-        if ((st.variants[i].family == FAM_NHWC) != layout) continue;
+        if (planar_to_nhwc) {
+            if (!(st.variants[i].traits & TRAIT_PLANAR_TO_NHWC)) continue;
+        } else if ((st.variants[i].family == FAM_NHWC) != layout) {
+            continue;
+        }
         if (wino_filters && st.variants[i].family != FAM_WINOGRAD) continue;
         if (st.variants[i].valid(st.variants[i], d, OH, OW)) r.push_back((int)i);
     }

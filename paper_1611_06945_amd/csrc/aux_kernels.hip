@@ -110,6 +110,42 @@ __global__ __launch_bounds__(256) void maxpool_kernel(const typename Prec<DT>::e
     out[i] = best;
 }
 
+// Channel-innermost on both sides with C a multiple of 8: one thread per (output pixel, 8 channels), every tap one
+// 16-byte load.  The maximum is taken on the widened values (exact, order preserving) and narrowed back, which is
+// exact as well since it is one of the stored values.
+template <int DT>
+__global__ __launch_bounds__(256) void maxpool_nhwc8_kernel(const uint16_t* __restrict__ in, uint16_t* __restrict__ out, int N,
+                                                            int C, int H, int W, int OH, int OW, int win, int stride,
+                                                            FastDiv dC8, FastDiv dOHW, FastDiv dOW)
+{
+    const uint32_t total = (uint32_t)N * OH * OW * (C >> 3);
+    const uint32_t i = blockIdx.x * 256u + threadIdx.x;
+    if (i >= total) return;
+    uint32_t pix, oct, n, rem, oy, ox;
+    dC8.divmod(i, pix, oct);
+    dOHW.divmod(pix, n, rem);
+    dOW.divmod(rem, oy, ox);
+    const uint16_t* src = in + ((size_t)(n * H + oy * stride) * W + ox * stride) * C + oct * 8;
+    float best[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) best[e] = -__builtin_inff();
+    for (int r = 0; r < win; ++r)
+        for (int s = 0; s < win; ++s) {
+            const uint4 v = *(const uint4*)(src + ((size_t)r * W + s) * C);
+            const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const uint16_t h = (uint16_t)(e & 1 ? w[e >> 1] >> 16 : w[e >> 1] & 0xFFFFu);
+                best[e] = __builtin_fmaxf(best[e], Prec<DT>::to_f32(h));
+            }
+        }
+    uint32_t o[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+        o[e] = (uint32_t)Prec<DT>::from_f32(best[2 * e]) | ((uint32_t)Prec<DT>::from_f32(best[2 * e + 1]) << 16);
+    *(uint4*)(out + (size_t)i * 8) = make_uint4(o[0], o[1], o[2], o[3]);
+}
+
 // The same pooling when input and output layouts differ: a tile of 32 channels x 32 output pixels of one image is
 // pooled by threads arranged along the INPUT's contiguous axis, parked in LDS, and written out by threads arranged
 // along the OUTPUT's contiguous axis, so that both sides of the conversion move contiguous runs.
@@ -190,8 +226,19 @@ hipError_t launch_maxpool(int N, int C, int H, int W, int win, int stride, int d
         return hipGetLastError();
     }
     const size_t total = (size_t)N * C * OH * OW;
-    dim3 grid((unsigned)((total + 255) / 256));
     const FastDiv dOHW = make_fastdiv((uint32_t)(OH * OW)), dOW = make_fastdiv((uint32_t)OW), dC = make_fastdiv((uint32_t)C);
+    if (in_nhwc && out_nhwc && dtype != CONV_F32 && (C % 8) == 0 && total / 8 < (1u << 31)) {
+        const FastDiv dC8 = make_fastdiv((uint32_t)(C / 8));
+        dim3 grid8((unsigned)((total / 8 + 255) / 256));
+        if (dtype == CONV_F16)
+            hipLaunchKernelGGL(maxpool_nhwc8_kernel<CONV_F16>, grid8, dim3(256), 0, s, (const uint16_t*)in, (uint16_t*)out, N, C,
+                               H, W, OH, OW, win, stride, dC8, dOHW, dOW);
+        else
+            hipLaunchKernelGGL(maxpool_nhwc8_kernel<CONV_BF16>, grid8, dim3(256), 0, s, (const uint16_t*)in, (uint16_t*)out, N,
+                               C, H, W, OH, OW, win, stride, dC8, dOHW, dOW);
+        return hipGetLastError();
+    }
+    dim3 grid((unsigned)((total + 255) / 256));
     switch (dtype) {
         case CONV_F32:
             hipLaunchKernelGGL(maxpool_kernel<CONV_F32>, grid, dim3(256), 0, s, (const float*)in, (float*)out, N, C, H, W, OH,

@@ -22,6 +22,8 @@
 
 namespace convfwd {
 
+typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
+
 struct u32x3 {  // what a 12-byte buffer load returns (the vector type is padded to 16 bytes)
     uint32_t x, y, z, unused;
 };
@@ -304,11 +306,32 @@ __global__ __launch_bounds__(CFG::NT) void swin16_kernel(ConvArgs a)
         }
 
 
+        const float floor_v = a.relu ? 0.0f : -__builtin_inff();
+        if (a.out_nhwc) {
+            // [N][OH][OW][K]: a lane's 4 consecutive channels of a pixel leave as one 8-byte store (K is a multiple of 4)
+            const uint32_t vo = p_ok ? (uint32_t)((img * a.OHW + p) * a.K + m0 + 4 * h) * 2u : kFarOffset;
+#pragma unroll
+            for (int mb = 0; mb < TMB; ++mb)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const float4 bq = *(const float4*)&bias_s[mb * 32 + q * 8 + h * 4];
+                    const float bv[4] = {bq.x, bq.y, bq.z, bq.w};
+                    uint32_t pk[2];
+#pragma unroll
+                    for (int e = 0; e < 2; ++e) {
+                        const float x0 = __builtin_fmaxf(acc[mb][4 * q + 2 * e] + bv[2 * e], floor_v);
+                        const float x1 = __builtin_fmaxf(acc[mb][4 * q + 2 * e + 1] + bv[2 * e + 1], floor_v);
+                        pk[e] = (uint32_t)Prec<DT>::from_f32(x0) | ((uint32_t)Prec<DT>::from_f32(x1) << 16);
+                    }
+                    const int kr = mb * 32 + q * 8;
+                    const uint32_t o = (m0 + kr + 4 * h < a.K) ? vo : kFarOffset;
+                    __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(u32x2_t, make_uint2(pk[0], pk[1])), rout, (int)o, kr * 2, 0);
+                }
+        } else {
         // byte offset of (image, channel m0 + 4h, pixel); the rows of a lane follow in steps of 1 and 5 channels
         uint32_t vo = p_ok ? (uint32_t)(img * a.K * a.OHW + p + (m0 + 4 * h) * a.OHW) * 2u : kFarOffset;
         const uint32_t step1 = (uint32_t)a.OHW * 2u, step5 = 5u * step1;
         const bool full = m0 + TM <= a.K;
-        const float floor_v = a.relu ? 0.0f : -__builtin_inff();
 #pragma unroll
         for (int mb = 0; mb < TMB; ++mb)
 #pragma unroll
@@ -324,6 +347,7 @@ __global__ __launch_bounds__(CFG::NT) void swin16_kernel(ConvArgs a)
                     if (p_ok) vo += e == 3 ? step5 : step1;
                 }
             }
+        }
         }
         if (first + 2 >= t_end) break;  // no group has a further tile
         __syncthreads();
@@ -372,6 +396,7 @@ bool swin16_valid(const Variant&, const conv_desc& d, int OH, int OW)
     const long long in_bytes = (long long)d.N * d.C * d.H * d.W * 2, out_bytes = (long long)d.N * d.K * OH * OW * 2;
     if (in_bytes > kUgemmMaxBytes || out_bytes > kUgemmMaxBytes) return false;  // scalar + vector offsets never wrap
     if ((long long)d.K * CFG::C * CFG::R * CFG::S * 2 > kUgemmMaxBytes) return false;
+    if ((d.flags & CONV_FLAG_OUT_NHWC) && (d.K % 4) != 0) return false;  // 8-byte stores of 4 channels
     const long long tiles_img = ((long long)OH * OW + CFG::TN - 1) / CFG::TN;
     if ((long long)d.N * tiles_img > (1LL << 30)) return false;
     if ((d.K + CFG::TM - 1) / CFG::TM > 256) return false;
@@ -396,6 +421,7 @@ void swin16_register(std::vector<Variant>& out)
     v.threads = CFG::NT;
     v.family = FAM_FIRSTLAYER;
     v.specificity = 6;
+    v.traits = TRAIT_PLANAR_TO_NHWC;
     v.valid = &swin16_valid<CFG>;
     v.launch = &swin16_launch<CFG>;
     out.push_back(v);

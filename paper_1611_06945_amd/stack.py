@@ -55,6 +55,7 @@ class ConvStack:
                 raise ValueError("layer %d has no channel-innermost kernel" % (i + 1))
         self.packed_filts: List[Optional[object]] = [None] * n
         self.plan_times = None
+        self.out_layouts = None   # set by the format selection: the output layout it timed and chose per layer
         self._build()
 
     # ---- geometry --------------------------------------------------------------------------------------------------
@@ -72,11 +73,21 @@ class ConvStack:
         """Layout of what layer i hands on: what the next layer consumes; [N][C][H][W] after the last layer."""
         return self.formats[i + 1] if i + 1 < len(self.shapes) else NCHW
 
+    def planar_writes_nhwc(self, i: int) -> bool:
+        """Whether a kernel for planar input can write layer i's output channel-innermost (first-layer window kernels)."""
+        if self.dtype == B.CONV_F32:
+            return False
+        d = B.desc_of(self.shapes[i], self.dtype, relu=self.relu, out_nhwc=True)
+        return B.conv_variant_count(d) > 0
+
     def _conv_out_layout(self, i: int) -> str:
-        """A channel-innermost kernel writes whatever layout is wanted next; the other kernels write [N][K][OH][OW].
-        When a pool follows, the pool converts, so the convolution keeps the layout of its own format."""
+        """A channel-innermost kernel writes whatever layout is wanted next; the planar kernels write [N][K][OH][OW],
+        except those that can write channel-innermost when that is what is wanted next.  When a pool follows a
+        channel-innermost layer, the pool converts, so the convolution keeps the layout of its own format."""
+        if self.out_layouts is not None:
+            return self.out_layouts[i]
         if self.formats[i] == NCHW:
-            return NCHW
+            return NHWC if self._handoff_layout(i) == NHWC and self.planar_writes_nhwc(i) else NCHW
         return NHWC if (i + 1) in self.pool_after else self._handoff_layout(i)
 
     def _build(self) -> None:
@@ -187,13 +198,20 @@ class ConvStack:
 
     # ---- format selection --------------------------------------------------------------------------------------------
     def _time_op(self, fn, reps: int = 20) -> float:
+        """Microseconds per call of a pool or conversion on the device.  The calls are recorded into a HIP graph and the
+        replay is timed: enqueued one by one from Python they would take longer to issue than to run."""
         torch = self.torch
         fn()
         torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            for _ in range(reps):
+                fn()
+        graph.replay()
+        torch.cuda.synchronize()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record()
-        for _ in range(reps):
-            fn()
+        graph.replay()
         e1.record()
         e1.synchronize()
         return e0.elapsed_time(e1) * 1e3 / reps
@@ -210,7 +228,7 @@ class ConvStack:
             f = torch.zeros(s.filt_shape(), dtype=self.tdt, device="cuda")
             out = torch.empty(s.out_shape(), dtype=self.tdt, device="cuda")
             for fmt in ((NCHW, NHWC) if self.nhwc_capable(i) else (NCHW,)):
-                for olay in ((NCHW, NHWC) if fmt == NHWC else (NCHW,)):
+                for olay in ((NCHW, NHWC) if fmt == NHWC or self.planar_writes_nhwc(i) else (NCHW,)):
                     d = B.desc_of(s, self.dtype, relu=self.relu, in_nhwc=fmt == NHWC, out_nhwc=olay == NHWC,
                                   filt_krsc=fmt == NHWC)
                     ws = torch.empty(max(256, B.conv_workspace_bytes(d)), dtype=torch.uint8, device="cuda")
@@ -247,11 +265,12 @@ class ConvStack:
                         nxt[want], bk[want] = total, (fmt, olay)
             best.append(nxt)
             back.append(bk)
-        want, chosen = NCHW, [None] * n
+        want, chosen, olays = NCHW, [None] * n, [None] * n
         for i in range(n - 1, -1, -1):
-            fmt, _ = back[i][want]
-            chosen[i] = fmt
+            fmt, olay = back[i][want]
+            chosen[i], olays[i] = fmt, olay
             want = fmt
         self.plan_times = {"conv_us": conv_t, "glue_us": glue_t, "input_convert_us": x_cvt, "total_us": best[n][NCHW]}
         self.formats = chosen
+        self.out_layouts = olays
         self._build()

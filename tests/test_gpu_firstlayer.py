@@ -10,11 +10,13 @@ not let them through).
 import numpy as np
 import pytest
 
+import oracle
+
 from paper_1611_06945_amd import binding as B
 from paper_1611_06945_amd import workloads as wl
 from paper_1611_06945_amd.workloads import ConvShape
 
-from gpu_util import TOL, DeviceCase, to_host_f64
+from gpu_util import TOL, DeviceCase, empty_out, to_host_f64, torch_mod
 from test_gpu_parity import assert_bit_exact, int_case, random_case, say
 
 pytestmark = pytest.mark.gpu
@@ -93,6 +95,40 @@ def test_non_finite_input_stays_inside_its_windows():
         assert np.all(~np.isfinite(got[~clean])), name
         err = np.max(np.abs(got[clean] - ref[clean])) / np.max(np.abs(ref[clean]))
         assert err <= TOL[wl.F16], "%s: error %.3g" % (name, err)
+
+
+@pytest.mark.parametrize("dtype", [wl.F16, wl.BF16])
+def test_channel_innermost_output_from_planar_input(dtype):
+    """CONV_FLAG_OUT_NHWC alone: the same kernels write [N][OH][OW][K] (what a channel-innermost second layer or pool
+    consumes) from planar input and filters; compared with the oracle after transposing back, bit-exact on integers."""
+    torch = torch_mod()
+    for si, shape in enumerate([ConvShape(2, 3, 227, 227, 96, 11, 11, 4, 0), ConvShape(3, 3, 23, 63, 40, 11, 11, 4, 0),
+                                ConvShape(2, 3, 11, 130, 64, 7, 7, 2, 3)]):
+        icase = int_case(shape, dtype, 1200 + si)
+        rcase = random_case(shape, dtype, 1210 + si)
+        desc = B.desc_of(shape, dtype, relu=True, out_nhwc=True)
+        names = [B.conv_variant_name(desc, i) for i in range(B.conv_variant_count(desc))]
+        assert names and all(n.startswith("swin_") for n in names), names
+        exp_int = wl.storage_to_f64(wl.to_storage(icase.ref().astype(np.float32), dtype), dtype)
+        for vi, name in enumerate(names):
+            say("  %s writing channel-innermost on %s" % (name, shape))
+            for case, exact in ((icase, True), (rcase, False)):
+                out = empty_out((shape.N, shape.OH, shape.OW, shape.K), dtype)
+                B.conv_force_variant(desc, vi)
+                try:
+                    B.conv_fwd(desc, case.d_in, case.d_filt, case.d_bias, out)
+                    torch.cuda.synchronize()
+                finally:
+                    B.conv_force_variant(desc, -1)
+                got = np.ascontiguousarray(np.transpose(to_host_f64(out, dtype), (0, 3, 1, 2)))
+                assert np.all(np.isfinite(got)), name
+                if exact:
+                    assert np.array_equal(got, exp_int), name
+                else:
+                    err = oracle.max_normalised_error(got, case.ref())
+                    assert err <= TOL[dtype], "%s: error %.3g" % (name, err)
+    # a channel count that is no multiple of 4 has no such kernel
+    assert B.conv_variant_count(B.desc_of(ConvShape(1, 3, 227, 227, 30, 11, 11, 4, 0), dtype, out_nhwc=True)) == 0
 
 
 def test_not_offered_outside_its_domain():
