@@ -71,7 +71,9 @@ hipError_t launch_split_reduce(const ConvArgs& a, int dtype, hipStream_t s)
 // comparison (exact and order preserving) and the winning stored pattern is written back unchanged.  Input and output
 // may each be channel-planar ([N][C][H][W]) or channel-innermost ([N][H][W][C]); one thread per output element in the
 // order of the output layout, so the pool can double as the layout conversion between two layers.
-template <int DT>
+// WIN = 3: the window is unrolled and its 9 loads are issued together (with a run-time window the loop fetches and
+// compares one element at a time, and the kernel's time is 9 memory round trips); WIN = 0: any window, run-time loops.
+template <int DT, int WIN>
 __global__ __launch_bounds__(256) void maxpool_kernel(const typename Prec<DT>::elem_t* __restrict__ in,
                                                       typename Prec<DT>::elem_t* __restrict__ out, int N, int C, int H, int W,
                                                       int OH, int OW, int win, int stride, int in_nhwc, int out_nhwc,
@@ -98,22 +100,38 @@ __global__ __launch_bounds__(256) void maxpool_kernel(const typename Prec<DT>::e
                                 : in + (((size_t)n * C + c) * H + (size_t)oy * stride) * W + (size_t)ox * stride;
     elem_t best = src[0];
     float bestf = Prec<DT>::to_f32(best);
-    for (int r = 0; r < win; ++r)
-        for (int s = 0; s < win; ++s) {
-            const elem_t v = src[r * sy + s * sx];
-            const float vf = Prec<DT>::to_f32(v);
+    if constexpr (WIN > 0) {
+        elem_t v[WIN * WIN];
+#pragma unroll
+        for (int r = 0; r < WIN; ++r)
+#pragma unroll
+            for (int s = 0; s < WIN; ++s) v[r * WIN + s] = src[r * sy + s * sx];
+#pragma unroll
+        for (int t = 1; t < WIN * WIN; ++t) {
+            const float vf = Prec<DT>::to_f32(v[t]);
             if (vf > bestf) {
                 bestf = vf;
-                best = v;
+                best = v[t];
             }
         }
+    } else {
+        for (int r = 0; r < win; ++r)
+            for (int s = 0; s < win; ++s) {
+                const elem_t v = src[r * sy + s * sx];
+                const float vf = Prec<DT>::to_f32(v);
+                if (vf > bestf) {
+                    bestf = vf;
+                    best = v;
+                }
+            }
+    }
     out[i] = best;
 }
 
 // Channel-innermost on both sides with C a multiple of 8: one thread per (output pixel, 8 channels), every tap one
 // 16-byte load.  The maximum is taken on the widened values (exact, order preserving) and narrowed back, which is
 // exact as well since it is one of the stored values.
-template <int DT>
+template <int DT, int WIN>
 __global__ __launch_bounds__(256) void maxpool_nhwc8_kernel(const uint16_t* __restrict__ in, uint16_t* __restrict__ out, int N,
                                                             int C, int H, int W, int OH, int OW, int win, int stride,
                                                             FastDiv dC8, FastDiv dOHW, FastDiv dOW)
@@ -129,16 +147,26 @@ __global__ __launch_bounds__(256) void maxpool_nhwc8_kernel(const uint16_t* __re
     float best[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) best[e] = -__builtin_inff();
-    for (int r = 0; r < win; ++r)
-        for (int s = 0; s < win; ++s) {
-            const uint4 v = *(const uint4*)(src + ((size_t)r * W + s) * C);
-            const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+    auto take = [&](const uint4& v) {
+        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const uint16_t h = (uint16_t)(e & 1 ? w[e >> 1] >> 16 : w[e >> 1] & 0xFFFFu);
-                best[e] = __builtin_fmaxf(best[e], Prec<DT>::to_f32(h));
-            }
+        for (int e = 0; e < 8; ++e) {
+            const uint16_t h = (uint16_t)(e & 1 ? w[e >> 1] >> 16 : w[e >> 1] & 0xFFFFu);
+            best[e] = __builtin_fmaxf(best[e], Prec<DT>::to_f32(h));
         }
+    };
+    if constexpr (WIN > 0) {
+        uint4 v[WIN * WIN];
+#pragma unroll
+        for (int r = 0; r < WIN; ++r)
+#pragma unroll
+            for (int s = 0; s < WIN; ++s) v[r * WIN + s] = *(const uint4*)(src + ((size_t)r * W + s) * C);
+#pragma unroll
+        for (int t = 0; t < WIN * WIN; ++t) take(v[t]);
+    } else {
+        for (int r = 0; r < win; ++r)
+            for (int s = 0; s < win; ++s) take(*(const uint4*)(src + ((size_t)r * W + s) * C));
+    }
     uint32_t o[4];
 #pragma unroll
     for (int e = 0; e < 4; ++e)
@@ -149,7 +177,7 @@ __global__ __launch_bounds__(256) void maxpool_nhwc8_kernel(const uint16_t* __re
 // The same pooling when input and output layouts differ: a tile of 32 channels x 32 output pixels of one image is
 // pooled by threads arranged along the INPUT's contiguous axis, parked in LDS, and written out by threads arranged
 // along the OUTPUT's contiguous axis, so that both sides of the conversion move contiguous runs.
-template <int DT, bool IN_NHWC>
+template <int DT, bool IN_NHWC, int WIN>
 __global__ __launch_bounds__(256) void maxpool_xlayout_kernel(const typename Prec<DT>::elem_t* __restrict__ in,
                                                               typename Prec<DT>::elem_t* __restrict__ out, int C, int H, int W,
                                                               int OH, int OW, int win, int stride, FastDiv dOW)
@@ -171,15 +199,31 @@ __global__ __launch_bounds__(256) void maxpool_xlayout_kernel(const typename Pre
                                         : in + (((size_t)n * C + c) * H + (size_t)oy * stride) * W + (size_t)ox * stride;
             elem_t best = src[0];
             float bestf = Prec<DT>::to_f32(best);
-            for (int r = 0; r < win; ++r)
-                for (int s = 0; s < win; ++s) {
-                    const elem_t v = src[r * sy + s * sx];
-                    const float vf = Prec<DT>::to_f32(v);
+            if constexpr (WIN > 0) {
+                elem_t v[WIN * WIN];
+#pragma unroll
+                for (int r = 0; r < WIN; ++r)
+#pragma unroll
+                    for (int s = 0; s < WIN; ++s) v[r * WIN + s] = src[r * sy + s * sx];
+#pragma unroll
+                for (int t = 1; t < WIN * WIN; ++t) {
+                    const float vf = Prec<DT>::to_f32(v[t]);
                     if (vf > bestf) {
                         bestf = vf;
-                        best = v;
+                        best = v[t];
                     }
                 }
+            } else {
+                for (int r = 0; r < win; ++r)
+                    for (int s = 0; s < win; ++s) {
+                        const elem_t v = src[r * sy + s * sx];
+                        const float vf = Prec<DT>::to_f32(v);
+                        if (vf > bestf) {
+                            bestf = vf;
+                            best = v;
+                        }
+                    }
+            }
             tile[cl][pl] = best;
         }
     }
@@ -198,7 +242,7 @@ __global__ __launch_bounds__(256) void maxpool_xlayout_kernel(const typename Pre
     }
 }
 
-template <int DT>
+template <int DT, int WIN>
 void launch_maxpool_xlayout(int N, int C, int H, int W, int OH, int OW, int win, int stride, bool in_nhwc, const void* in,
                             void* out, hipStream_t s)
 {
@@ -206,54 +250,56 @@ void launch_maxpool_xlayout(int N, int C, int H, int W, int OH, int OW, int win,
     dim3 grid((unsigned)((OH * OW + 31) / 32), (unsigned)((C + 31) / 32), (unsigned)N);
     const FastDiv dOW = make_fastdiv((uint32_t)OW);
     if (in_nhwc)
-        hipLaunchKernelGGL((maxpool_xlayout_kernel<DT, true>), grid, dim3(256), 0, s, (const elem_t*)in, (elem_t*)out, C, H, W,
-                           OH, OW, win, stride, dOW);
+        hipLaunchKernelGGL((maxpool_xlayout_kernel<DT, true, WIN>), grid, dim3(256), 0, s, (const elem_t*)in, (elem_t*)out, C,
+                           H, W, OH, OW, win, stride, dOW);
     else
-        hipLaunchKernelGGL((maxpool_xlayout_kernel<DT, false>), grid, dim3(256), 0, s, (const elem_t*)in, (elem_t*)out, C, H, W,
-                           OH, OW, win, stride, dOW);
+        hipLaunchKernelGGL((maxpool_xlayout_kernel<DT, false, WIN>), grid, dim3(256), 0, s, (const elem_t*)in, (elem_t*)out, C,
+                           H, W, OH, OW, win, stride, dOW);
+}
+
+// WIN = 3 (unrolled window) or 0 (any window)
+template <int DT, int WIN>
+hipError_t launch_maxpool_typed(int N, int C, int H, int W, int win, int stride, bool in_nhwc, bool out_nhwc, const void* in,
+                                void* out, hipStream_t s)
+{
+    typedef typename Prec<DT>::elem_t elem_t;
+    const int OH = (H - win) / stride + 1, OW = (W - win) / stride + 1;
+    if (in_nhwc != out_nhwc && N <= 65535 && (C + 31) / 32 <= 65535) {
+        launch_maxpool_xlayout<DT, WIN>(N, C, H, W, OH, OW, win, stride, in_nhwc, in, out, s);
+        return hipGetLastError();
+    }
+    const size_t total = (size_t)N * C * OH * OW;
+    const FastDiv dOHW = make_fastdiv((uint32_t)(OH * OW)), dOW = make_fastdiv((uint32_t)OW), dC = make_fastdiv((uint32_t)C);
+    if constexpr (DT != CONV_F32) {
+        if (in_nhwc && out_nhwc && (C % 8) == 0 && total / 8 < (1u << 31)) {
+            const FastDiv dC8 = make_fastdiv((uint32_t)(C / 8));
+            dim3 grid8((unsigned)((total / 8 + 255) / 256));
+            hipLaunchKernelGGL((maxpool_nhwc8_kernel<DT, WIN>), grid8, dim3(256), 0, s, (const uint16_t*)in, (uint16_t*)out, N, C,
+                               H, W, OH, OW, win, stride, dC8, dOHW, dOW);
+            return hipGetLastError();
+        }
+    }
+    dim3 grid((unsigned)((total + 255) / 256));
+    hipLaunchKernelGGL((maxpool_kernel<DT, WIN>), grid, dim3(256), 0, s, (const elem_t*)in, (elem_t*)out, N, C, H, W, OH, OW, win,
+                       stride, (int)in_nhwc, (int)out_nhwc, dOHW, dOW, dC);
+    return hipGetLastError();
 }
 
 hipError_t launch_maxpool(int N, int C, int H, int W, int win, int stride, int dtype, bool in_nhwc, bool out_nhwc,
                           const void* in, void* out, hipStream_t s)
 {
-    const int OH = (H - win) / stride + 1, OW = (W - win) / stride + 1;
-    if (in_nhwc != out_nhwc && N <= 65535 && (C + 31) / 32 <= 65535) {
-        switch (dtype) {
-            case CONV_F32: launch_maxpool_xlayout<CONV_F32>(N, C, H, W, OH, OW, win, stride, in_nhwc, in, out, s); break;
-            case CONV_F16: launch_maxpool_xlayout<CONV_F16>(N, C, H, W, OH, OW, win, stride, in_nhwc, in, out, s); break;
-            default: launch_maxpool_xlayout<CONV_BF16>(N, C, H, W, OH, OW, win, stride, in_nhwc, in, out, s); break;
-        }
-        return hipGetLastError();
-    }
-    const size_t total = (size_t)N * C * OH * OW;
-    const FastDiv dOHW = make_fastdiv((uint32_t)(OH * OW)), dOW = make_fastdiv((uint32_t)OW), dC = make_fastdiv((uint32_t)C);
-    if (in_nhwc && out_nhwc && dtype != CONV_F32 && (C % 8) == 0 && total / 8 < (1u << 31)) {
-        const FastDiv dC8 = make_fastdiv((uint32_t)(C / 8));
-        dim3 grid8((unsigned)((total / 8 + 255) / 256));
-        if (dtype == CONV_F16)
-            hipLaunchKernelGGL(maxpool_nhwc8_kernel<CONV_F16>, grid8, dim3(256), 0, s, (const uint16_t*)in, (uint16_t*)out, N, C,
-                               H, W, OH, OW, win, stride, dC8, dOHW, dOW);
-        else
-            hipLaunchKernelGGL(maxpool_nhwc8_kernel<CONV_BF16>, grid8, dim3(256), 0, s, (const uint16_t*)in, (uint16_t*)out, N,
-                               C, H, W, OH, OW, win, stride, dC8, dOHW, dOW);
-        return hipGetLastError();
-    }
-    dim3 grid((unsigned)((total + 255) / 256));
+    const bool w3 = win == 3;
     switch (dtype) {
         case CONV_F32:
-            hipLaunchKernelGGL(maxpool_kernel<CONV_F32>, grid, dim3(256), 0, s, (const float*)in, (float*)out, N, C, H, W, OH,
-                               OW, win, stride, (int)in_nhwc, (int)out_nhwc, dOHW, dOW, dC);
-            break;
+            return w3 ? launch_maxpool_typed<CONV_F32, 3>(N, C, H, W, win, stride, in_nhwc, out_nhwc, in, out, s)
+                      : launch_maxpool_typed<CONV_F32, 0>(N, C, H, W, win, stride, in_nhwc, out_nhwc, in, out, s);
         case CONV_F16:
-            hipLaunchKernelGGL(maxpool_kernel<CONV_F16>, grid, dim3(256), 0, s, (const uint16_t*)in, (uint16_t*)out, N, C, H,
-                               W, OH, OW, win, stride, (int)in_nhwc, (int)out_nhwc, dOHW, dOW, dC);
-            break;
+            return w3 ? launch_maxpool_typed<CONV_F16, 3>(N, C, H, W, win, stride, in_nhwc, out_nhwc, in, out, s)
+                      : launch_maxpool_typed<CONV_F16, 0>(N, C, H, W, win, stride, in_nhwc, out_nhwc, in, out, s);
         default:
-            hipLaunchKernelGGL(maxpool_kernel<CONV_BF16>, grid, dim3(256), 0, s, (const uint16_t*)in, (uint16_t*)out, N, C, H,
-                               W, OH, OW, win, stride, (int)in_nhwc, (int)out_nhwc, dOHW, dOW, dC);
-            break;
+            return w3 ? launch_maxpool_typed<CONV_BF16, 3>(N, C, H, W, win, stride, in_nhwc, out_nhwc, in, out, s)
+                      : launch_maxpool_typed<CONV_BF16, 0>(N, C, H, W, win, stride, in_nhwc, out_nhwc, in, out, s);
     }
-    return hipGetLastError();
 }
 
 // out[a][s][b] = in[a][b][s]: 32x32 tiles through LDS so that both the reads (along s) and the writes (along b) are
