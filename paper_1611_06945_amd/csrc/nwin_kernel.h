@@ -177,13 +177,18 @@ __global__ __launch_bounds__(CFG::NT) void nwin_kernel(ConvArgs a)
     if (chunk_begin < chunk_end) {
         __syncthreads();  // zero fill done before the first real write
         store_chunk(0);
+        // The registers are free again: the next chunk's loads start now and have a whole chunk's products to arrive,
+        // not the part of one that precedes their store.  Loads are unconditional (past the last chunk they fetch the
+        // neighbouring channels or fall outside the tensors; the data is not used): a conditional load makes every
+        // later wait assume the worst.
+        load_chunk(chunk_begin + 1);
         __syncthreads();
         int buf = 0;
         for (int chunk = chunk_begin; chunk < chunk_end; ++chunk) {
             const bool more = chunk + 1 < chunk_end;
-            if (more) load_chunk(chunk + 1);
             compute(buf, tap_first{}, tap_mid{});
             if (more) store_chunk(buf ^ 1);  // the other buffer was last read before the previous barrier
+            load_chunk(chunk + 2);
             compute(buf, tap_mid{}, tap_last{});
             __syncthreads();
             buf ^= 1;
