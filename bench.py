@@ -416,7 +416,9 @@ def main():
         sh = w.shape
         tiles = sh.N * ((sh.OH + 1) // 2) * ((sh.OW + 1) // 2)
         executed = 2.0 * 16 * (-(-sh.K // tm) * tm) * (-(-tiles // tt) * tt) * sh.C
-        roof["algorithm"] = "winograd F(2x2,3x3): filter transform kernel + fused product kernel per launch"
+        fused = variant.endswith("_ff")
+        roof["algorithm"] = ("winograd F(2x2,3x3): one kernel per launch (filter, input and output transforms around the MFMA planes)"
+                             if fused else "winograd F(2x2,3x3): filter transform kernel + fused product kernel per launch")
         roof["mfma_flops_executed"] = executed
         roof["frac_executed"] = round(executed / (kern_ms * 1e-3) / 1e12 / PEAK_TFLOPS[dt], 5)
         n = B.conv_variant_count(r.desc)
@@ -425,17 +427,14 @@ def main():
         # the same layer with the filters handed over in the Winograd domain (the transform is then a conversion done
         # once, ahead of time, as the paper does for constant weights): an extra figure, never the headline value
         pre = B.desc_of(sh, w.dtype, relu=True, filt_winograd=True)
-        pre_names = [B.conv_variant_name(pre, i) for i in range(B.conv_variant_count(pre))]
-        if variant in pre_names:
+        if B.conv_variant_count(pre) > 0:
             x, f, b, o = r.sets[0]
             u = torch.empty(B.conv_transformed_filter_bytes(pre), dtype=torch.uint8, device="cuda")
             B.conv_transform_filters(pre, f, u)
-            B.conv_force_variant(pre, pre_names.index(variant))
-            try:
-                us = min(B.conv_time_us(pre, x, u, b, o, None, 0, launches=200) for _ in range(3))
-            finally:
-                B.conv_force_variant(pre, -1)
-            roof["pretransformed_filters"] = {"us": round(us, 2), "tflops": round(sh.flops / (us * 1e-6) / 1e12, 2),
+            B.conv_autotune(pre, x, u, b, o, None, 0)
+            us = min(B.conv_time_us(pre, x, u, b, o, None, 0, launches=200) for _ in range(3))
+            roof["pretransformed_filters"] = {"variant": B.conv_variant_name(pre, -1), "us": round(us, 2),
+                                              "tflops": round(sh.flops / (us * 1e-6) / 1e12, 2),
                                               "frac": round(sh.flops / (us * 1e-6) / 1e12 / PEAK_TFLOPS[dt], 5),
                                               "frac_executed": round(executed / (us * 1e-6) / 1e12 / PEAK_TFLOPS[dt], 5)}
         if direct:

@@ -17,6 +17,10 @@ void register_wino_f32(std::vector<Variant>& out)
     wino_register<WinoCfg<1, 3, 2, 1, 8>>(out);
     wino_register<WinoCfg<4, 2, 2, 1, 8>>(out);
     wino_register<WinoCfg<2, 4, 2, 2, 8>>(out);
+    // filter transform inside the product kernel: no filter kernel, no workspace
+    wino_register<WinoCfg<2, 3, 2, 1, 8, 1>>(out);
+    wino_register<WinoCfg<3, 2, 2, 1, 8, 1>>(out);
+    wino_register<WinoCfg<2, 2, 2, 1, 8, 1>>(out);
 }
 
 hipError_t launch_wino_filter_transform(const float* filt, float* out, int K, int C, hipStream_t s)

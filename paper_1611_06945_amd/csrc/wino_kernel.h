@@ -27,9 +27,15 @@
 
 namespace convfwd {
 
-template <int MBLK_, int NBLK_, int XW_, int LBE_, int CB_>
+struct WinoF3 {  // what a 12-byte buffer load returns (the vector type is padded to 16 bytes)
+    float x, y, z, unused;
+};
+
+template <int MBLK_, int NBLK_, int XW_, int LBE_, int CB_, int FF_ = 0>
 struct WinoCfg {
     static constexpr int MBLK = MBLK_, NBLK = NBLK_, XW = XW_, LBE = LBE_, CB = CB_;
+    // FF: the filter transform runs inside the product kernel, step by step (no filter kernel, no workspace)
+    static constexpr bool FF = FF_ != 0;
     static constexpr int WAVES = 16 / XW;        // every wave owns XW of the 16 transform planes
     static constexpr int NT = 64 * WAVES;
     static constexpr int TM = 16 * MBLK;         // output channels per workgroup
@@ -40,6 +46,11 @@ struct WinoCfg {
     static constexpr int VP = TT + (TT % 32 == 0 ? 16 : 0);
     static constexpr int V_FLOATS = 16 * CB * VP;  // one buffer of transformed tiles
     static constexpr int MP = TT + 4;            // row pitch of the plane buffer of the epilogue (4 mod 8: conflict-free writes)
+    // FF: transformed filters of a step in LDS, [16 planes][4 lane groups][TM channels][HN]; the group pitch is 8 mod 32
+    // floats so that the transform's 8 writes of one filter row (4 groups x 2) fall on different banks
+    static constexpr int UQ = TM * HN + 8;
+    static constexpr int U_FLOATS = FF ? 16 * 4 * UQ : 0;
+    static_assert(!FF || (CB == 8 && TM * CB <= NT), "one filter per thread and step");
     static_assert(16 % XW == 0 && (CB == 8 || CB == 16) && TT * CB <= NT, "one transform task per thread");
 };
 
@@ -71,7 +82,7 @@ template <class CFG>
 size_t wino_lds_bytes(int N, int OH, int OW)
 {
     const WinoGeom g = wino_geom<CFG>(N, OH, OW);
-    const size_t pipe = sizeof(float) * (2 * (size_t)CFG::V_FLOATS + 2 * (size_t)CFG::CB * g.raw_chan);
+    const size_t pipe = sizeof(float) * (2 * (size_t)CFG::V_FLOATS + 2 * (size_t)CFG::CB * g.raw_chan + 2 * (size_t)CFG::U_FLOATS);
     const size_t epi = sizeof(float) * 16 * (size_t)CFG::TM * CFG::MP;
     return pipe > epi ? pipe : epi;
 }
@@ -145,6 +156,8 @@ __global__ __launch_bounds__(CFG::NT) void wino_kernel(ConvArgs a)
 {
     constexpr int MBLK = CFG::MBLK, NBLK = CFG::NBLK, XW = CFG::XW, LBE = CFG::LBE, NT = CFG::NT, TM = CFG::TM, TT = CFG::TT;
     constexpr int CB = CFG::CB, HN = CFG::HN, V_FLOATS = CFG::V_FLOATS, MP = CFG::MP, VP = CFG::VP;
+    constexpr bool FF = CFG::FF;
+    constexpr int UQ = CFG::UQ, U_FLOATS = CFG::U_FLOATS;
     constexpr uint32_t kFar = 0x80000000u;  // tensors stay below 2 GiB: this offset plus any in-range scalar offset is out of range
     typedef Mma<CONV_F32, 16> mma_t;
     extern __shared__ __attribute__((aligned(16))) float smem[];
@@ -153,6 +166,7 @@ __global__ __launch_bounds__(CFG::NT) void wino_kernel(ConvArgs a)
     const int PWL = geo.PWL, raw_chan = geo.raw_chan;
     float* const Vs0 = smem;                      // [2][16][CB][VP]
     float* const Rs0 = Vs0 + 2 * V_FLOATS;        // [2][CB][raw_chan]: rows [nr_max][4][PWL] per channel
+    float* const Us0 = Rs0 + 2 * CB * raw_chan;   // FF: [2][16][4][UQ]
 
     const int tid = threadIdx.x, lane = tid & 63, li = lane & 15, kq = lane >> 4;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -214,6 +228,7 @@ __global__ __launch_bounds__(CFG::NT) void wino_kernel(ConvArgs a)
 
     auto load_filters = [&](auto setc, int chunk) {
         constexpr int set = decltype(setc)::value;
+        if constexpr (FF) return;
         const uint32_t soff = (uint32_t)chunk * u_step;
 #pragma unroll
         for (int x = 0; x < XW; ++x)
@@ -233,6 +248,76 @@ __global__ __launch_bounds__(CFG::NT) void wino_kernel(ConvArgs a)
                     af[set][x][mb][3] = t.w;
                 }
             }
+    };
+    // FF: filter task (kl, cl) = (t / CB, t % CB) owns filter (m0 + kl, chunk*CB + cl) of every step: its 9 taps are 36
+    // contiguous bytes, the CB filters of one output channel 36*CB contiguous bytes.  They are loaded two steps ahead,
+    // transformed one step ahead
+    // and written to LDS in the layout the MFMA lanes read: plane, lane group q = cl % 4, channel, h = cl / 4.
+    const __amdgpu_buffer_rsrc_t rf = make_rsrc(a.filt, a.filt_bytes);
+    // the filter tasks take the threads from the top of the workgroup, the input-transform tasks those from the bottom: the
+    // waves that do both are as few as possible
+    const int f_t = tid - (NT - TM * CB);
+    const bool f_task = FF && f_t >= 0;
+    const int f_kl = (f_t >= 0 ? f_t : 0) / CB, f_cl = (f_t >= 0 ? f_t : 0) % CB;
+    const uint32_t f_off = (f_task && m0 + f_kl < a.K) ? (uint32_t)(((m0 + f_kl) * a.C + f_cl) * 9) * 4u : kFar;
+    const int f_dst = (f_cl & 3) * UQ + f_kl * HN + (f_cl >> 2);
+    float fr[2][FF ? 9 : 1];
+    auto load_raw = [&](auto setc, int chunk) {
+        constexpr int set = decltype(setc)::value;
+        if constexpr (FF) {
+            const uint32_t soff = (uint32_t)(chunk * CB * 9) * 4u;
+#pragma unroll
+            for (int j = 0; j < 3; ++j) {
+                const WinoF3 t = __builtin_bit_cast(WinoF3, __builtin_amdgcn_raw_buffer_load_b96(rf, (int)(f_off + 12u * j), (int)soff, 0));
+                fr[set][3 * j + 0] = t.x;
+                fr[set][3 * j + 1] = t.y;
+                fr[set][3 * j + 2] = t.z;
+            }
+        }
+    };
+    auto transform_filters = [&](auto setc, auto bufc) {
+        constexpr int set = decltype(setc)::value, buf = decltype(bufc)::value;
+        if constexpr (FF) {
+            if (f_task) {
+                // G g G^T with the halves folded into fused multiply-adds: (a0 + a2 +- a1) / 2 = fma(a0 + a2, 1/2, +- a1 / 2)
+                // (4 operations per column or row instead of 5; exact whenever the direct form is, e.g. on small integers)
+                const float* g = fr[set];
+                float gg[4][3];
+#pragma unroll
+                for (int j = 0; j < 3; ++j) {
+                    const float g0 = g[j], g1 = g[3 + j], g2 = g[6 + j];
+                    const float t = g0 + g2, hg = 0.5f * g1;
+                    gg[0][j] = g0;
+                    gg[1][j] = __builtin_fmaf(t, 0.5f, hg);
+                    gg[2][j] = __builtin_fmaf(t, 0.5f, -hg);
+                    gg[3][j] = g2;
+                }
+                float* Us = Us0 + buf * U_FLOATS + f_dst;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const float a0 = gg[i][0], a1 = gg[i][1], a2 = gg[i][2];
+                    const float t = a0 + a2, ha = 0.5f * a1;
+                    Us[(4 * i + 0) * 4 * UQ] = a0;
+                    Us[(4 * i + 1) * 4 * UQ] = __builtin_fmaf(t, 0.5f, ha);
+                    Us[(4 * i + 2) * 4 * UQ] = __builtin_fmaf(t, 0.5f, -ha);
+                    Us[(4 * i + 3) * 4 * UQ] = a2;
+                }
+            }
+        }
+    };
+    auto read_filters = [&](auto bufc) {  // FF: this wave's planes, lane (li, kq): channels m0 + mb*16 + li, h = 0..HN-1
+        constexpr int buf = decltype(bufc)::value;
+        if constexpr (FF) {
+            const float* Us = Us0 + buf * U_FLOATS + ((wave * XW) * 4 + kq) * UQ + li * HN;
+#pragma unroll
+            for (int x = 0; x < XW; ++x)
+#pragma unroll
+                for (int mb = 0; mb < MBLK; ++mb) {
+                    const float2 t = *(const float2*)&Us[x * 4 * UQ + mb * 16 * HN];
+                    af[buf][x][mb][0] = t.x;
+                    af[buf][x][mb][1] = t.y;
+                }
+        }
     };
     auto load_rows = [&](auto setc, int chunk) {
         constexpr int set = decltype(setc)::value;
@@ -353,6 +438,8 @@ __global__ __launch_bounds__(CFG::NT) void wino_kernel(ConvArgs a)
     // entering step i: Vs[i&1] holds the transformed tiles of step i and fragment set bf[i&1] was read from it; af[i&1]
     // is in flight or loaded; Rs[(i+1)&1] holds the rows of step i+1; r_reg[(i+1)&1] holds the rows of step i+2.
     load_filters(c0_t{}, 0);
+    load_raw(c0_t{}, 0);
+    load_raw(c1_t{}, 1);
     load_rows(c0_t{}, 0);
     load_rows(c1_t{}, 1);
     for (int i = tid; i < 2 * CB * raw_chan; i += NT) Rs0[i] = 0.0f;  // border and unused rows stay zero for the whole kernel
@@ -363,8 +450,10 @@ __global__ __launch_bounds__(CFG::NT) void wino_kernel(ConvArgs a)
     __syncthreads();
     transform_read(c0_t{});
     transform_write(c0_t{});
+    transform_filters(c0_t{}, c0_t{});
     __syncthreads();
     read_tiles(c0_t{});
+    read_filters(c0_t{});
 
     // One step, one barrier.  The products of step i surround the LDS traffic that prepares steps i+1 and i+2, and the
     // last quarter of them runs after the barrier, behind the reads of the next step's fragments.
@@ -373,18 +462,21 @@ __global__ __launch_bounds__(CFG::NT) void wino_kernel(ConvArgs a)
         typedef std::integral_constant<int, buf ^ 1> other_t;
         const bool nxt = i + 1 < chunks, nxt2 = i + 2 < chunks;
         load_filters(other_t{}, i + 1);
+        load_raw(bufc, i + 2);   // FF: register set `buf` was transformed in the previous step
         load_rows(bufc, i + 3);
         if (nxt) transform_read(other_t{});
         __builtin_amdgcn_sched_barrier(0);
         mma_range(bufc, c0_t{}, u_a{});
         __builtin_amdgcn_sched_barrier(0);
         if (nxt) transform_write(other_t{});
+        if (nxt) transform_filters(other_t{}, other_t{});
         if (nxt2) store_rows(other_t{}, bufc);
         __builtin_amdgcn_sched_barrier(0);
         mma_range(bufc, u_a{}, u_b{});
         __builtin_amdgcn_sched_barrier(0);  // the products above cover the completion of the LDS writes before the barrier
         __syncthreads();
         if (nxt) read_tiles(other_t{});
+        if (nxt) read_filters(other_t{});
         __builtin_amdgcn_sched_barrier(0);
         mma_range(bufc, u_b{}, u_c{});
     };
@@ -457,7 +549,7 @@ __global__ __launch_bounds__(CFG::NT) void wino_kernel(ConvArgs a)
 template <class CFG>
 size_t wino_ws_bytes(const Variant& v, const conv_desc& d, int OH, int OW)
 {
-    if (d.flags & CONV_FLAG_FILT_WINOGRAD) return 0;  // the caller hands the transformed filters over
+    if (CFG::FF || (d.flags & CONV_FLAG_FILT_WINOGRAD)) return 0;  // transformed in the kernel, or handed over by the caller
     return (size_t)16 * wino_kpitch(d.K) * d.C * sizeof(float);
 }
 
@@ -473,7 +565,9 @@ hipError_t wino_launch(const Variant& v, ConvArgs& a, hipStream_t s)
     a.dX = make_fastdiv((uint32_t)g.TW);
     a.dY = make_fastdiv((uint32_t)g.TH);
     a.dZ = make_fastdiv((uint32_t)g.tiles_img);
-    if (a.filt_wino) {
+    if (CFG::FF) {
+        // nothing to prepare: the product kernel reads the filters as they are
+    } else if (a.filt_wino) {
         a.ws = (float*)const_cast<void*>(a.filt);  // already in the Winograd domain
     } else {
         hipLaunchKernelGGL(wino_filter_kernel<CFG::CB>, dim3((unsigned)((a.K + 31) / 32), (unsigned)(a.C / CFG::CB)), dim3(32 * CFG::CB), 0, s,
@@ -491,7 +585,7 @@ bool wino_valid(const Variant& v, const conv_desc& d, int OH, int OW)
 {
     if (d.dtype != CONV_F32 || d.R != 3 || d.S != 3 || d.stride != 1 || d.pad > 1) return false;
     if ((d.C % CFG::CB) != 0) return false;
-    if ((d.flags & CONV_FLAG_FILT_WINOGRAD) && CFG::CB != 8) return false;  // the hand-over layout is that of the 8-channel step
+    if ((d.flags & CONV_FLAG_FILT_WINOGRAD) && (CFG::CB != 8 || CFG::FF)) return false;  // the hand-over layout is that of the 8-channel step
     const WinoGeom g = wino_geom<CFG>(d.N, OH, OW);
     // every (input row of the workgroup's tile rows, x) needs a staging slot
     if ((long long)g.nr_max * 4 * d.W > (long long)CFG::NT * CFG::LBE) return false;
@@ -510,7 +604,7 @@ void wino_register(std::vector<Variant>& out)
 {
     Variant v;
     char buf[96];
-    snprintf(buf, sizeof buf, "wino_f32_M%dT%d_x%d_c%d_e%d", CFG::TM, CFG::TT, CFG::XW, CFG::CB, CFG::LBE);
+    snprintf(buf, sizeof buf, "wino_f32_M%dT%d_x%d_c%d_e%d%s", CFG::TM, CFG::TT, CFG::XW, CFG::CB, CFG::LBE, CFG::FF ? "_ff" : "");
     v.name = buf;
     v.dtype = CONV_F32;
     v.split = 1;

@@ -134,3 +134,33 @@ def test_filters_handed_over_in_the_winograd_domain():
             ref = case.run(variant=plain_names.index(name))       # the same variant transforming in the call
             assert np.array_equal(out.cpu().numpy(), ref.cpu().numpy()), name
             assert case.error(out) <= TOL[wl.F32]
+
+
+def test_variants_that_transform_filters_in_the_kernel_need_no_workspace():
+    """The "_ff" variants read the filters as they are: conv_fwd (no workspace) can run them, and once the layer has been
+    autotuned that entry point uses the fastest variant that needs no workspace."""
+    torch = torch_mod()
+    shape = ConvShape(4, 32, 13, 13, 96, 3, 3, 1, 1)
+    case = random_case(shape, wl.F32, 1010)
+    ff = [(i, n) for i, n in wino_variants(case) if n.endswith("_ff")]
+    assert ff
+    for vi, name in ff:
+        assert B.conv_variant_workspace(case.desc, vi) == 0
+        err = case.error(case.run(variant=vi, with_ws=False))
+        say("  %s through conv_fwd: max normalised error %.3g" % (name, err))
+        assert err <= TOL[wl.F32], "%s: error %.3g" % (name, err)
+    ws = case.workspace()
+    out = empty_out(shape.out_shape(), wl.F32)
+    B.conv_autotune(case.desc, case.d_in, case.d_filt, case.d_bias, out, ws, ws.numel())
+    n = B.conv_variant_count(case.desc)
+    times = {B.conv_variant_name(case.desc, i): B.conv_variant_time_us(case.desc, i) for i in range(n)}
+    no_ws = {B.conv_variant_name(case.desc, i) for i in range(n) if B.conv_variant_workspace(case.desc, i) == 0}
+    fastest_no_ws = min(no_ws, key=lambda nm: times[nm])
+    # conv_fwd has no workspace to offer: the name reported for it is the fastest variant that needs none
+    out2 = empty_out(shape.out_shape(), wl.F32)
+    B.conv_fwd(case.desc, case.d_in, case.d_filt, case.d_bias, out2)
+    torch.cuda.synchronize()
+    assert case.error(out2) <= TOL[wl.F32]
+    say("  fastest without workspace: %s (%.1f us)" % (fastest_no_ws, times[fastest_no_ws]))
+    assert B.conv_variant_name(case.desc, -2) == fastest_no_ws   # idx -2: what conv_fwd runs
+    B.conv_cache_clear()
