@@ -411,11 +411,15 @@ def main():
         # also rates the vendor library's Winograd kernels); the MFMA units execute 2.25x fewer multiplications, on tiles
         # padded to the workgroup shape.  Both views are reported, next to the fastest direct variant the tuner measured.
         import re
-        m = re.match(r"wino_f32_M(\d+)T(\d+)_", variant)
-        tm, tt = int(m.group(1)), int(m.group(2))
         sh = w.shape
         tiles = sh.N * ((sh.OH + 1) // 2) * ((sh.OW + 1) // 2)
-        executed = 2.0 * 16 * (-(-sh.K // tm) * tm) * (-(-tiles // tt) * tt) * sh.C
+
+        def executed_flops(name):
+            m = re.match(r"wino_f32_M(\d+)T(\d+)_", name)
+            tm, tt = int(m.group(1)), int(m.group(2))
+            return 2.0 * 16 * (-(-sh.K // tm) * tm) * (-(-tiles // tt) * tt) * sh.C
+
+        executed = executed_flops(variant)
         fused = variant.endswith("_ff")
         roof["algorithm"] = ("winograd F(2x2,3x3): one kernel per launch (filter, input and output transforms around the MFMA planes)"
                              if fused else "winograd F(2x2,3x3): filter transform kernel + fused product kernel per launch")
@@ -433,10 +437,11 @@ def main():
             B.conv_transform_filters(pre, f, u)
             B.conv_autotune(pre, x, u, b, o, None, 0)
             us = min(B.conv_time_us(pre, x, u, b, o, None, 0, launches=200) for _ in range(3))
-            roof["pretransformed_filters"] = {"variant": B.conv_variant_name(pre, -1), "us": round(us, 2),
+            pre_variant = B.conv_variant_name(pre, -1)
+            roof["pretransformed_filters"] = {"variant": pre_variant, "us": round(us, 2),
                                               "tflops": round(sh.flops / (us * 1e-6) / 1e12, 2),
                                               "frac": round(sh.flops / (us * 1e-6) / 1e12 / PEAK_TFLOPS[dt], 5),
-                                              "frac_executed": round(executed / (us * 1e-6) / 1e12 / PEAK_TFLOPS[dt], 5)}
+                                              "frac_executed": round(executed_flops(pre_variant) / (us * 1e-6) / 1e12 / PEAK_TFLOPS[dt], 5)}
         if direct:
             t_us, nm = min(direct)
             roof["best_direct"] = {"variant": nm, "tuner_us": round(t_us, 2),
