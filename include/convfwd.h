@@ -46,7 +46,8 @@ enum {
     CONV_FLAG_RELU = 1u,      /* act = max(x,0); without it act is the identity */
     /* Optional channel-innermost formats (the paper's explicit data-format conversions, Section 3 "Graph-level
      * Optimizations"): the same operation on tensors stored as in [N][H][W][C], filt [K][R][S][C], out [N][OH][OW][K].
-     * Kernels exist for fp16/bf16 with IN_NHWC and FILT_KRSC both set and C % 8 == 0 (and K % 8 == 0 with OUT_NHWC),
+     * Kernels exist for fp16/bf16 with IN_NHWC and FILT_KRSC both set, C % 8 == 0 (and K % 8 == 0 with OUT_NHWC) and
+     * an input and a filter tensor below 1 GiB each,
      * and, with OUT_NHWC alone (planar input and filters, channel-innermost output), for the fp16/bf16 first layers the
      * strided window kernels serve (3 channels, 11x11 stride 4 or 7x7 stride 2; K % 4 == 0): the conversion then costs
      * nothing.  Any other combination of these bits gives CONV_ENOVARIANT.  conv_convert_layout() converts tensors. */

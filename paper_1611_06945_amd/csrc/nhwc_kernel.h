@@ -272,7 +272,7 @@ bool nhwc_valid(const Variant& v, const conv_desc& d, int OH, int OW)
     if (CFG::TM > kcap) return false;
     if (CFG::TM == 96 && (d.K % 96) != 0) return false;
     const long long pcap = ((P + 63) / 64) * 64;
-    if (CFG::TN > pcap) return false;
+    if (CFG::TN > pcap && CFG::TM > 32) return false;  // the smallest channel tile stays valid however few the pixels
     const long long steps = (Q + CFG::TK - 1) / CFG::TK;
     if (v.split > 1 && steps < 2LL * v.split) return false;
     if (v.split > 1 && (long long)d.K * P * 4 >= (1LL << 32)) return false;

@@ -102,6 +102,8 @@ NHWC_SHAPES = [
     ConvShape(3, 64, 13, 13, 40, 3, 3, 1, 1),    # window kernel: one band per image, ragged K
     ConvShape(2, 128, 14, 10, 72, 3, 3, 1, 0),   # window kernel: no padding, K over two 64-row tiles, four chunks
     ConvShape(1, 64, 20, 20, 72, 3, 3, 1, 1),    # window kernel: bands of 9, 9 and 2 rows, K over two 64-row tiles
+    ConvShape(1, 8, 1, 1, 8, 1, 1, 1, 0),        # one pixel, one channel vector: far below the smallest tile
+    ConvShape(1, 16, 34, 3, 8, 3, 3, 4, 1),      # 9 output pixels, stride 4
 ]
 
 

@@ -325,3 +325,39 @@ def test_strided_window_variants_for_first_layers():
                    (ConvShape(20, 3, 227, 227, 96, 11, 11, 4, 11), 1)]:   # padding as wide as the window
         _, names = names_of(sh, dt)
         assert names and not any(n.startswith("swin_") for n in names), (sh, dt)
+
+
+def test_every_valid_descriptor_has_a_variant_and_a_default():
+    """Seeded random descriptors over the whole documented domain: each has at least one variant, unique names, and a
+    default selection that names one of them (host logic only: no launch)."""
+    import numpy as np
+
+    rng = np.random.default_rng(4242)
+    checked = 0
+    for _ in range(3000):
+        R, S = int(rng.integers(1, 13)), int(rng.integers(1, 13))
+        pad = int(rng.integers(0, 4))
+        H, W = int(rng.integers(1, 260)), int(rng.integers(1, 260))
+        if H + 2 * pad < R or W + 2 * pad < S:
+            continue
+        shape = wl.ConvShape(int(rng.integers(1, 33)), int(rng.integers(1, 1100)), H, W, int(rng.integers(1, 1100)), R, S,
+                             int(rng.integers(1, 5)), pad)
+        n_in, n_out = shape.N * shape.C * H * W, shape.N * shape.K * shape.OH * shape.OW
+        if 4 * max(n_in, n_out) >= 2 ** 32:
+            continue  # every tensor stays below 4 GiB (documented limit of the descriptor)
+        for dtype in (wl.F32, wl.F16, wl.BF16):
+            descs = [B.desc_of(shape, dtype, relu=bool(rng.integers(0, 2)))]
+            gib = 2 ** 30 - 2 ** 20  # channel-innermost kernels: input and filter tensors below 1 GiB each
+            small = 2 * (n_in + pad * (W + 1) * shape.C) < gib and 2 * shape.K * shape.C * R * S < gib
+            if dtype != wl.F32 and shape.C % 8 == 0 and small:
+                descs.append(B.desc_of(shape, dtype, relu=True, in_nhwc=True, out_nhwc=False, filt_krsc=True))
+                if shape.K % 8 == 0:
+                    descs.append(B.desc_of(shape, dtype, relu=True, in_nhwc=True, out_nhwc=True, filt_krsc=True))
+            for d in descs:
+                n = B.conv_variant_count(d)
+                assert n >= 1, (shape, dtype, d.flags)
+                names = [B.conv_variant_name(d, i) for i in range(n)]
+                assert len(set(names)) == n
+                assert B.conv_variant_name(d, -1) in names
+                checked += 1
+    assert checked > 5000
