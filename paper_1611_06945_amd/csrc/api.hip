@@ -152,7 +152,20 @@ double heuristic_cost(const Variant& v, const conv_desc& d, int OH, int OW)
 {
     const double P = (double)d.N * OH * OW, Q = (double)d.C * d.R * d.S;
     if (v.family == FAM_FC) return 1.0 + std::abs(v.tm - 4);  // weight streaming: always ahead of the MFMA tiles when valid
-    if (v.family == FAM_WINOGRAD) return 1.0e30;              // another arithmetic: chosen by measurement only
+    if (v.family == FAM_WINOGRAD) {
+        // F(2x2,3x3) product kernel: one workgroup per (v.tm channels, v.tn / 4 tiles of 2x2 outputs), one round per 256
+        // workgroups, a step per v.tk / 9 input channels whose cost grows with the products and with the operands it
+        // transforms; the separate filter transform is a launch plus its traffic.  Least-squares fit (rms 8 %) to every
+        // Winograd variant on the 3x3 operations of Appendix A and benchmark configuration 4 at batch 1, 5 and 20.
+        const double tt = v.tn / 4.0, cb = v.tk / 9.0;
+        const double tiles = (double)d.N * std::ceil(OH / 2.0) * std::ceil(OW / 2.0);
+        const double rounds = std::ceil(std::ceil(d.K / (double)v.tm) * std::ceil(tiles / tt) / 256.0);
+        double t_step = 0.026 + 0.262e-4 * v.tm * tt * cb + 1.443e-3 * (v.tm + tt) * cb;
+        double t_filters = 4.15 + 0.49e-5 * (double)d.K * d.C;
+        if (v.traits & TRAIT_FILTERS_IN_KERNEL) t_filters = 0.0, t_step *= 1.12;
+        if (d.flags & CONV_FLAG_FILT_WINOGRAD) t_filters = 0.0;
+        return 4.62 + t_filters + rounds * (d.C / cb) * t_step;
+    }
     if (v.family == FAM_FIRSTLAYER) {
         // persistent workgroups, one per CU and channel tile, walking over tiles of v.tn pixels of one image: a start-up
         // that grows with the filter rows a workgroup re-lays, then a time per tile (measured on the 11x11 stride-4 and

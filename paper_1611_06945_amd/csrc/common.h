@@ -112,7 +112,8 @@ enum { TRAIT_SCALAR_LOADS = 1u,  // filter tile fetched element by element (no a
        TRAIT_WINDOW_TILES = 4u,  // tiles are bands of one image's pixels (window-reuse kernels of any family)
        TRAIT_REGISTER_OPERANDS = 8u,  // input operand gathered straight into MFMA registers, no LDS staging of the patch
        TRAIT_STRIDED_VECTOR = 16u,    // gathers four input columns per load on stride-4 layers
-       TRAIT_PLANAR_TO_NHWC = 32u };  // reads [N][C][H][W] and [K][C][R][S], can write [N][OH][OW][K] (CONV_FLAG_OUT_NHWC alone)
+       TRAIT_PLANAR_TO_NHWC = 32u,    // reads [N][C][H][W] and [K][C][R][S], can write [N][OH][OW][K] (CONV_FLAG_OUT_NHWC alone)
+       TRAIT_FILTERS_IN_KERNEL = 64u };  // Winograd: the filter transform runs inside the product kernel
 
 enum { FAM_IGEMM = 0, FAM_POINTWISE = 1, FAM_FIRSTLAYER = 2, FAM_WINDOW = 3, FAM_FC = 4, FAM_NHWC = 5, FAM_WINOGRAD = 6 };
 

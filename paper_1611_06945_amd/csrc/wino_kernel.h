@@ -617,6 +617,7 @@ void wino_register(std::vector<Variant>& out)
     v.valid = &wino_valid<CFG>;
     v.launch = &wino_launch<CFG>;
     v.ws_extra = &wino_ws_bytes<CFG>;
+    if (CFG::FF) v.traits |= TRAIT_FILTERS_IN_KERNEL;
     out.push_back(v);
 }
 

@@ -262,8 +262,10 @@ def test_winograd_variants_and_the_transformed_filter_format():
     assert all(B.conv_variant_workspace(plain, i) == (0 if names[i].endswith("_ff") else 16 * 384 * 256 * 4) for i in wino)
     assert any(names[i].endswith("_ff") for i in wino)
     assert B.conv_workspace_bytes(plain) >= 16 * 384 * 256 * 4
-    # ... and are chosen by measurement only: without a tuned entry the direct kernels stay selected
-    assert not B.conv_variant_name(plain, -1).startswith("wino_")
+    # ... the cost model picks them where they pay (this layer at batch 20), not on a small batch of the same layer,
+    # and only the workspace-free ones when the caller brings no workspace
+    assert B.conv_variant_name(plain, -1).startswith("wino_")
+    assert not B.conv_variant_name(B.desc_of(sh.with_batch(1), 0), -1).startswith("wino_")
     # filters handed over in the Winograd domain: only those variants, no workspace, its own cache key
     pre = B.desc_of(sh, 0, filt_winograd=True)
     names_pre = [B.conv_variant_name(pre, i) for i in range(B.conv_variant_count(pre))]
