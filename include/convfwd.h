@@ -59,7 +59,16 @@ enum {
      * conversions the paper does ahead of time (Section 3, "Graph-level Optimizations").  Only the Winograd variants
      * serve such a descriptor (fp32, 3x3, stride 1, pad <= 1, C % 8 == 0; otherwise CONV_ENOVARIANT), and they then
      * need no workspace.  Not combinable with the channel-innermost bits. */
-    CONV_FLAG_FILT_WINOGRAD = 16u
+    CONV_FLAG_FILT_WINOGRAD = 16u,
+    /* A 3x3 stride-2 max-pool (no padding, the pooling layers of the paper's networks) fused behind the activation:
+     * out holds [N][K][PH][PW] (or [N][PH][PW][K] with OUT_NHWC), PH = (OH-3)/2 + 1, PW = (OW-3)/2 + 1, each element
+     * the maximum of act(conv + bias) over its window -- the convolution's own output is never written (the paper's
+     * rule for fusing an operation into the write of the convolution result, Section 3 "Graph-level Optimizations").
+     * Needs OH, OW >= 3.  Served by the fp16/bf16 window kernels whose workgroup holds a whole output image
+     * (stride 1, OH*OW <= 192 for 3x3 windows, <= 768 for 5x5); other descriptors give CONV_ENOVARIANT and the caller
+     * runs maxpool_fwd() behind the convolution.  The result is bit-identical to that sequence run with the same
+     * variant.  Not combinable with CONV_FLAG_FILT_WINOGRAD. */
+    CONV_FLAG_MAXPOOL_3X3S2 = 32u
 };
 
 typedef enum {
@@ -82,7 +91,8 @@ typedef struct {
     uint32_t flags;       /* CONV_FLAG_*                                     */
 } conv_desc;
 
-/* Output extent (formula above).  Pure host code.  CONV_EINVAL if the descriptor is not valid. */
+/* Extent of the tensor the call writes: (OH, OW) by the formula above, or (PH, PW) with CONV_FLAG_MAXPOOL_3X3S2.
+ * Pure host code.  CONV_EINVAL if the descriptor is not valid. */
 int conv_out_shape(const conv_desc* desc, int32_t* OH, int32_t* OW);
 
 /* FLOPs of the layer in the convention of Appendix A: 2*N*K*OH*OW*C*R*S.  0 if the descriptor is invalid. */

@@ -74,7 +74,7 @@ int hip_fail(hipError_t e, const char* what)
 }
 
 constexpr uint32_t kLayoutFlags = CONV_FLAG_IN_NHWC | CONV_FLAG_OUT_NHWC | CONV_FLAG_FILT_KRSC;
-constexpr uint32_t kKnownFlags = CONV_FLAG_RELU | kLayoutFlags | CONV_FLAG_FILT_WINOGRAD;
+constexpr uint32_t kKnownFlags = CONV_FLAG_RELU | kLayoutFlags | CONV_FLAG_FILT_WINOGRAD | CONV_FLAG_MAXPOOL_3X3S2;
 
 // Validation shared by every entry point; fills OH/OW.
 int check_desc(const conv_desc* d, int& OH, int& OW)
@@ -91,6 +91,7 @@ int check_desc(const conv_desc* d, int& OH, int& OW)
     const int64_t n_in = (int64_t)d->N * d->C * d->H * d->W;
     const int64_t n_f = (int64_t)d->K * d->C * d->R * d->S;
     if (oh >= lim || ow >= lim) return CONV_EINVAL;
+    if ((d->flags & CONV_FLAG_MAXPOOL_3X3S2) && (oh < 3 || ow < 3)) return CONV_EINVAL;
     // guard the products against overflow before forming them
     if ((double)d->N * d->C * (double)d->H * d->W >= (double)lim) return CONV_EINVAL;
     if ((double)d->K * d->C * (double)d->R * d->S >= (double)lim) return CONV_EINVAL;
@@ -116,6 +117,8 @@ std::vector<int> valid_list(State& st, const conv_desc& d, int OH, int OW)
     const bool layout = (d.flags & kLayoutFlags) != 0;
     const bool wino_filters = (d.flags & CONV_FLAG_FILT_WINOGRAD) != 0;
     if (layout && wino_filters) return r;
+    const bool pool = (d.flags & CONV_FLAG_MAXPOOL_3X3S2) != 0;
+    if (pool && wino_filters) return r;
     // ... except planar input and filters with a channel-innermost output, which some planar kernels can write
     const bool planar_to_nhwc = (d.flags & kLayoutFlags) == CONV_FLAG_OUT_NHWC;
     for (size_t i = 0; i < st.variants.size(); ++i) {
@@ -125,6 +128,7 @@ std::vector<int> valid_list(State& st, const conv_desc& d, int OH, int OW)
             continue;
         }
         if (wino_filters && st.variants[i].family != FAM_WINOGRAD) continue;
+        if (pool && !(st.variants[i].traits & TRAIT_POOL_EPILOGUE)) continue;
         if (st.variants[i].valid(st.variants[i], d, OH, OW)) r.push_back((int)i);
     }
     return r;
@@ -263,6 +267,10 @@ void fill_args(ConvArgs& a, const conv_desc& d, int OH, int OW, const void* in, 
     a.in_bytes = (uint32_t)((uint64_t)d.N * d.C * d.H * d.W * dtype_size(d.dtype));
     a.filt_bytes = (uint32_t)((uint64_t)d.K * d.C * d.R * d.S * dtype_size(d.dtype));
     a.out_bytes = (uint32_t)((uint64_t)d.N * d.K * OH * OW * dtype_size(d.dtype));
+    a.pool = (d.flags & CONV_FLAG_MAXPOOL_3X3S2) ? 1 : 0;
+    a.POH = a.pool ? (OH - 3) / 2 + 1 : 0;
+    a.POW = a.pool ? (OW - 3) / 2 + 1 : 0;
+    if (a.pool) a.out_bytes = (uint32_t)((uint64_t)d.N * d.K * a.POH * a.POW * dtype_size(d.dtype));
     a.nsplit = 1;
     a.steps_per_split = 0;
     a.dRS = make_fastdiv((uint32_t)a.RS);
@@ -325,8 +333,9 @@ int conv_out_shape(const conv_desc* desc, int32_t* OH, int32_t* OW)
     const int rc = check_desc(desc, oh, ow);
     if (rc) return rc;
     if (!OH || !OW) return CONV_EINVAL;
-    *OH = oh;
-    *OW = ow;
+    const bool pool = (desc->flags & CONV_FLAG_MAXPOOL_3X3S2) != 0;
+    *OH = pool ? (oh - 3) / 2 + 1 : oh;
+    *OW = pool ? (ow - 3) / 2 + 1 : ow;
     return CONV_OK;
 }
 

@@ -78,6 +78,8 @@ struct ConvArgs {
     int relu;
     int out_nhwc;  // output is [N][OH][OW][K] instead of [N][K][OH][OW]
     int filt_wino; // `filt` already holds the Winograd-domain filters (no transform kernel, no workspace)
+    int pool;      // 3x3 stride-2 max-pool fused behind the activation: out is [N][K][POH][POW] (or channel-innermost)
+    int POH, POW;  // pooled extent (0 without pool)
     uint32_t in_bytes, filt_bytes, out_bytes;  // extents for the hardware bounds check of tile loads
     int nsplit;           // number of reduction splits (gridDim.z)
     int steps_per_split;  // reduction steps (of the kernel's own step size) per split
@@ -113,7 +115,8 @@ enum { TRAIT_SCALAR_LOADS = 1u,  // filter tile fetched element by element (no a
        TRAIT_REGISTER_OPERANDS = 8u,  // input operand gathered straight into MFMA registers, no LDS staging of the patch
        TRAIT_STRIDED_VECTOR = 16u,    // gathers four input columns per load on stride-4 layers
        TRAIT_PLANAR_TO_NHWC = 32u,    // reads [N][C][H][W] and [K][C][R][S], can write [N][OH][OW][K] (CONV_FLAG_OUT_NHWC alone)
-       TRAIT_FILTERS_IN_KERNEL = 64u };  // Winograd: the filter transform runs inside the product kernel
+       TRAIT_FILTERS_IN_KERNEL = 64u,  // Winograd: the filter transform runs inside the product kernel
+       TRAIT_POOL_EPILOGUE = 128u };   // can max-pool its output tile before the store (CONV_FLAG_MAXPOOL_3X3S2)
 
 enum { FAM_IGEMM = 0, FAM_POINTWISE = 1, FAM_FIRSTLAYER = 2, FAM_WINDOW = 3, FAM_FC = 4, FAM_NHWC = 5, FAM_WINOGRAD = 6 };
 

@@ -217,6 +217,34 @@ __global__ __launch_bounds__(CFG::NT) void nwin_kernel(ConvArgs a)
                         red[(kw * 32 + acc_row<32>(v, lane)) * RP + (wn * NBW + nb) * 32 + li] = acc[mb][nb][v];
             }
             __syncthreads();
+            if (a.pool) {
+                // the band is the whole image: 3x3 stride-2 maxima of the summed block, then bias + activation + rounding
+                // (all three are monotone, so this equals pooling the rounded activations)
+                const int npool = a.POH * a.POW;
+                for (int e = tid; e < 32 * npool; e += NT) {
+                    const int row = onhwc ? (e & 31) : e / npool, pp = onhwc ? (e >> 5) : e - row * npool;
+                    const int py = pp / a.POW, px = pp - py * a.POW;
+                    const int k = m0 + (wmi * TMB + mb) * 32 + row;
+                    float m = -INFINITY;
+#pragma unroll
+                    for (int dy = 0; dy < 3; ++dy)
+#pragma unroll
+                        for (int dx = 0; dx < 3; ++dx) {
+                            const int idx = row * RP + (2 * py + dy) * a.OW + 2 * px + dx;
+                            float x = red[idx];
+#pragma unroll
+                            for (int q = 1; q < KW; ++q) x += red[q * 32 * RP + idx];
+                            m = x > m ? x : m;
+                        }
+                    const bool ok = k < a.K;
+                    m += buffer_load_elem<float>(rbias, ok ? (uint32_t)k * 4u : kOutOfRange);
+                    if (a.relu) m = m > 0.0f ? m : 0.0f;
+                    const uint32_t o = onhwc ? (uint32_t)((img * npool + pp) * a.K + k) : (uint32_t)((img * a.K + k) * npool + pp);
+                    buffer_store_elem<elem_t>(Prec<DT>::from_f32(m), rout, ok ? o * 2u : kOutOfRange);
+                }
+                __syncthreads();
+                continue;
+            }
             constexpr int NE = (32 * TNP + NT - 1) / NT;  // outputs of this 32-row block per thread
 #pragma unroll
             for (int j = 0; j < NE; ++j) {
@@ -287,6 +315,8 @@ bool nwin_valid(const Variant& v, const conv_desc& d, int OH, int OW)
     if (v.split > 1 && (long long)d.K * P * 4 >= (1LL << 32)) return false;
     if (CFG::TM > 32 && d.K < CFG::TM) return false;
     if (d.K > 65535LL * CFG::TM || (long long)d.N * g.bands > 2147483647LL) return false;
+    // the fused max-pool reads its windows from the workgroup's own tile: one band per image, no partial sums elsewhere
+    if ((d.flags & CONV_FLAG_MAXPOOL_3X3S2) && (g.bands != 1 || v.split > 1)) return false;
     return true;
 }
 
@@ -308,7 +338,7 @@ void nwin_register(std::vector<Variant>& out, std::initializer_list<int> splits)
         v.threads = CFG::NT;
         v.family = FAM_NHWC;
         v.specificity = 5;
-        v.traits = TRAIT_WINDOW_TILES;
+        v.traits = TRAIT_WINDOW_TILES | TRAIT_POOL_EPILOGUE;
         v.valid = &nwin_valid<CFG>;
         v.launch = &nwin_launch<CFG>;
         out.push_back(v);

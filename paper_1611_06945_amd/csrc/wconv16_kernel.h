@@ -327,6 +327,33 @@ __global__ __launch_bounds__(CFG::NT) void wconv16_kernel(ConvArgs a)
                         red[(kw * 32 + acc_row<32>(v, lane)) * TNP + (wn * NBW + nb) * 32 + li] = acc[mb][nb][v];
             }
             __syncthreads();
+            if (a.pool) {
+                // the band is the whole image: 3x3 stride-2 maxima of the summed block, then bias + activation + rounding
+                // (all three are monotone, so this equals pooling the rounded activations)
+                const int npool = a.POH * a.POW;
+                for (int e = tid; e < 32 * npool; e += NT) {
+                    const int row = e / npool, pp = e - row * npool;
+                    const int py = pp / a.POW, px = pp - py * a.POW;
+                    const int k = m0 + (wmi * TMB + mb) * 32 + row;
+                    float m = -INFINITY;
+#pragma unroll
+                    for (int dy = 0; dy < 3; ++dy)
+#pragma unroll
+                        for (int dx = 0; dx < 3; ++dx) {
+                            const int idx = row * TNP + (2 * py + dy) * a.OW + 2 * px + dx;
+                            float x = red[idx];
+#pragma unroll
+                            for (int q = 1; q < KW; ++q) x += red[q * 32 * TNP + idx];
+                            m = x > m ? x : m;
+                        }
+                    const bool ok = k < a.K;
+                    m += buffer_load_elem<float>(rbias, ok ? (uint32_t)k * 4u : kOutOfRange);
+                    if (a.relu) m = m > 0.0f ? m : 0.0f;
+                    buffer_store_elem<elem_t>(Prec<DT>::from_f32(m), rout, ok ? (uint32_t)((img * a.K + k) * npool + pp) * 2u : kOutOfRange);
+                }
+                __syncthreads();
+                continue;
+            }
             constexpr int NE = (32 * TNP + NT - 1) / NT;  // outputs of this 32-row block per thread
             float xs[NE], bs[NE];
 #pragma unroll
@@ -414,6 +441,8 @@ bool wconv16_valid(const Variant& v, const conv_desc& d, int OH, int OW)
     if (v.split > 1 && (long long)d.K * P * 4 >= (1LL << 32)) return false;
     if (CFG::TM > 32 && d.K < CFG::TM) return false;
     if (d.K > 65535LL * CFG::TM || (long long)d.N * g.bands > 2147483647LL) return false;
+    // the fused max-pool reads its windows from the workgroup's own tile: one band per image, no partial sums elsewhere
+    if ((d.flags & CONV_FLAG_MAXPOOL_3X3S2) && (g.bands != 1 || v.split > 1)) return false;
     return true;
 }
 
@@ -435,7 +464,7 @@ void wconv16_register(std::vector<Variant>& out, std::initializer_list<int> spli
         v.threads = CFG::NT;
         v.family = FAM_WINDOW;
         v.specificity = 4;
-        v.traits = CFG::LBN > 0 ? TRAIT_WHOLE_IMAGE : 0u;
+        v.traits = (CFG::LBN > 0 ? TRAIT_WHOLE_IMAGE : 0u) | TRAIT_POOL_EPILOGUE;
         v.valid = &wconv16_valid<CFG>;
         v.launch = &wconv16_launch<CFG>;
         out.push_back(v);

@@ -1,0 +1,124 @@
+"""GPU parity of the 3x3 stride-2 max-pool fused into the convolution's epilogue (CONV_FLAG_MAXPOOL_3X3S2): against the
+CPU oracle's convolution followed by its max-pool, and bit for bit against the library's own two-call sequence."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_1611_06945_amd import binding as B
+from paper_1611_06945_amd import workloads as wl
+from paper_1611_06945_amd.workloads import ConvShape
+
+from gpu_util import TOL, empty_out, to_device, to_host_f64, to_host_stored, torch_mod
+from test_gpu_parity import say
+
+pytestmark = pytest.mark.gpu
+
+DT16 = [wl.F16, wl.BF16]
+
+
+def nhwc(a):
+    return np.ascontiguousarray(np.transpose(a, (0, 2, 3, 1)))
+
+
+def nchw(a):
+    return np.ascontiguousarray(np.transpose(a, (0, 3, 1, 2)))
+
+
+POOL_SHAPES = [
+    ConvShape(3, 64, 13, 13, 40, 3, 3, 1, 1),    # 13x13 -> 6x6, K ragged against the 32-row blocks
+    ConvShape(2, 32, 14, 12, 64, 3, 3, 1, 1),    # 14x12 -> 6x5: even extents leave the last row and column unused
+    ConvShape(2, 32, 13, 13, 33, 3, 3, 1, 0),    # no padding: 11x11 -> 5x5
+    ConvShape(2, 32, 5, 42, 8, 3, 3, 1, 0),      # 3x40 -> 1x19: a single row of windows (planar kernels only)
+    ConvShape(2, 32, 13, 13, 40, 5, 5, 1, 2),    # 5x5 window
+    ConvShape(1, 16, 27, 27, 48, 5, 5, 1, 2),    # 27x27 -> 13x13: only the 768-pixel tiles hold the whole image
+]
+
+
+def data_for(shape, dtype, seed, ints):
+    if ints:
+        return wl.small_int_case(shape, dtype, seed)
+    return {
+        "in": wl.to_storage(wl.draw(("uniform", -1.0, 1.0), shape.in_shape(), seed), dtype),
+        "filt": wl.to_storage(wl.draw(("normal", wl.he_sigma(shape)), shape.filt_shape(), seed + 1), dtype),
+        "bias": wl.draw(("uniform", -0.1, 0.1), (shape.K,), seed + 2),
+    }
+
+
+def run(desc, d_in, d_filt, d_bias, oshape, dtype, variant):
+    torch = torch_mod()
+    out = empty_out(oshape, dtype)
+    ws = torch.empty(max(256, B.conv_workspace_bytes(desc)), dtype=torch.uint8, device="cuda")
+    B.conv_force_variant(desc, variant)
+    try:
+        B.conv_fwd_ws(desc, d_in, d_filt, d_bias, out, ws, ws.numel())
+        torch.cuda.synchronize()
+    finally:
+        B.conv_force_variant(desc, -1)
+    return out
+
+
+@pytest.mark.parametrize("layout", ["planar", "nhwc_to_nhwc", "nhwc_to_planar"])
+@pytest.mark.parametrize("dtype", DT16)
+@pytest.mark.parametrize("si", range(len(POOL_SHAPES)))
+def test_fused_maxpool_every_variant(si, dtype, layout):
+    torch = torch_mod()
+    shape = POOL_SHAPES[si]
+    in_nhwc, out_nhwc = layout != "planar", layout == "nhwc_to_nhwc"
+    if out_nhwc and shape.K % 8:
+        pytest.skip("channel-innermost outputs need K % 8 == 0")
+    if layout == "planar" and shape.OH * shape.OW > 192:
+        pytest.skip("no planar window kernel holds an image of more than 192 pixels in one tile")
+    if layout != "planar" and shape.H == 5:
+        pytest.skip("the channel-innermost window kernels have no staging slots for 42-wide rows of this band")
+    PH, PW = (shape.OH - 3) // 2 + 1, (shape.OW - 3) // 2 + 1
+    for ints, relu, use_bias in [(True, True, True), (True, False, False), (False, True, True)]:
+        data = data_for(shape, dtype, 3000 + 10 * si, ints)
+        conv = oracle.conv_fwd(wl.storage_to_f64(data["in"], dtype), wl.storage_to_f64(data["filt"], dtype),
+                               data["bias"].astype(np.float64) if use_bias else None,
+                               stride=shape.stride, pad=shape.pad, relu=relu)
+        want = oracle.maxpool_fwd(conv, win=3, stride=2)
+        assert want.shape == (shape.N, shape.K, PH, PW)
+        d_in = to_device(nhwc(data["in"]) if in_nhwc else data["in"], dtype)
+        d_filt = to_device(nhwc(data["filt"]) if in_nhwc else data["filt"], dtype)
+        d_bias = to_device(data["bias"], wl.F32) if use_bias else None
+        kw = dict(relu=relu, in_nhwc=in_nhwc, out_nhwc=out_nhwc, filt_krsc=in_nhwc)
+        fused = B.desc_of(shape, dtype, maxpool=True, **kw)
+        assert B.conv_out_shape(fused) == (PH, PW)
+        names = [B.conv_variant_name(fused, i) for i in range(B.conv_variant_count(fused))]
+        assert names, "no variant pools %s (%s)" % (shape, layout)
+        plain = B.desc_of(shape, dtype, **kw)
+        plain_names = [B.conv_variant_name(plain, i) for i in range(B.conv_variant_count(plain))]
+        oshape = (shape.N, PH, PW, shape.K) if out_nhwc else (shape.N, shape.K, PH, PW)
+        for vi, name in enumerate(names):
+            say("  %s on %s dtype %d %s ints=%s relu=%s bias=%s" % (name, shape, dtype, layout, ints, relu, use_bias))
+            out = run(fused, d_in, d_filt, d_bias, oshape, dtype, vi)
+            got_bits = to_host_stored(out, dtype)
+            # the library's own two-call sequence with the same kernel (same summation order): equal bit for bit
+            full = run(plain, d_in, d_filt, d_bias,
+                       (shape.N, shape.OH, shape.OW, shape.K) if out_nhwc else shape.out_shape(), dtype, plain_names.index(name))
+            seq = empty_out(oshape, dtype)
+            B.maxpool_fwd_layout(shape.N, shape.K, shape.OH, shape.OW, 3, 2, dtype, out_nhwc, out_nhwc, full, seq)
+            torch.cuda.synchronize()
+            seq_bits = to_host_stored(seq, dtype)
+            assert np.array_equal(got_bits.view(np.uint16), seq_bits.view(np.uint16)), "%s: differs from conv + maxpool" % name
+            got = to_host_f64(out, dtype)
+            got = nchw(got) if out_nhwc else got
+            assert np.all(np.isfinite(got)), "%s: unwritten or overflowed elements" % name
+            if ints:
+                exp = wl.storage_to_f64(wl.to_storage(want.astype(np.float32), dtype), dtype)
+                assert np.array_equal(got, exp), "%s: %d mismatches" % (name, int((got != exp).sum()))
+            else:
+                err = oracle.max_normalised_error(got, want)
+                assert err <= TOL[dtype], "%s: error %.3g" % (name, err)
+
+
+def test_fused_maxpool_is_refused_where_no_tile_holds_the_image():
+    L = B.lib()
+    import ctypes
+    for shape, dtype, kw in [(ConvShape(2, 32, 27, 27, 32, 3, 3, 1, 1), wl.F16, {}),            # 729 pixels, 3x3 window
+                             (ConvShape(2, 32, 13, 13, 32, 3, 3, 1, 1), wl.F32, {}),            # fp32
+                             (ConvShape(2, 32, 13, 13, 32, 3, 3, 2, 1), wl.F16, {}),            # stride 2
+                             (ConvShape(2, 3, 35, 35, 32, 11, 11, 4, 0), wl.F16, {})]:          # first layer
+        d = B.desc_of(shape, dtype, maxpool=True, **kw)
+        assert B.conv_variant_count(d) == 0
+        assert L.conv_fwd(ctypes.byref(d), 256, 512, None, 1024, None) == B.CONV_ENOVARIANT

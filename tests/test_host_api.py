@@ -52,7 +52,7 @@ def test_out_shape_of_benchmark_configs():
 
 
 @pytest.mark.parametrize("field,value", [("N", 0), ("C", 0), ("H", 0), ("W", -1), ("K", 0), ("R", 0), ("S", 0),
-                                         ("stride", 0), ("pad", -1), ("flags", 32)])
+                                         ("stride", 0), ("pad", -1), ("flags", 64)])
 def test_invalid_descriptor_fields(field, value):
     d = B.make_desc(1, 3, 8, 8, 4, 3, 3, 1, 1)
     setattr(d, field, value)
@@ -363,3 +363,22 @@ def test_every_valid_descriptor_has_a_variant_and_a_default():
                 assert B.conv_variant_name(d, -1) in names
                 checked += 1
     assert checked > 5000
+
+
+def test_fused_maxpool_flag_host_rules():
+    from paper_1611_06945_amd.workloads import ConvShape
+
+    sh = ConvShape(20, 256, 13, 13, 256, 3, 3, 1, 1)
+    fused = B.desc_of(sh, 1, maxpool=True)
+    assert B.conv_out_shape(B.desc_of(sh, 1)) == (13, 13) and B.conv_out_shape(fused) == (6, 6)
+    names = [B.conv_variant_name(fused, i) for i in range(B.conv_variant_count(fused))]
+    assert names and all(n.startswith("wconv_f16_3x3") and "_sk" not in n for n in names)  # one band per image, no splits
+    nh = B.desc_of(sh, 2, maxpool=True, in_nhwc=True, out_nhwc=True, filt_krsc=True)
+    assert all(B.conv_variant_name(nh, i).startswith("nhwc_win_bf16_3x3") for i in range(B.conv_variant_count(nh)))
+    assert B.conv_variant_count(nh) >= 1
+    # conv output smaller than the pooling window, fp32, Winograd-domain filters: refused
+    L = B.lib()
+    tiny = B.desc_of(ConvShape(1, 16, 4, 4, 8, 3, 3, 1, 0), 1, maxpool=True)  # 2x2 conv output
+    assert L.conv_variant_count(ctypes.byref(tiny)) == B.CONV_EINVAL
+    assert B.conv_variant_count(B.desc_of(sh, 0, maxpool=True)) == 0
+    assert B.conv_variant_count(B.desc_of(sh, 0, maxpool=True, filt_winograd=True)) == 0
