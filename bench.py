@@ -181,7 +181,8 @@ def stack_report(dtype, batch=20, reps=50):
             e1.synchronize()
             per.append(e0.elapsed_time(e1) / reps)
         ms = statistics.median(per)
-        rep[tag] = {"formats": st.formats, "ms": round(ms, 5), "gflops": round(flops / (ms * 1e-3) / 1e9, 1),
+        rep[tag] = {"formats": st.formats, "pool_fused": st.fused, "ms": round(ms, 5),
+                    "gflops": round(flops / (ms * 1e-3) / 1e9, 1),
                     "variants": [B.conv_variant_name(d, -1) for d in st.descs]}
         # the same chain recorded once into a HIP graph and replayed: one launch per pass instead of one per operation
         graph = st.capture(x, filts, biases)
@@ -468,9 +469,9 @@ def main():
                 rep["layer"], rep["variant"], rep["ms"], rep["gflops"], rep["frac_mfma_peak"], rep["frac_hbm_peak"]))
         out["layers"] = layers
         out["stack"] = stack_report(wl.F16)
-        log("stack f16: all-NCHW %.4f ms (HIP graph %.4f), formats selected %s %.4f ms (HIP graph %.4f)" % (
+        log("stack f16: all-NCHW %.4f ms (HIP graph %.4f), formats selected %s pools fused %s %.4f ms (HIP graph %.4f)" % (
             out["stack"]["nchw"]["ms"], out["stack"]["nchw"]["graph_ms"], out["stack"]["selected"]["formats"],
-            out["stack"]["selected"]["ms"], out["stack"]["selected"]["graph_ms"]))
+            out["stack"]["selected"]["pool_fused"], out["stack"]["selected"]["ms"], out["stack"]["selected"]["graph_ms"]))
 
     if not a.no_cpu:
         out["cpu_baseline"] = cpu_baseline(w)

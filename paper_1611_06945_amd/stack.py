@@ -15,6 +15,11 @@ by dynamic programming.  A max-pool between two layers converts for free (it rea
 one layout and writes the other); elsewhere an explicit conversion is inserted.
 Filters of channel-innermost layers are repacked once in `prepare()`.  The
 stack's input and final output are always [N][C][H][W].
+
+Where a max-pool follows a layer whose kernels can pool their own output tile
+(CONV_FLAG_MAXPOOL_3X3S2: the paper's fusion rule applied to the pooling
+operation), the fused call replaces convolution + pool when `fuse_pool` asks for
+it, or, with `formats="auto"`, when it measures faster.
 """
 from __future__ import annotations
 
@@ -28,9 +33,10 @@ NCHW, NHWC = "nchw", "nhwc"
 
 class ConvStack:
     def __init__(self, shapes: Sequence[ConvShape], dtype: int, pool_after: Sequence[int] = (), relu: bool = True,
-                 pool_win: int = 3, pool_stride: int = 2, formats=None):
+                 pool_win: int = 3, pool_stride: int = 2, formats=None, fuse_pool: bool = False):
         """`pool_after` holds 1-based layer numbers that are followed by a max-pool.  `formats`: None = every layer
-        in [N][C][H][W]; "auto" = decided by autotune(); or a list of "nchw"/"nhwc", one per layer."""
+        in [N][C][H][W]; "auto" = decided by autotune(); or a list of "nchw"/"nhwc", one per layer.  `fuse_pool`: pool
+        inside the convolution wherever a kernel can (with "auto" the timings decide instead)."""
         import torch
 
         self.torch = torch
@@ -56,6 +62,7 @@ class ConvStack:
         self.packed_filts: List[Optional[object]] = [None] * n
         self.plan_times = None
         self.out_layouts = None   # set by the format selection: the output layout it timed and chose per layer
+        self.fused = [bool(fuse_pool) and self.can_fuse_pool(i, self.formats[i], self._handoff_layout(i)) for i in range(n)]
         self._build()
 
     # ---- geometry --------------------------------------------------------------------------------------------------
@@ -80,10 +87,22 @@ class ConvStack:
         d = B.desc_of(self.shapes[i], self.dtype, relu=self.relu, out_nhwc=True)
         return B.conv_variant_count(d) > 0
 
+    def can_fuse_pool(self, i: int, fmt: str, out_layout: str) -> bool:
+        """Whether some kernel runs layer i in format `fmt` with the following 3x3 stride-2 pool fused, writing `out_layout`."""
+        if (i + 1) not in self.pool_after or (self.pool_win, self.pool_stride) != (3, 2):
+            return False
+        if fmt == NCHW and out_layout == NHWC:
+            return False
+        d = B.desc_of(self.shapes[i], self.dtype, relu=self.relu, in_nhwc=fmt == NHWC, out_nhwc=out_layout == NHWC,
+                      filt_krsc=fmt == NHWC, maxpool=True)
+        return B.conv_variant_count(d) > 0
+
     def _conv_out_layout(self, i: int) -> str:
         """A channel-innermost kernel writes whatever layout is wanted next; the planar kernels write [N][K][OH][OW],
         except those that can write channel-innermost when that is what is wanted next.  When a pool follows a
         channel-innermost layer, the pool converts, so the convolution keeps the layout of its own format."""
+        if self.fused[i]:
+            return self._handoff_layout(i)   # the fused call writes the pooled tensor, in the layout wanted next
         if self.out_layouts is not None:
             return self.out_layouts[i]
         if self.formats[i] == NCHW:
@@ -98,11 +117,12 @@ class ConvStack:
         for i, s in enumerate(self.shapes):
             nh = self.formats[i] == NHWC
             lay = self._conv_out_layout(i)
-            d = B.desc_of(s, self.dtype, relu=self.relu, in_nhwc=nh, out_nhwc=(lay == NHWC), filt_krsc=nh)
+            d = B.desc_of(s, self.dtype, relu=self.relu, in_nhwc=nh, out_nhwc=(lay == NHWC), filt_krsc=nh,
+                          maxpool=self.fused[i])
             self.descs.append(d)
             self.conv_layout.append(lay)
             # buffers are flat in memory; the shape recorded here is the logical [N][K][OH][OW] one
-            self.conv_out.append(torch.empty(s.out_shape(), dtype=self.tdt, device="cuda"))
+            self.conv_out.append(None if self.fused[i] else torch.empty(s.out_shape(), dtype=self.tdt, device="cuda"))
             self.pool_out.append(torch.empty(self._pooled_shape(i), dtype=self.tdt, device="cuda")
                                  if (i + 1) in self.pool_after else None)
             # an explicit conversion is needed only where no pool follows and the layouts differ
@@ -142,6 +162,8 @@ class ConvStack:
     # ---- execution ---------------------------------------------------------------------------------------------------
     def _after_conv(self, i: int, stream) -> None:
         s = self.shapes[i]
+        if self.fused[i]:
+            return
         if self.pool_out[i] is not None:
             B.maxpool_fwd_layout(s.N, s.K, s.OH, s.OW, self.pool_win, self.pool_stride, self.dtype,
                                  self.conv_layout[i] == NHWC, self._handoff_layout(i) == NHWC, self.conv_out[i],
@@ -163,7 +185,8 @@ class ConvStack:
         cur = self._first_input(x, stream)
         for i, d in enumerate(self.descs):
             call = B.conv_autotune if tune else B.conv_fwd_ws
-            call(d, cur, self._filt(i, filts), biases[i], self.conv_out[i], self.workspace, self.workspace.numel(), stream)
+            out = self.pool_out[i] if self.fused[i] else self.conv_out[i]
+            call(d, cur, self._filt(i, filts), biases[i], out, self.workspace, self.workspace.numel(), stream)
             self._after_conv(i, stream)
             cur = self.layer_output(i)
         return cur
@@ -222,6 +245,7 @@ class ConvStack:
         torch = self.torch
         n = len(self.shapes)
         conv_t = [{} for _ in range(n)]      # (format, out layout) -> microseconds
+        fused_t = [{} for _ in range(n)]     # (format, pooled-output layout) -> microseconds of convolution + fused pool
         glue_t = [{} for _ in range(n)]      # (conv out layout, handoff layout) -> microseconds of pool / conversion
         for i, s in enumerate(self.shapes):
             xin = torch.zeros(s.in_shape(), dtype=self.tdt, device="cuda")
@@ -236,6 +260,15 @@ class ConvStack:
                     conv_t[i][(fmt, olay)] = B.conv_time_us(d, xin, f, biases[i], out, ws, ws.numel(), stream, launches=20)
             pooled = (i + 1) in self.pool_after
             dst = torch.empty(self._pooled_shape(i) if pooled else s.out_shape(), dtype=self.tdt, device="cuda")
+            for fmt in ((NCHW, NHWC) if self.nhwc_capable(i) else (NCHW,)):
+                for olay in (NCHW, NHWC):
+                    if not self.can_fuse_pool(i, fmt, olay):
+                        continue
+                    d = B.desc_of(s, self.dtype, relu=self.relu, in_nhwc=fmt == NHWC, out_nhwc=olay == NHWC,
+                                  filt_krsc=fmt == NHWC, maxpool=True)
+                    ws = torch.empty(max(256, B.conv_workspace_bytes(d)), dtype=torch.uint8, device="cuda")
+                    B.conv_autotune(d, xin, f, biases[i], dst, ws, ws.numel(), stream)
+                    fused_t[i][(fmt, olay)] = B.conv_time_us(d, xin, f, biases[i], dst, ws, ws.numel(), stream, launches=20)
             for a in (NCHW, NHWC):
                 for b in (NCHW, NHWC):
                     if pooled:
@@ -262,15 +295,21 @@ class ConvStack:
                     # a pool converts from olay to `want`; without a pool the kernel may write `want` itself
                     total = best[i].get(fmt, float("inf")) + t + glue_t[i][(olay, want)]
                     if total < nxt.get(want, float("inf")):
-                        nxt[want], bk[want] = total, (fmt, olay)
+                        nxt[want], bk[want] = total, (fmt, olay, False)
+                for (fmt, olay), t in fused_t[i].items():
+                    total = best[i].get(fmt, float("inf")) + t
+                    if olay == want and total < nxt.get(want, float("inf")):
+                        nxt[want], bk[want] = total, (fmt, olay, True)
             best.append(nxt)
             back.append(bk)
-        want, chosen, olays = NCHW, [None] * n, [None] * n
+        want, chosen, olays, fused = NCHW, [None] * n, [None] * n, [False] * n
         for i in range(n - 1, -1, -1):
-            fmt, olay = back[i][want]
-            chosen[i], olays[i] = fmt, olay
+            fmt, olay, fz = back[i][want]
+            chosen[i], olays[i], fused[i] = fmt, olay, fz
             want = fmt
-        self.plan_times = {"conv_us": conv_t, "glue_us": glue_t, "input_convert_us": x_cvt, "total_us": best[n][NCHW]}
+        self.plan_times = {"conv_us": conv_t, "glue_us": glue_t, "fused_pool_us": fused_t, "input_convert_us": x_cvt,
+                           "total_us": best[n][NCHW]}
         self.formats = chosen
         self.out_layouts = olays
+        self.fused = fused
         self._build()

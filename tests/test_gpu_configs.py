@@ -107,38 +107,25 @@ def _to_nchw(t, layout, dtype):
     return host
 
 
-@pytest.mark.parametrize("formats", [["nchw", "nhwc", "nchw", "nhwc", "nhwc"], "auto"])
-@pytest.mark.parametrize("dtype", [wl.F16, wl.BF16])
-def test_config5_stack_with_format_selection(dtype, formats):
-    # the same five layers with channel-innermost formats where chosen: conversions by the pools, one explicit
-    # conversion (layer 3 -> 4 in the fixed assignment), repacked filters; every layer against the oracle
-    torch = torch_mod()
-    layers = wl.config5_layers(20, dtype)
-    shapes = [w.shape for w in layers]
-    stack = ConvStack(shapes, dtype, pool_after=wl.STACK_POOL_AFTER, formats=formats)
-    gen = [w.generate() for w in layers]
-    x = to_device(gen[0]["in"], dtype)
-    filts = [to_device(g["filt"], dtype) for g in gen]
-    biases = [to_device(g["bias"], wl.F32) for g in gen]
-    stack.autotune(x, filts, biases)
-    say("  formats: %s" % (stack.formats,))
-    if formats == "auto":
-        say("  planned total %.1f us" % stack.plan_times["total_us"])
-    else:
-        assert stack.formats == formats
-    assert stack.formats[0] == "nchw"  # three input channels: no channel-innermost kernel
-    y = stack.run(x, filts, biases)
-    torch.cuda.synchronize()
+def _check_stack_against_oracle(stack, shapes, gen, dtype, y):
+    """Every layer of a finished run against the oracle, each judged on the GPU's own stored input."""
     cur = wl.storage_to_f64(gen[0]["in"], dtype)
     for i, s in enumerate(shapes):
         ref = oracle.conv_fwd(cur, wl.storage_to_f64(gen[i]["filt"], dtype), gen[i]["bias"].astype(np.float64),
                               stride=s.stride, pad=s.pad, relu=True)
+        handed = _to_nchw(stack.layer_output(i), stack.output_layout(i), dtype)
+        if stack.fused[i]:  # the convolution's own output is never stored: compare the pooled tensor
+            assert stack.conv_out[i] is None
+            err = oracle.max_normalised_error(handed, oracle.maxpool_fwd(ref, win=3, stride=2))
+            say("  layer %d + pool (%s, %s) error %.3g" % (i + 1, stack.formats[i], B.conv_variant_name(stack.descs[i], -1), err))
+            assert np.all(np.isfinite(handed)) and err <= TOL[dtype], (i + 1, err)
+            cur = handed
+            continue
         got = _to_nchw(stack.conv_out[i], stack.conv_layout[i], dtype)
         assert np.all(np.isfinite(got))
         err = oracle.max_normalised_error(got, ref)
         say("  layer %d (%s, %s) error %.3g" % (i + 1, stack.formats[i], B.conv_variant_name(stack.descs[i], -1), err))
         assert err <= TOL[dtype], (i + 1, err)
-        handed = _to_nchw(stack.layer_output(i), stack.output_layout(i), dtype)
         if stack.pool_out[i] is not None:
             assert np.array_equal(handed, oracle.maxpool_fwd(got, win=3, stride=2)), "max-pool after layer %d" % (i + 1)
         else:
@@ -146,6 +133,54 @@ def test_config5_stack_with_format_selection(dtype, formats):
         cur = handed  # the next layer is judged on the GPU's own stored input
     assert stack.output_layout(len(shapes) - 1) == "nchw"
     assert np.array_equal(to_host_f64(y, dtype), cur)
+
+
+def _stack_on_device(dtype, batch, **kw):
+    layers = wl.config5_layers(batch, dtype)
+    shapes = [w.shape for w in layers]
+    stack = ConvStack(shapes, dtype, pool_after=wl.STACK_POOL_AFTER, **kw)
+    gen = [w.generate() for w in layers]
+    x = to_device(gen[0]["in"], dtype)
+    filts = [to_device(g["filt"], dtype) for g in gen]
+    biases = [to_device(g["bias"], wl.F32) for g in gen]
+    return stack, shapes, gen, x, filts, biases
+
+
+@pytest.mark.parametrize("formats", [["nchw", "nhwc", "nchw", "nhwc", "nhwc"], "auto"])
+@pytest.mark.parametrize("dtype", [wl.F16, wl.BF16])
+def test_config5_stack_with_format_selection(dtype, formats):
+    # the same five layers with channel-innermost formats where chosen: conversions by the pools, one explicit
+    # conversion (layer 3 -> 4 in the fixed assignment), repacked filters; every layer against the oracle
+    torch = torch_mod()
+    stack, shapes, gen, x, filts, biases = _stack_on_device(dtype, 20, formats=formats)
+    stack.autotune(x, filts, biases)
+    say("  formats: %s, pools fused: %s" % (stack.formats, stack.fused))
+    if formats == "auto":
+        say("  planned total %.1f us" % stack.plan_times["total_us"])
+    else:
+        assert stack.formats == formats and not any(stack.fused)
+    assert stack.formats[0] == "nchw"  # three input channels: no channel-innermost kernel
+    y = stack.run(x, filts, biases)
+    torch.cuda.synchronize()
+    _check_stack_against_oracle(stack, shapes, gen, dtype, y)
+
+
+@pytest.mark.parametrize("dtype", [wl.F16, wl.BF16])
+def test_config5_stack_with_the_second_pool_fused_into_its_convolution(dtype):
+    # fuse_pool fuses every pool that some kernel can run in its epilogue: with channel-innermost layers the 768-pixel
+    # tiles hold a whole 27x27 image, so the pool behind layer 2 goes; the first layer's kernels cannot pool.  With
+    # every layer in [N][C][H][W] no kernel holds a 27x27 image and nothing is fused.
+    torch = torch_mod()
+    planar = ConvStack([w.shape for w in wl.config5_layers(5, dtype)], dtype, pool_after=wl.STACK_POOL_AFTER, fuse_pool=True)
+    assert planar.fused == [False] * 5
+    del planar
+    stack, shapes, gen, x, filts, biases = _stack_on_device(dtype, 5, formats=["nchw", "nhwc", "nhwc", "nhwc", "nhwc"],
+                                                            fuse_pool=True)
+    assert stack.fused == [False, True, False, False, False]
+    stack.autotune(x, filts, biases)
+    y = stack.run(x, filts, biases)
+    torch.cuda.synchronize()
+    _check_stack_against_oracle(stack, shapes, gen, dtype, y)
 
 
 @pytest.mark.parametrize("formats", [None, ["nchw", "nhwc", "nhwc", "nhwc", "nhwc"]])
