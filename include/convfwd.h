@@ -64,8 +64,9 @@ enum {
      * out holds [N][K][PH][PW] (or [N][PH][PW][K] with OUT_NHWC), PH = (OH-3)/2 + 1, PW = (OW-3)/2 + 1, each element
      * the maximum of act(conv + bias) over its window -- the convolution's own output is never written (the paper's
      * rule for fusing an operation into the write of the convolution result, Section 3 "Graph-level Optimizations").
-     * Needs OH, OW >= 3.  Served by the fp16/bf16 window kernels whose workgroup holds a whole output image
-     * (stride 1, OH*OW <= 192 for 3x3 windows, <= 768 for 5x5); other descriptors give CONV_ENOVARIANT and the caller
+     * Needs OH, OW >= 3.  Served by the window kernels whose workgroup holds a whole output image (stride 1; fp16/bf16:
+     * OH*OW <= 192 for 3x3 and 5x5 windows, <= 768 for 5x5 channel-innermost; fp32: 3x3 windows, OH*OW <= 208, planar
+     * tensors); other descriptors give CONV_ENOVARIANT and the caller
      * runs maxpool_fwd() behind the convolution.  The result is bit-identical to that sequence run with the same
      * variant.  Not combinable with CONV_FLAG_FILT_WINOGRAD. */
     CONV_FLAG_MAXPOOL_3X3S2 = 32u

@@ -246,6 +246,34 @@ void wconv_kernel(ConvArgs a)
                 for (int v = 0; v < 4; ++v) red[(w * 16 + 4 * g + v) * TNP + (nb0 + nb) * 16 + li] = acc[mb][nb][v];
             }
         __syncthreads();
+        if (a.pool) {
+            // the tile is the whole image: 3x3 stride-2 maxima of the summed block, then bias + activation (both
+            // monotone, so this equals pooling the activations)
+            const int npool = a.POH * a.POW;
+            for (int e = tid; e < 16 * npool; e += NT) {
+                const int row = e / npool, pp = e - row * npool;
+                const int py = pp / a.POW, px = pp - py * a.POW;
+                const int k = m0 + mb * 16 + row;
+                float m = -INFINITY;
+#pragma unroll
+                for (int dy = 0; dy < 3; ++dy)
+#pragma unroll
+                    for (int dx = 0; dx < 3; ++dx) {
+                        const int idx = row * TNP + (2 * py + dy) * a.OW + 2 * px + dx;
+                        float x = red[idx];
+                        x += red[16 * TNP + idx];
+                        x += red[32 * TNP + idx];
+                        x += red[48 * TNP + idx];
+                        m = x > m ? x : m;
+                    }
+                const bool ok = k < a.K;
+                m += buffer_load_elem<float>(rbias, ok ? (uint32_t)k * 4u : kOutOfRange);
+                if (a.relu) m = m > 0.0f ? m : 0.0f;
+                buffer_store_elem<float>(m, rout, ok ? (uint32_t)((img * a.K + k) * npool + pp) * 4u : kOutOfRange);
+            }
+            __syncthreads();
+            continue;
+        }
         constexpr int NE = (16 * TNP + NT - 1) / NT;  // outputs of this 16-row block per thread
         // element j*NT + tid of the [16][TNP] block: row and column by one division, then by stepping
         int rowj[NE], colj[NE];
@@ -331,6 +359,8 @@ bool wconv_valid(const Variant& v, const conv_desc& d, int OH, int OW)
     if (v.split > 1 && (long long)d.K * P * 4 >= (1LL << 32)) return false;
     if (CFG::TM > 16 && d.K < CFG::TM) return false;
     if (d.K > 65535LL * CFG::TM || (long long)d.N * ntiles > 2147483647LL) return false;
+    // the fused max-pool reads its windows from the workgroup's own tile: the whole image, no partial sums elsewhere
+    if ((d.flags & CONV_FLAG_MAXPOOL_3X3S2) && (ntiles != 1 || v.split > 1)) return false;
     return true;
 }
 
@@ -352,6 +382,7 @@ void wconv_register(std::vector<Variant>& out, std::initializer_list<int> splits
         v.threads = CFG::NT;
         v.family = FAM_WINDOW;
         v.specificity = 4;
+        v.traits = TRAIT_POOL_EPILOGUE;
         v.valid = &wconv_valid<CFG>;
         v.launch = &wconv_launch<CFG>;
         out.push_back(v);

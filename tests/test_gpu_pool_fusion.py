@@ -116,9 +116,53 @@ def test_fused_maxpool_is_refused_where_no_tile_holds_the_image():
     L = B.lib()
     import ctypes
     for shape, dtype, kw in [(ConvShape(2, 32, 27, 27, 32, 3, 3, 1, 1), wl.F16, {}),            # 729 pixels, 3x3 window
-                             (ConvShape(2, 32, 13, 13, 32, 3, 3, 1, 1), wl.F32, {}),            # fp32
+                             (ConvShape(2, 32, 13, 13, 32, 5, 5, 1, 2), wl.F32, {}),            # fp32, 5x5 window
                              (ConvShape(2, 32, 13, 13, 32, 3, 3, 2, 1), wl.F16, {}),            # stride 2
                              (ConvShape(2, 3, 35, 35, 32, 11, 11, 4, 0), wl.F16, {})]:          # first layer
         d = B.desc_of(shape, dtype, maxpool=True, **kw)
         assert B.conv_variant_count(d) == 0
         assert L.conv_fwd(ctypes.byref(d), 256, 512, None, 1024, None) == B.CONV_ENOVARIANT
+
+
+F32_POOL_SHAPES = [
+    ConvShape(3, 64, 13, 13, 40, 3, 3, 1, 1),    # 13x13 -> 6x6, K ragged against the 16-row blocks
+    ConvShape(2, 32, 14, 14, 64, 3, 3, 1, 1),    # 14x14 -> 6x6 on the 208-pixel tiles
+    ConvShape(2, 32, 15, 15, 33, 3, 3, 1, 0),    # no padding: 13x13 -> 6x6
+    ConvShape(2, 16, 12, 16, 16, 3, 3, 1, 1),    # 12x16 -> 5x7
+]
+
+
+@pytest.mark.parametrize("si", range(len(F32_POOL_SHAPES)))
+def test_fused_maxpool_fp32_every_variant(si):
+    torch = torch_mod()
+    dtype = wl.F32
+    shape = F32_POOL_SHAPES[si]
+    PH, PW = (shape.OH - 3) // 2 + 1, (shape.OW - 3) // 2 + 1
+    for ints, relu, use_bias in [(True, True, True), (True, False, False), (False, True, True)]:
+        data = data_for(shape, dtype, 3500 + 10 * si, ints)
+        conv = oracle.conv_fwd(data["in"].astype(np.float64), data["filt"].astype(np.float64),
+                               data["bias"].astype(np.float64) if use_bias else None,
+                               stride=shape.stride, pad=shape.pad, relu=relu)
+        want = oracle.maxpool_fwd(conv, win=3, stride=2)
+        d_in, d_filt = to_device(data["in"], dtype), to_device(data["filt"], dtype)
+        d_bias = to_device(data["bias"], wl.F32) if use_bias else None
+        fused = B.desc_of(shape, dtype, relu=relu, maxpool=True)
+        plain = B.desc_of(shape, dtype, relu=relu)
+        plain_names = [B.conv_variant_name(plain, i) for i in range(B.conv_variant_count(plain))]
+        names = [B.conv_variant_name(fused, i) for i in range(B.conv_variant_count(fused))]
+        assert names, "no variant pools %s" % (shape,)
+        for vi, name in enumerate(names):
+            say("  %s on %s ints=%s relu=%s bias=%s" % (name, shape, ints, relu, use_bias))
+            out = run(fused, d_in, d_filt, d_bias, (shape.N, shape.K, PH, PW), dtype, vi)
+            full = run(plain, d_in, d_filt, d_bias, shape.out_shape(), dtype, plain_names.index(name))
+            seq = empty_out((shape.N, shape.K, PH, PW), dtype)
+            B.maxpool_fwd(shape.N, shape.K, shape.OH, shape.OW, 3, 2, dtype, full, seq)
+            torch.cuda.synchronize()
+            got = out.cpu().numpy()
+            assert np.array_equal(got.view(np.uint32), seq.cpu().numpy().view(np.uint32)), "%s: differs from conv + maxpool" % name
+            assert np.all(np.isfinite(got)), "%s: unwritten elements" % name
+            if ints:
+                assert np.array_equal(got.astype(np.float64), want), "%s: mismatches" % name
+            else:
+                err = oracle.max_normalised_error(got.astype(np.float64), want)
+                assert err <= TOL[dtype], "%s: error %.3g" % (name, err)

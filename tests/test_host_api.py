@@ -376,9 +376,12 @@ def test_fused_maxpool_flag_host_rules():
     nh = B.desc_of(sh, 2, maxpool=True, in_nhwc=True, out_nhwc=True, filt_krsc=True)
     assert all(B.conv_variant_name(nh, i).startswith("nhwc_win_bf16_3x3") for i in range(B.conv_variant_count(nh)))
     assert B.conv_variant_count(nh) >= 1
-    # conv output smaller than the pooling window, fp32, Winograd-domain filters: refused
+    # conv output smaller than the pooling window, Winograd-domain filters: refused
     L = B.lib()
     tiny = B.desc_of(ConvShape(1, 16, 4, 4, 8, 3, 3, 1, 0), 1, maxpool=True)  # 2x2 conv output
     assert L.conv_variant_count(ctypes.byref(tiny)) == B.CONV_EINVAL
-    assert B.conv_variant_count(B.desc_of(sh, 0, maxpool=True)) == 0
+    f32 = B.desc_of(sh, 0, maxpool=True)   # fp32: the 3x3 window kernel pools too
+    assert B.conv_variant_count(f32) >= 1
+    assert all(B.conv_variant_name(f32, i).startswith("wconv_f32_3x3") for i in range(B.conv_variant_count(f32)))
+    assert B.conv_variant_count(B.desc_of(ConvShape(20, 96, 13, 13, 256, 5, 5, 1, 2), 0, maxpool=True)) == 0  # fp32 5x5
     assert B.conv_variant_count(B.desc_of(sh, 0, maxpool=True, filt_winograd=True)) == 0
