@@ -36,6 +36,15 @@ struct State {
     std::map<Key, Choice> cache;
     std::map<Key, int> forced;                   // index into valid_list(desc)
     std::map<Key, std::vector<double>> times_us;  // per valid-list index, from the last autotune
+    // Per descriptor: its valid list and the cost model's picks.  The registry never changes after start-up, so these
+    // are computed once; a call then costs two map look-ups instead of a pass over every variant.
+    struct Memo {
+        std::vector<int> valid;
+        int pick_any = -2;       // cost model's pick with unlimited workspace (-2: not computed yet)
+        size_t pick_any_ws = 0;  // workspace that pick needs
+        int pick_nows = -2;      // cost model's pick among variants that need no workspace
+    };
+    std::map<Key, Memo> memo;
 };
 
 State& state()
@@ -219,10 +228,22 @@ int pick_heuristic(State& st, const std::vector<int>& valid, const conv_desc& d,
     return best;
 }
 
+State::Memo& memo_of(State& st, const conv_desc& d, int OH, int OW)
+{
+    const Key k = key_of(d);
+    auto it = st.memo.find(k);
+    if (it == st.memo.end()) {
+        it = st.memo.emplace(k, State::Memo{}).first;
+        it->second.valid = valid_list(st, d, OH, OW);
+    }
+    return it->second;
+}
+
 // Returns the registry index to run, or a negative status.
 int select_variant(State& st, const conv_desc& d, int OH, int OW, size_t ws_limit)
 {
-    const std::vector<int> valid = valid_list(st, d, OH, OW);
+    State::Memo& m = memo_of(st, d, OH, OW);
+    const std::vector<int>& valid = m.valid;  // ascending registry indices
     if (valid.empty()) return CONV_ENOVARIANT;
     const Key k = key_of(d);
     auto f = st.forced.find(k);
@@ -237,12 +258,23 @@ int select_variant(State& st, const conv_desc& d, int OH, int OW, size_t ws_limi
         for (const std::string* nm : {&c->second.best, &c->second.best_nows}) {
             auto it = st.by_name.find(*nm);
             if (it == st.by_name.end()) continue;
-            const Variant& v = st.variants[it->second];
-            if (!v.valid(v, d, OH, OW)) continue;
-            if (ws_bytes_of(v, d, OH, OW) <= ws_limit) return it->second;
+            if (!std::binary_search(valid.begin(), valid.end(), it->second)) continue;
+            if (ws_bytes_of(st.variants[it->second], d, OH, OW) <= ws_limit) return it->second;
         }
     }
-    const int h = pick_heuristic(st, valid, d, OH, OW, ws_limit);
+    // the unconstrained pick also wins under any limit that admits it
+    if (m.pick_any == -2) {
+        m.pick_any = pick_heuristic(st, valid, d, OH, OW, SIZE_MAX);
+        m.pick_any_ws = m.pick_any >= 0 ? ws_bytes_of(st.variants[m.pick_any], d, OH, OW) : 0;
+    }
+    if (m.pick_any >= 0 && m.pick_any_ws <= ws_limit) return m.pick_any;
+    int h;
+    if (ws_limit == 0) {
+        if (m.pick_nows == -2) m.pick_nows = pick_heuristic(st, valid, d, OH, OW, 0);
+        h = m.pick_nows;
+    } else {
+        h = pick_heuristic(st, valid, d, OH, OW, ws_limit);
+    }
     return h < 0 ? CONV_ENOVARIANT : h;
 }
 
@@ -353,7 +385,7 @@ size_t conv_workspace_bytes(const conv_desc* desc)
     State& st = state();
     std::lock_guard<std::mutex> g(st.mu);
     size_t need = 0;
-    for (int idx : valid_list(st, *desc, OH, OW)) need = std::max(need, ws_bytes_of(st.variants[idx], *desc, OH, OW));
+    for (int idx : memo_of(st, *desc, OH, OW).valid) need = std::max(need, ws_bytes_of(st.variants[idx], *desc, OH, OW));
     return need;
 }
 
@@ -420,7 +452,7 @@ int conv_autotune(const conv_desc* desc, const void* in, const void* filt, const
     std::vector<int> valid;
     {
         std::lock_guard<std::mutex> g(st.mu);
-        valid = valid_list(st, *desc, OH, OW);
+        valid = memo_of(st, *desc, OH, OW).valid;
     }
     if (valid.empty()) return CONV_ENOVARIANT;
     hipStream_t s = (hipStream_t)stream;
@@ -496,7 +528,7 @@ int conv_variant_count(const conv_desc* desc)
     if (rc) return rc;
     State& st = state();
     std::lock_guard<std::mutex> g(st.mu);
-    return (int)valid_list(st, *desc, OH, OW).size();
+    return (int)memo_of(st, *desc, OH, OW).valid.size();
 }
 
 int conv_variant_name(const conv_desc* desc, int idx, char* buf, size_t n)
@@ -512,7 +544,7 @@ int conv_variant_name(const conv_desc* desc, int idx, char* buf, size_t n)
         reg = select_variant(st, *desc, OH, OW, idx == -1 ? (size_t)-1 : 0);
         if (reg < 0) return reg;
     } else {
-        const std::vector<int> valid = valid_list(st, *desc, OH, OW);
+        const std::vector<int>& valid = memo_of(st, *desc, OH, OW).valid;
         if (idx < 0 || idx >= (int)valid.size()) return CONV_ENOVARIANT;
         reg = valid[idx];
     }
@@ -527,7 +559,7 @@ long long conv_variant_workspace(const conv_desc* desc, int idx)
     if (rc) return rc;
     State& st = state();
     std::lock_guard<std::mutex> g(st.mu);
-    const std::vector<int> valid = valid_list(st, *desc, OH, OW);
+    const std::vector<int>& valid = memo_of(st, *desc, OH, OW).valid;
     if (idx < 0 || idx >= (int)valid.size()) return CONV_ENOVARIANT;
     return (long long)ws_bytes_of(st.variants[valid[idx]], *desc, OH, OW);
 }
@@ -543,7 +575,7 @@ int conv_force_variant(const conv_desc* desc, int idx)
         st.forced.erase(key_of(*desc));
         return CONV_OK;
     }
-    if (idx < 0 || idx >= (int)valid_list(st, *desc, OH, OW).size()) return CONV_ENOVARIANT;
+    if (idx < 0 || idx >= (int)memo_of(st, *desc, OH, OW).valid.size()) return CONV_ENOVARIANT;
     st.forced[key_of(*desc)] = idx;
     return CONV_OK;
 }
@@ -683,7 +715,7 @@ size_t conv_transformed_filter_bytes(const conv_desc* desc)
     if (desc->flags & kLayoutFlags) return 0;
     State& st = state();
     std::lock_guard<std::mutex> g(st.mu);
-    if (valid_list(st, d, OH, OW).empty()) return 0;
+    if (memo_of(st, d, OH, OW).valid.empty()) return 0;
     return wino_transformed_filter_bytes(d.K, d.C);
 }
 
