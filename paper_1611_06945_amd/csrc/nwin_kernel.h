@@ -147,19 +147,28 @@ __global__ __launch_bounds__(CFG::NT) void nwin_kernel(ConvArgs a)
         constexpr int T0 = decltype(t0)::value, T1 = decltype(t1)::value;
         const elem_t* __restrict__ As = As0 + buf * TM * LDA + ((wm * TMB) * 32 + li) * LDA + chan0;
         const elem_t* __restrict__ Bs = Bs0 + buf * b_elems + chan0;
-#pragma unroll
-        for (int t = T0; t < T1; ++t) {
+        // The operands of tap t + 1 are read before the products of tap t are issued (two register sets): a whole tap's
+        // MFMAs cover the LDS latency.  Left to itself the compiler reads each operand just ahead of its use.
+        uint4 af[2][TMB], bf[2][NBW];
+        auto read_tap = [&](int t, int set) {
             const int r = t / S, s = t % S;
-            uint4 af[TMB], bf[NBW];
 #pragma unroll
-            for (int mb = 0; mb < TMB; ++mb) af[mb] = *(const uint4*)&As[mb * 32 * LDA + t * CB];
+            for (int mb = 0; mb < TMB; ++mb) af[set][mb] = *(const uint4*)&As[mb * 32 * LDA + t * CB];
             const int toff = (r * PW + s) * CP;
 #pragma unroll
-            for (int nb = 0; nb < NBW; ++nb) bf[nb] = *(const uint4*)&Bs[bpos[nb] + toff];
+            for (int nb = 0; nb < NBW; ++nb) bf[set][nb] = *(const uint4*)&Bs[bpos[nb] + toff];
+        };
+        read_tap(T0, 0);
+#pragma unroll
+        for (int t = T0; t < T1; ++t) {
+            const int set = (t - T0) & 1;
+            if (t + 1 < T1) read_tap(t + 1, set ^ 1);
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int mb = 0; mb < TMB; ++mb)
 #pragma unroll
-                for (int nb = 0; nb < NBW; ++nb) acc[mb][nb] = mma_t::run(af[mb], bf[nb], acc[mb][nb]);
+                for (int nb = 0; nb < NBW; ++nb) acc[mb][nb] = mma_t::run(af[set][mb], bf[set][nb], acc[mb][nb]);
+            __builtin_amdgcn_sched_barrier(0);
         }
     };
     constexpr int TSPLIT = (RS * 5 + 8) / 9;

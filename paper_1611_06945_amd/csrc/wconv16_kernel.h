@@ -243,10 +243,20 @@ __global__ __launch_bounds__(CFG::NT) void wconv16_kernel(ConvArgs a)
                     araw[mb][4 * i + 3] = v.w;
                 }
         }
+        // The patch operands of tap t + 1 are read before the products of tap t are issued (two register sets): a whole
+        // tap's MFMAs cover the LDS latency.  Left to itself the compiler reads each operand just ahead of its use.
+        uint4 bf[2][NBW];
+        auto read_tap = [&](int t, int set) {
+            const int toff = ((t / S) * PW + (t % S)) * CP;
+#pragma unroll
+            for (int nb = 0; nb < NBW; ++nb) bf[set][nb] = *(const uint4*)&Bs[bpos[nb] + toff];
+        };
+        read_tap(T0, 0);
 #pragma unroll
         for (int t = T0; t < T1; ++t) {
-            const int r = t / S, s = t % S;
-            uint4 af[TMB], bf[NBW];
+            const int set = (t - T0) & 1;
+            if (t + 1 < T1) read_tap(t + 1, set ^ 1);
+            uint4 af[TMB];
 #pragma unroll
             for (int mb = 0; mb < TMB; ++mb) {
                 uint32_t d[4];
@@ -259,13 +269,12 @@ __global__ __launch_bounds__(CFG::NT) void wconv16_kernel(ConvArgs a)
                 }
                 af[mb] = make_uint4(d[0], d[1], d[2], d[3]);
             }
-            const int toff = (r * PW + s) * CP;
-#pragma unroll
-            for (int nb = 0; nb < NBW; ++nb) bf[nb] = *(const uint4*)&Bs[bpos[nb] + toff];
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int mb = 0; mb < TMB; ++mb)
 #pragma unroll
-                for (int nb = 0; nb < NBW; ++nb) acc[mb][nb] = mma_t::run(af[mb], bf[nb], acc[mb][nb]);
+                for (int nb = 0; nb < NBW; ++nb) acc[mb][nb] = mma_t::run(af[mb], bf[set][nb], acc[mb][nb]);
+            __builtin_amdgcn_sched_barrier(0);
         }
     };
     constexpr int TSPLIT = (RS * 5 + 8) / 9;

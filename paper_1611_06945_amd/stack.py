@@ -241,15 +241,16 @@ class ConvStack:
 
     def _choose_formats(self, x, filts, biases, stream) -> None:
         """Time each layer in each format (its best variant), each conversion and each pool, then pick per layer by
-        dynamic programming over the chain.  Data content does not matter for the timings; scratch tensors are used."""
+        dynamic programming over the chain, on scratch tensors filled with random values."""
         torch = self.torch
         n = len(self.shapes)
         conv_t = [{} for _ in range(n)]      # (format, out layout) -> microseconds
         fused_t = [{} for _ in range(n)]     # (format, pooled-output layout) -> microseconds of convolution + fused pool
         glue_t = [{} for _ in range(n)]      # (conv out layout, handoff layout) -> microseconds of pool / conversion
         for i, s in enumerate(self.shapes):
-            xin = torch.zeros(s.in_shape(), dtype=self.tdt, device="cuda")
-            f = torch.zeros(s.filt_shape(), dtype=self.tdt, device="cuda")
+            # random values of the size of real activations and weights: kernels run measurably faster on zeros
+            xin = torch.rand(s.in_shape(), device="cuda").to(self.tdt)
+            f = (torch.randn(s.filt_shape(), device="cuda") * (2.0 / (s.C * s.R * s.S)) ** 0.5).to(self.tdt)
             out = torch.empty(s.out_shape(), dtype=self.tdt, device="cuda")
             for fmt in ((NCHW, NHWC) if self.nhwc_capable(i) else (NCHW,)):
                 for olay in ((NCHW, NHWC) if fmt == NHWC or self.planar_writes_nhwc(i) else (NCHW,)):
