@@ -183,15 +183,17 @@ def test_config5_stack_with_the_second_pool_fused_into_its_convolution(dtype):
     _check_stack_against_oracle(stack, shapes, gen, dtype, y)
 
 
-@pytest.mark.parametrize("formats", [None, ["nchw", "nhwc", "nhwc", "nhwc", "nhwc"]])
-def test_config5_stack_as_hip_graph(formats):
+@pytest.mark.parametrize("formats,fuse_pool", [(None, False), (["nchw", "nhwc", "nhwc", "nhwc", "nhwc"], False),
+                                               (["nchw", "nhwc", "nhwc", "nhwc", "nhwc"], True)])
+def test_config5_stack_as_hip_graph(formats, fuse_pool):
     """The stack recorded into a HIP graph must reproduce the eagerly enqueued stack bit for bit, on every replay: the
     graph is replayed several times with eager runs, buffer poisoning and synchronisations in between."""
     torch = torch_mod()
     dtype = wl.F16
     layers = wl.config5_layers(5, dtype)
     shapes = [w.shape for w in layers]
-    stack = ConvStack(shapes, dtype, pool_after=wl.STACK_POOL_AFTER, formats=formats)
+    stack = ConvStack(shapes, dtype, pool_after=wl.STACK_POOL_AFTER, formats=formats, fuse_pool=fuse_pool)
+    assert any(stack.fused) == fuse_pool
     gen = [w.generate() for w in layers]
     x = to_device(gen[0]["in"], dtype)
     filts = [to_device(g["filt"], dtype) for g in gen]
