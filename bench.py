@@ -323,6 +323,8 @@ def main():
     ap.add_argument("--steps", type=int, default=2000)
     ap.add_argument("--warmup", type=int, default=100)
     ap.add_argument("--workload", default="cfg4_mid3x3_n20_f32")
+    ap.add_argument("--variant", help="run the headline workload on this variant instead of the autotuned one "
+                                      "(for profiling one kernel; the figure is then not the headline)")
     ap.add_argument("--no-layers", action="store_true", help="skip the per-layer table")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--sweep", choices=["appendix_a"], help="time the paper's whole benchmark set instead of one workload")
@@ -368,7 +370,14 @@ def main():
     # ---- headline: exactly `steps` timed steps after `warmup` untimed ones --------------------------------
     r = Resident(w)
     variant = r.autotune()
-    log("headline %s -> %s" % (w.name, variant))
+    if a.variant:
+        names = [B.conv_variant_name(r.desc, i) for i in range(B.conv_variant_count(r.desc))]
+        if a.variant not in names:
+            log("variant %r is not valid for %s; choose from %s" % (a.variant, w.name, names))
+            sys.exit(2)
+        B.conv_force_variant(r.desc, names.index(a.variant))
+        variant = r.variant = a.variant
+    log("headline %s -> %s%s" % (w.name, variant, " (forced)" if a.variant else ""))
     for _ in range(a.warmup):
         r.step()
     torch.cuda.synchronize()
