@@ -231,8 +231,11 @@ __global__ __launch_bounds__(CFG::NT) void nwin_kernel(ConvArgs a)
                 // (all three are monotone, so this equals pooling the rounded activations)
                 const int npool = a.POH * a.POW;
                 for (int e = tid; e < 32 * npool; e += NT) {
-                    const int row = onhwc ? (e & 31) : e / npool, pp = onhwc ? (e >> 5) : e - row * npool;
-                    const int py = pp / a.POW, px = pp - py * a.POW;
+                    uint32_t qrow, qpp, upy, upx;  // a.dX divides by POH*POW, a.dY by POW
+                    a.dX.divmod((uint32_t)e, qrow, qpp);
+                    const int row = onhwc ? (e & 31) : (int)qrow, pp = onhwc ? (e >> 5) : (int)qpp;
+                    a.dY.divmod((uint32_t)pp, upy, upx);
+                    const int py = (int)upy, px = (int)upx;
                     const int k = m0 + (wmi * TMB + mb) * 32 + row;
                     float m = -INFINITY;
 #pragma unroll
@@ -300,6 +303,10 @@ hipError_t nwin_launch(const Variant& v, ConvArgs& a, hipStream_t s)
     a.nsplit = v.split;
     a.steps_per_split = (total_chunks + v.split - 1) / v.split;
     dim3 grid((unsigned)(a.N * g.bands), (unsigned)((a.K + CFG::TM - 1) / CFG::TM), (unsigned)v.split);
+    if (a.pool) {
+        a.dX = make_fastdiv((uint32_t)(a.POH * a.POW));
+        a.dY = make_fastdiv((uint32_t)a.POW);
+    }
     hipLaunchKernelGGL(nwin_kernel<CFG>, grid, dim3(CFG::NT), lds, s, a);
     return hipGetLastError();
 }

@@ -341,8 +341,10 @@ __global__ __launch_bounds__(CFG::NT) void wconv16_kernel(ConvArgs a)
                 // (all three are monotone, so this equals pooling the rounded activations)
                 const int npool = a.POH * a.POW;
                 for (int e = tid; e < 32 * npool; e += NT) {
-                    const int row = e / npool, pp = e - row * npool;
-                    const int py = pp / a.POW, px = pp - py * a.POW;
+                    uint32_t urow, upp, upy, upx;  // a.dX divides by POH*POW, a.dY by POW
+                    a.dX.divmod((uint32_t)e, urow, upp);
+                    a.dY.divmod(upp, upy, upx);
+                    const int row = (int)urow, pp = (int)upp, py = (int)upy, px = (int)upx;
                     const int k = m0 + (wmi * TMB + mb) * 32 + row;
                     float m = -INFINITY;
 #pragma unroll
@@ -422,6 +424,10 @@ hipError_t wconv16_launch(const Variant& v, ConvArgs& a, hipStream_t s)
     a.nsplit = v.split;
     a.steps_per_split = (total_chunks + v.split - 1) / v.split;
     dim3 grid((unsigned)(a.N * g.bands), (unsigned)((a.K + CFG::TM - 1) / CFG::TM), (unsigned)v.split);
+    if (a.pool) {
+        a.dX = make_fastdiv((uint32_t)(a.POH * a.POW));
+        a.dY = make_fastdiv((uint32_t)a.POW);
+    }
     hipLaunchKernelGGL(wconv16_kernel<CFG>, grid, dim3(CFG::NT), lds, s, a);
     return hipGetLastError();
 }

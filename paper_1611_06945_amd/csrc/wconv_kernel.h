@@ -251,8 +251,10 @@ void wconv_kernel(ConvArgs a)
             // monotone, so this equals pooling the activations)
             const int npool = a.POH * a.POW;
             for (int e = tid; e < 16 * npool; e += NT) {
-                const int row = e / npool, pp = e - row * npool;
-                const int py = pp / a.POW, px = pp - py * a.POW;
+                uint32_t urow, upp, upy, upx;  // a.dX divides by POH*POW, a.dY by POW
+                a.dX.divmod((uint32_t)e, urow, upp);
+                a.dY.divmod(upp, upy, upx);
+                const int row = (int)urow, pp = (int)upp, py = (int)upy, px = (int)upx;
                 const int k = m0 + mb * 16 + row;
                 float m = -INFINITY;
 #pragma unroll
@@ -338,6 +340,10 @@ hipError_t wconv_launch(const Variant& v, ConvArgs& a, hipStream_t s)
     a.steps_per_split = (total_chunks + v.split - 1) / v.split;
     const int ntiles = (a.OHW + CFG::TNP - 1) / CFG::TNP;
     dim3 grid((unsigned)(a.N * ntiles), (unsigned)((a.K + CFG::TM - 1) / CFG::TM), (unsigned)v.split);
+    if (a.pool) {
+        a.dX = make_fastdiv((uint32_t)(a.POH * a.POW));
+        a.dY = make_fastdiv((uint32_t)a.POW);
+    }
     hipLaunchKernelGGL(wconv_kernel<CFG>, grid, dim3(CFG::NT), lds, s, a);
     return hipGetLastError();
 }
