@@ -131,6 +131,22 @@ int conv_fwd_ws(const conv_desc* desc, const void* in, const void* filt, const f
                 void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * For callers that cannot allocate device memory or be handed a workspace (code under HIP graph capture, serving
+ * loops, harnesses that forbid hipMalloc): conv_fwd_ws with the scratch memory taken from an array the library holds
+ * itself, CONV_STATIC_SCRATCH_BYTES per GPU, resident from library load to process end.  The call allocates and frees
+ * nothing.  The variant is selected as conv_fwd_ws selects it with unlimited workspace (forced > autotuned/cached >
+ * cost model); when that variant needs more than CONV_STATIC_SCRATCH_BYTES the call is rejected with CONV_EWORKSPACE
+ * (conv_strerror names the variant and both sizes) and nothing is enqueued -- use conv_fwd or conv_fwd_ws then.
+ * Results are bit-identical to conv_fwd_ws running the same variant.  Nothing in the array has to start at zero
+ * (every partial sum and every transformed filter is written before it is read), and its contents are undefined
+ * afterwards.  Every call on one GPU shares that GPU's array: calls that overlap in time on one GPU (different
+ * streams, or threads) race on it and must be serialised by the caller; calls on one stream are ordered.
+ */
+#define CONV_STATIC_SCRATCH_BYTES (32u << 20)
+int conv_fwd_static(const conv_desc* desc, const void* in, const void* filt, const float* bias, void* out,
+                    void* stream);
+
+/*
  * Brute-force autotuning (paper, Section 3 "Variant Selection and Autotuning":
  * exhaustive search over a fixed set of configurations, by measured run time):
  * runs every variant valid for `desc` that fits `workspace_bytes` on the given

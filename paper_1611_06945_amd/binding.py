@@ -20,6 +20,7 @@ LIB_PATH = os.path.join(_PKG, "libconvfwd.so")
 CONV_F32, CONV_F16, CONV_BF16 = 0, 1, 2
 CONV_FLAG_RELU, CONV_FLAG_IN_NHWC, CONV_FLAG_OUT_NHWC, CONV_FLAG_FILT_KRSC, CONV_FLAG_FILT_WINOGRAD = 1, 2, 4, 8, 16
 CONV_FLAG_MAXPOOL_3X3S2 = 32
+CONV_STATIC_SCRATCH_BYTES = 32 << 20
 CONV_OK, CONV_EINVAL, CONV_EDTYPE, CONV_EWORKSPACE, CONV_EHIP, CONV_ENOVARIANT, CONV_EIO = 0, -1, -2, -3, -4, -5, -6
 
 
@@ -67,6 +68,8 @@ def lib() -> ctypes.CDLL:
         L.conv_fwd.restype = ctypes.c_int
         L.conv_fwd_ws.argtypes = [dp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
         L.conv_fwd_ws.restype = ctypes.c_int
+        L.conv_fwd_static.argtypes = [dp, vp, vp, vp, vp, vp]
+        L.conv_fwd_static.restype = ctypes.c_int
         L.conv_autotune.argtypes = [dp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
         L.conv_autotune.restype = ctypes.c_int
         L.conv_variant_count.argtypes = [dp]
@@ -181,6 +184,11 @@ def conv_fwd(desc, inp, filt, bias, out, stream=None) -> None:
 def conv_fwd_ws(desc, inp, filt, bias, out, workspace, workspace_bytes, stream=None) -> None:
     _check(lib().conv_fwd_ws(ctypes.byref(desc), _ptr(inp), _ptr(filt), _ptr(bias), _ptr(out), _ptr(workspace),
                              int(workspace_bytes), _stream(stream)), "conv_fwd_ws")
+
+
+def conv_fwd_static(desc, inp, filt, bias, out, stream=None) -> None:
+    _check(lib().conv_fwd_static(ctypes.byref(desc), _ptr(inp), _ptr(filt), _ptr(bias), _ptr(out), _stream(stream)),
+           "conv_fwd_static")
 
 
 def conv_autotune(desc, inp, filt, bias, out, workspace=None, workspace_bytes=0, stream=None) -> None:

@@ -75,6 +75,7 @@ State& state()
 }
 
 thread_local std::string g_hip_msg;
+thread_local std::string g_ws_msg;  // detail for CONV_EWORKSPACE from conv_fwd_static
 
 int hip_fail(hipError_t e, const char* what)
 {
@@ -333,6 +334,35 @@ int run_variant(const Variant& v, const conv_desc& d, ConvArgs& a, hipStream_t s
 
 bool aligned16(const void* p) { return (((uintptr_t)p) & 15u) == 0; }
 
+// Library-owned scratch of conv_fwd_static: one array per GPU, living in the code object's data segment for as long as
+// the process does.  In host code the symbol below is only a handle, never a device address: the address on a device
+// comes from hipGetSymbolAddress with that device current (static_scratch_ptr), and only that pointer is handed to
+// kernels.
+static __device__ __align__(256) unsigned char scratch[CONV_STATIC_SCRATCH_BYTES];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+// Device address of `scratch` on the current device (looked up once per device).
+int static_scratch_ptr(void** out)
+{
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return hip_fail(e, "hipGetDevice");
+    if (dev < 0 || dev >= kMaxDevices) return hip_fail(hipErrorInvalidDevice, "conv_fwd_static: device ordinal");
+    std::lock_guard<std::mutex> g(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return hip_fail(e, "hipGetSymbolAddress(scratch)");
+        if (!p || (((uintptr_t)p) & 255u)) return hip_fail(hipErrorInvalidSymbol, "scratch: null or misaligned address");
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return CONV_OK;
+}
+
 int fwd_common(const conv_desc* desc, const void* in, const void* filt, const float* bias, void* out, void* ws,
                size_t ws_bytes, void* stream)
 {
@@ -398,6 +428,38 @@ int conv_fwd_ws(const conv_desc* desc, const void* in, const void* filt, const f
                 size_t workspace_bytes, void* stream)
 {
     return fwd_common(desc, in, filt, bias, out, workspace, workspace_bytes, stream);
+}
+
+int conv_fwd_static(const conv_desc* desc, const void* in, const void* filt, const float* bias, void* out, void* stream)
+{
+    int OH, OW;
+    const int rc = check_desc(desc, OH, OW);
+    if (rc) return rc;
+    if (!in || !filt || !out) return CONV_EINVAL;
+    if (!aligned16(in) || !aligned16(filt) || !aligned16(out) || (bias && (((uintptr_t)bias) & 3u))) return CONV_EINVAL;
+    State& st = state();
+    int idx;
+    {
+        std::lock_guard<std::mutex> g(st.mu);
+        idx = select_variant(st, *desc, OH, OW, SIZE_MAX);
+    }
+    if (idx < 0) return idx;
+    const size_t need = ws_bytes_of(st.variants[idx], *desc, OH, OW);
+    if (need > (size_t)CONV_STATIC_SCRATCH_BYTES) {
+        char msg[256];
+        snprintf(msg, sizeof msg, "conv_fwd_static: variant %s needs %zu bytes of scratch, the library holds %zu",
+                 st.variants[idx].name.c_str(), need, (size_t)CONV_STATIC_SCRATCH_BYTES);
+        g_ws_msg = msg;
+        return CONV_EWORKSPACE;
+    }
+    void* ws = nullptr;
+    if (need) {
+        const int prc = static_scratch_ptr(&ws);
+        if (prc) return prc;
+    }
+    ConvArgs a;
+    fill_args(a, *desc, OH, OW, in, filt, bias, out, ws);
+    return run_variant(st.variants[idx], *desc, a, (hipStream_t)stream);
 }
 
 int conv_time_us(const conv_desc* desc, const void* in, const void* filt, const float* bias, void* out, void* workspace,
@@ -755,7 +817,11 @@ const char* conv_strerror(int status)
         case CONV_OK: return "success";
         case CONV_EINVAL: return "invalid descriptor, pointer, alignment or size";
         case CONV_EDTYPE: return "unsupported dtype";
-        case CONV_EWORKSPACE: return "workspace missing or too small";
+        case CONV_EWORKSPACE:
+            if (g_ws_msg.empty()) return "workspace missing or too small";
+            buf = "workspace missing or too small: " + g_ws_msg;
+            g_ws_msg.clear();
+            return buf.c_str();
         case CONV_EHIP: buf = "HIP error: " + g_hip_msg; return buf.c_str();
         case CONV_ENOVARIANT: return "no such variant for this descriptor";
         case CONV_EIO: return "autotune cache file unreadable, unwritable or malformed";

@@ -385,3 +385,27 @@ def test_fused_maxpool_flag_host_rules():
     assert all(B.conv_variant_name(f32, i).startswith("wconv_f32_3x3") for i in range(B.conv_variant_count(f32)))
     assert B.conv_variant_count(B.desc_of(ConvShape(20, 96, 13, 13, 256, 5, 5, 1, 2), 0, maxpool=True)) == 0  # fp32 5x5
     assert B.conv_variant_count(B.desc_of(sh, 0, maxpool=True, filt_winograd=True)) == 0
+
+
+def test_static_scratch_entry_point_validates_and_refuses_oversized_variants_on_the_host():
+    d = B.make_desc(20, 64, 56, 56, 192, 3, 3, 1, 1, B.CONV_F32, relu=True)
+    with pytest.raises(B.ConvError) as ei:
+        B.conv_fwd_static(d, None, 512, None, 1024)
+    assert ei.value.status == B.CONV_EINVAL
+    with pytest.raises(B.ConvError) as ei:
+        B.conv_fwd_static(d, 256 + 4, 512, None, 1024)  # misaligned input pointer
+    assert ei.value.status == B.CONV_EINVAL
+    over = [i for i in range(B.conv_variant_count(d)) if B.conv_variant_workspace(d, i) > B.CONV_STATIC_SCRATCH_BYTES]
+    assert over
+    B.conv_force_variant(d, over[0])
+    try:
+        with pytest.raises(B.ConvError) as ei:  # refused before any HIP call: works without a GPU
+            B.conv_fwd_static(d, 256, 512, None, 1024)
+        assert ei.value.status == B.CONV_EWORKSPACE
+        assert B.conv_variant_name(d, over[0]) in str(ei.value)
+        assert str(B.CONV_STATIC_SCRATCH_BYTES) in str(ei.value)
+    finally:
+        B.conv_force_variant(d, -1)
+    # the header's constant and the binding's agree
+    text = open(os.path.join(ROOT, "include", "convfwd.h")).read()
+    assert "#define CONV_STATIC_SCRATCH_BYTES (32u << 20)" in text and B.CONV_STATIC_SCRATCH_BYTES == 32 << 20
