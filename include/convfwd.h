@@ -69,7 +69,14 @@ enum {
      * tensors); other descriptors give CONV_ENOVARIANT and the caller
      * runs maxpool_fwd() behind the convolution.  The result is bit-identical to that sequence run with the same
      * variant.  Not combinable with CONV_FLAG_FILT_WINOGRAD. */
-    CONV_FLAG_MAXPOOL_3X3S2 = 32u
+    CONV_FLAG_MAXPOOL_3X3S2 = 32u,
+    /* Filters handed over in the order the 16-bit matrix instructions consume them, as written by
+     * conv_transform_filters() for the same descriptor with this bit set: the other ahead-of-time filter conversion
+     * (Section 3, "Graph-level Optimizations"; the filter operand then goes from memory straight into the multiplying
+     * wave's registers).  fp16/bf16, stride 1, C % 16 == 0, windows the packed-filter kernels are built for (3x3,
+     * 5x5) with pad < window, input channel-innermost (CONV_FLAG_IN_NHWC), output in either format; otherwise
+     * CONV_ENOVARIANT.  Not combinable with CONV_FLAG_FILT_KRSC, CONV_FLAG_FILT_WINOGRAD or CONV_FLAG_MAXPOOL_3X3S2. */
+    CONV_FLAG_FILT_PACKED = 64u
 };
 
 typedef enum {
@@ -234,12 +241,16 @@ int maxpool_fwd_layout(int32_t N, int32_t C, int32_t H, int32_t W, int32_t win, 
 int conv_convert_layout(int32_t A, int32_t B, int32_t S, int32_t dtype, const void* in, void* out, void* stream);
 
 /*
- * Filter transform of the Winograd F(2x2,3x3) variants as an explicit, separately timed conversion: U = G g G^T for
- * every (output channel, input channel) pair of the KCRS filter tensor `filt` (device, 16-byte aligned), written to
- * `out` (device, 256-byte aligned, conv_transformed_filter_bytes(desc) bytes, layout private to the library), which
- * is then passed as `filt` of a descriptor with CONV_FLAG_FILT_WINOGRAD set.  `desc` is the layer's descriptor with or
- * without that bit.  conv_transformed_filter_bytes returns 0, conv_transform_filters CONV_ENOVARIANT, when no
- * Winograd variant serves the descriptor; CONV_EINVAL for NULL or misaligned pointers.  Enqueued on `stream`.
+ * Ahead-of-time filter conversions as explicit, separately timed calls (paper, Section 3 "Graph-level
+ * Optimizations": data-format conversions are operations of their own).  `filt` is the KCRS filter tensor (device,
+ * 16-byte aligned); the result goes to `out` (device, 256-byte aligned, conv_transformed_filter_bytes(desc) bytes,
+ * layout private to the library), which is then passed as `filt` of the layer's descriptor with the format's bit set.
+ * The target format is the one whose bit `desc` carries:
+ *   CONV_FLAG_FILT_WINOGRAD  U = G g G^T of the Winograd F(2x2,3x3) variants (fp32);
+ *   CONV_FLAG_FILT_PACKED    the matrix-instruction operand order of the packed-filter kernels (fp16/bf16);
+ * with neither bit it is the Winograd domain for fp32 and the packed order for fp16/bf16.  Other bits of `desc`
+ * describe the layer as usual.  conv_transformed_filter_bytes returns 0, conv_transform_filters CONV_ENOVARIANT, when
+ * no kernel of that format serves the layer; CONV_EINVAL for NULL or misaligned pointers.  Enqueued on `stream`.
  */
 size_t conv_transformed_filter_bytes(const conv_desc* desc);
 int conv_transform_filters(const conv_desc* desc, const void* filt, void* out, void* stream);

@@ -20,6 +20,7 @@ LIB_PATH = os.path.join(_PKG, "libconvfwd.so")
 CONV_F32, CONV_F16, CONV_BF16 = 0, 1, 2
 CONV_FLAG_RELU, CONV_FLAG_IN_NHWC, CONV_FLAG_OUT_NHWC, CONV_FLAG_FILT_KRSC, CONV_FLAG_FILT_WINOGRAD = 1, 2, 4, 8, 16
 CONV_FLAG_MAXPOOL_3X3S2 = 32
+CONV_FLAG_FILT_PACKED = 64
 CONV_STATIC_SCRATCH_BYTES = 32 << 20
 CONV_OK, CONV_EINVAL, CONV_EDTYPE, CONV_EWORKSPACE, CONV_EHIP, CONV_ENOVARIANT, CONV_EIO = 0, -1, -2, -3, -4, -5, -6
 
@@ -119,11 +120,11 @@ def make_desc(N, C, H, W, K, R, S, stride=1, pad=0, dtype=CONV_F32, relu=False, 
 
 
 def desc_of(shape, dtype=CONV_F32, relu=True, in_nhwc=False, out_nhwc=False, filt_krsc=False, filt_winograd=False,
-            maxpool=False) -> conv_desc:
+            maxpool=False, filt_packed=False) -> conv_desc:
     """conv_desc from a workloads.ConvShape (optionally with channel-innermost tensor formats)."""
     flags = ((CONV_FLAG_RELU if relu else 0) | (CONV_FLAG_IN_NHWC if in_nhwc else 0) |
              (CONV_FLAG_OUT_NHWC if out_nhwc else 0) | (CONV_FLAG_FILT_KRSC if filt_krsc else 0) |
-             (CONV_FLAG_FILT_WINOGRAD if filt_winograd else 0) | (CONV_FLAG_MAXPOOL_3X3S2 if maxpool else 0))
+             (CONV_FLAG_FILT_WINOGRAD if filt_winograd else 0) | (CONV_FLAG_MAXPOOL_3X3S2 if maxpool else 0) | (CONV_FLAG_FILT_PACKED if filt_packed else 0))
     return make_desc(shape.N, shape.C, shape.H, shape.W, shape.K, shape.R, shape.S, shape.stride, shape.pad, dtype,
                      flags=flags)
 
@@ -262,7 +263,7 @@ def conv_transformed_filter_bytes(desc) -> int:
 
 
 def conv_transform_filters(desc, filt, out, stream=None) -> None:
-    """KCRS filters -> Winograd-domain filters for a descriptor with CONV_FLAG_FILT_WINOGRAD."""
+    """KCRS filters -> the ahead-of-time format whose bit `desc` carries (Winograd domain, or MFMA operand order)."""
     _check(lib().conv_transform_filters(ctypes.byref(desc), _ptr(filt), _ptr(out), _stream(stream)), "conv_transform_filters")
 
 

@@ -68,6 +68,8 @@ State& state()
         register_swin_bf16(s->variants);
         register_wconv_f16(s->variants);
         register_wconv_bf16(s->variants);
+        register_pwin_f16(s->variants);
+        register_pwin_bf16(s->variants);
         for (size_t i = 0; i < s->variants.size(); ++i) s->by_name[s->variants[i].name] = (int)i;
         return s;
     }();
@@ -84,7 +86,8 @@ int hip_fail(hipError_t e, const char* what)
 }
 
 constexpr uint32_t kLayoutFlags = CONV_FLAG_IN_NHWC | CONV_FLAG_OUT_NHWC | CONV_FLAG_FILT_KRSC;
-constexpr uint32_t kKnownFlags = CONV_FLAG_RELU | kLayoutFlags | CONV_FLAG_FILT_WINOGRAD | CONV_FLAG_MAXPOOL_3X3S2;
+constexpr uint32_t kKnownFlags =
+    CONV_FLAG_RELU | kLayoutFlags | CONV_FLAG_FILT_WINOGRAD | CONV_FLAG_MAXPOOL_3X3S2 | CONV_FLAG_FILT_PACKED;
 
 // Validation shared by every entry point; fills OH/OW.
 int check_desc(const conv_desc* d, int& OH, int& OW)
@@ -131,7 +134,15 @@ std::vector<int> valid_list(State& st, const conv_desc& d, int OH, int OW)
     if (pool && wino_filters) return r;
     // ... except planar input and filters with a channel-innermost output, which some planar kernels can write
     const bool planar_to_nhwc = (d.flags & kLayoutFlags) == CONV_FLAG_OUT_NHWC;
+    // filters in MFMA operand order: only the kernels written for them, which check the other formats themselves
+    const bool packed = (d.flags & CONV_FLAG_FILT_PACKED) != 0;
+    if (packed && (wino_filters || (d.flags & CONV_FLAG_FILT_KRSC))) return r;
     for (size_t i = 0; i < st.variants.size(); ++i) {
+        if (packed != ((st.variants[i].traits & TRAIT_PACKED_FILTERS) != 0)) continue;
+        if (packed) {
+            if (st.variants[i].valid(st.variants[i], d, OH, OW)) r.push_back((int)i);
+            continue;
+        }
         if (planar_to_nhwc) {
             if (!(st.variants[i].traits & TRAIT_PLANAR_TO_NHWC)) continue;
         } else if ((st.variants[i].family == FAM_NHWC) != layout) {
@@ -768,14 +779,33 @@ int conv_convert_layout(int32_t A, int32_t B, int32_t S, int32_t dtype, const vo
     return CONV_OK;
 }
 
+// The target format of a filter conversion: the flag the descriptor carries, else Winograd for fp32 and the MFMA
+// operand order for the 16-bit types.
+static uint32_t filter_target(const conv_desc* desc)
+{
+    if (desc->flags & CONV_FLAG_FILT_PACKED) return CONV_FLAG_FILT_PACKED;
+    if (desc->flags & CONV_FLAG_FILT_WINOGRAD) return CONV_FLAG_FILT_WINOGRAD;
+    return desc->dtype == CONV_F32 ? CONV_FLAG_FILT_WINOGRAD : CONV_FLAG_FILT_PACKED;
+}
+
 size_t conv_transformed_filter_bytes(const conv_desc* desc)
 {
     int OH, OW;
     if (check_desc(desc, OH, OW)) return 0;
+    if ((desc->flags & CONV_FLAG_FILT_PACKED) && (desc->flags & CONV_FLAG_FILT_WINOGRAD)) return 0;
+    State& st = state();
+    if (filter_target(desc) == CONV_FLAG_FILT_PACKED) {
+        // served when some packed-filter kernel accepts the layer with a channel-innermost input
+        if (desc->dtype == CONV_F32 || (desc->C % 16) != 0 || (desc->flags & CONV_FLAG_FILT_KRSC)) return 0;
+        conv_desc d = *desc;
+        d.flags = (d.flags & ~(kLayoutFlags | CONV_FLAG_MAXPOOL_3X3S2)) | CONV_FLAG_FILT_PACKED | CONV_FLAG_IN_NHWC;
+        std::lock_guard<std::mutex> g(st.mu);
+        if (memo_of(st, d, OH, OW).valid.empty()) return 0;
+        return (size_t)((d.K + 31) / 32) * 32 * (size_t)d.C * d.R * d.S * 2;
+    }
     conv_desc d = *desc;
     d.flags = (d.flags & ~kLayoutFlags) | CONV_FLAG_FILT_WINOGRAD;
     if (desc->flags & kLayoutFlags) return 0;
-    State& st = state();
     std::lock_guard<std::mutex> g(st.mu);
     if (memo_of(st, d, OH, OW).valid.empty()) return 0;
     return wino_transformed_filter_bytes(d.K, d.C);
@@ -788,7 +818,11 @@ int conv_transform_filters(const conv_desc* desc, const void* filt, void* out, v
     if (rc) return rc;
     if (!filt || !out || !aligned16(filt) || (((uintptr_t)out) & 255u) || filt == out) return CONV_EINVAL;
     if (conv_transformed_filter_bytes(desc) == 0) return CONV_ENOVARIANT;
-    const hipError_t e = launch_wino_filter_transform((const float*)filt, (float*)out, desc->K, desc->C, (hipStream_t)stream);
+    hipError_t e;
+    if (filter_target(desc) == CONV_FLAG_FILT_PACKED)
+        e = launch_pack_filters16(filt, out, desc->K, desc->C, desc->R * desc->S, (hipStream_t)stream);
+    else
+        e = launch_wino_filter_transform((const float*)filt, (float*)out, desc->K, desc->C, (hipStream_t)stream);
     if (e != hipSuccess) return hip_fail(e, "transform_filters");
     return CONV_OK;
 }

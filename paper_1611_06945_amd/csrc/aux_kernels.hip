@@ -326,6 +326,39 @@ __global__ __launch_bounds__(256) void transpose_kernel(const E* __restrict__ in
     }
 }
 
+// Filters [K][C][R][S] -> the MFMA operand order of the packed-filter window kernels:
+// out[row block rb][16-channel group c16][tap t][half g][row m][8 channels j] = filt[rb*32 + m][c16*16 + g*8 + j][t],
+// zero for rows past K.  One thread writes one 16-byte vector (the 8 channels one lane feeds to a 32x32x16 MFMA).
+__global__ __launch_bounds__(256) void pack_filters16_kernel(const uint16_t* __restrict__ filt, uint4* __restrict__ out, int K,
+                                                            int C, int RS, int nvec)
+{
+    const int v = blockIdx.x * 256 + threadIdx.x;
+    if (v >= nvec) return;
+    const int m = v & 31, g = (v >> 5) & 1;
+    int rest = v >> 6;
+    const int t = rest % RS;
+    rest /= RS;
+    const int C16 = C >> 4, c16 = rest % C16, rb = rest / C16;
+    const int k = rb * 32 + m, c = c16 * 16 + g * 8;
+    uint32_t w[4] = {0, 0, 0, 0};
+    if (k < K) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const uint32_t h = filt[((size_t)k * C + c + j) * RS + t];
+            w[j >> 1] |= h << ((j & 1) * 16);
+        }
+    }
+    out[v] = make_uint4(w[0], w[1], w[2], w[3]);
+}
+
+hipError_t launch_pack_filters16(const void* filt, void* out, int K, int C, int RS, hipStream_t s)
+{
+    const long long nvec = (long long)((K + 31) / 32) * 32 * (C / 16) * RS * 2;
+    hipLaunchKernelGGL(pack_filters16_kernel, dim3((unsigned)((nvec + 255) / 256)), dim3(256), 0, s, (const uint16_t*)filt,
+                       (uint4*)out, K, C, RS, (int)nvec);
+    return hipGetLastError();
+}
+
 hipError_t launch_transpose(int A, int B, int S, int esize, const void* in, void* out, hipStream_t s)
 {
     dim3 grid((unsigned)((S + 31) / 32), (unsigned)((B + 31) / 32), (unsigned)A);

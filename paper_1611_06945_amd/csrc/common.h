@@ -116,7 +116,8 @@ enum { TRAIT_SCALAR_LOADS = 1u,  // filter tile fetched element by element (no a
        TRAIT_STRIDED_VECTOR = 16u,    // gathers four input columns per load on stride-4 layers
        TRAIT_PLANAR_TO_NHWC = 32u,    // reads [N][C][H][W] and [K][C][R][S], can write [N][OH][OW][K] (CONV_FLAG_OUT_NHWC alone)
        TRAIT_FILTERS_IN_KERNEL = 64u,  // Winograd: the filter transform runs inside the product kernel
-       TRAIT_POOL_EPILOGUE = 128u };   // can max-pool its output tile before the store (CONV_FLAG_MAXPOOL_3X3S2)
+       TRAIT_POOL_EPILOGUE = 128u,     // can max-pool its output tile before the store (CONV_FLAG_MAXPOOL_3X3S2)
+       TRAIT_PACKED_FILTERS = 256u };  // reads filters in MFMA operand order (CONV_FLAG_FILT_PACKED); checks the tensor formats itself
 
 enum { FAM_IGEMM = 0, FAM_POINTWISE = 1, FAM_FIRSTLAYER = 2, FAM_WINDOW = 3, FAM_FC = 4, FAM_NHWC = 5, FAM_WINOGRAD = 6 };
 
@@ -138,6 +139,8 @@ void register_wconv_f32(std::vector<Variant>& out);
 void register_wconv_f16(std::vector<Variant>& out);
 void register_wconv_bf16(std::vector<Variant>& out);
 void register_wino_f32(std::vector<Variant>& out);
+void register_pwin_f16(std::vector<Variant>& out);
+void register_pwin_bf16(std::vector<Variant>& out);
 
 // Raises a kernel's dynamic-LDS limit to `bytes` on the current device when it is not already that high (once per
 // device and kernel; safe to call from several threads).
@@ -152,6 +155,8 @@ hipError_t launch_transpose(int A, int B, int S, int esize, const void* in, void
 // Winograd filter transform in the layout of the 8-channel-step variants (wino_f32.hip); bytes = 16 * K' * C * 4
 hipError_t launch_wino_filter_transform(const float* filt, float* out, int K, int C, hipStream_t s);
 size_t wino_transformed_filter_bytes(int K, int C);
+// KCRS 16-bit filters -> MFMA operand order of the packed-filter kernels (aux_kernels.hip); C % 16 == 0
+hipError_t launch_pack_filters16(const void* filt, void* out, int K, int C, int RS, hipStream_t s);
 
 // Device ceilings measured in place (probe_kernels.hip).
 hipError_t probe_mfma(int dtype, int block, float* sink, hipStream_t s, double* tflops);

@@ -1,0 +1,21 @@
+// bf16-storage instantiations of the packed-filter window kernel (stride-1 layers, channel-innermost input).
+#include "pwin_kernel.h"
+
+namespace convfwd {
+
+//                                     DT       R  S  KW WN TMB NBW AD LBT
+#define PW(R, S, KW, WN, TMB, NBW, AD, LBT) PwinCfg<CONV_BF16, R, S, KW, WN, TMB, NBW, AD, LBT>
+
+void register_pwin_bf16(std::vector<Variant>& out)
+{
+    // 3x3
+    pwin_register<PW(3, 3, 4, 1, 2, 3, 9, 6)>(out);  // M64 N96  C64, 4 waves: 64x96 wave tiles, 192 slab positions
+    pwin_register<PW(3, 3, 4, 1, 2, 2, 9, 5)>(out);  // M64 N64  C64, 4 waves
+    pwin_register<PW(3, 3, 4, 2, 2, 3, 9, 5)>(out);  // M64 N192 C64, 8 waves
+    pwin_register<PW(3, 3, 2, 2, 2, 3, 9, 8)>(out);  // M64 N192 C32, 4 waves
+    // 5x5
+    pwin_register<PW(5, 5, 2, 2, 2, 4, 5, 9)>(out);  // M64 N256 C32, 4 waves: 64x128 wave tiles, 576 slab positions
+    pwin_register<PW(5, 5, 2, 2, 2, 3, 5, 8)>(out);  // M64 N192 C32, 4 waves
+}
+
+}  // namespace convfwd
