@@ -257,13 +257,19 @@ int conv_transform_filters(const conv_desc* desc, const void* filt, void* out, v
 
 /*
  * Measured ceilings of the device, for reporting next to the published peaks (the paper's own practice of timing on
- * the device with device-level timers, Section 4 "Experimental Setup").  Both synchronise `stream`.
+ * the device with device-level timers, Section 4 "Experimental Setup").  All synchronise `stream`.
  *  - conv_probe_mfma_peak: TFLOP/s of a register-only MFMA issue loop for `dtype` with 16x16 or 32x32 blocks
  *    (`block` = 16 or 32); `scratch` is any 4-byte device location (never written in practice).
  *  - conv_probe_stream_bandwidth: GB/s (bytes read + bytes written) of a plain copy of `bytes` from `src` to `dst`,
  *    both device pointers, 16-byte aligned, not overlapping.
+ *  - conv_probe_mfma_mix: the same issue loop with exactly `waves_per_simd` (1..4) waves on every SIMD and
+ *    `valu_per_mfma` (0, 2, 4 or 8) vector-ALU instructions between consecutive MFMAs: how much of the issue rate a
+ *    given occupancy reaches, and whether vector-ALU work hides behind matrix work.  Writes TFLOP/s and the
+ *    nanoseconds one SIMD spends per MFMA.
  */
 int conv_probe_mfma_peak(int32_t dtype, int32_t block, void* scratch, void* stream, double* tflops);
+int conv_probe_mfma_mix(int32_t dtype, int32_t block, int32_t waves_per_simd, int32_t valu_per_mfma, void* scratch,
+                        void* stream, double* tflops, double* ns_per_mfma);
 int conv_probe_stream_bandwidth(const void* src, void* dst, size_t bytes, void* stream, double* gbytes_per_s);
 
 /* Text for a conv_status; for CONV_EHIP it includes the message of the last failed HIP call of this thread. */

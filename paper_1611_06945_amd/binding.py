@@ -102,6 +102,9 @@ def lib() -> ctypes.CDLL:
         L.conv_convert_layout.restype = ctypes.c_int
         L.conv_probe_mfma_peak.argtypes = [ctypes.c_int32, ctypes.c_int32, vp, vp, ctypes.POINTER(ctypes.c_double)]
         L.conv_probe_mfma_peak.restype = ctypes.c_int
+        L.conv_probe_mfma_mix.argtypes = [ctypes.c_int32] * 4 + [vp, vp, ctypes.POINTER(ctypes.c_double),
+                                          ctypes.POINTER(ctypes.c_double)]
+        L.conv_probe_mfma_mix.restype = ctypes.c_int
         L.conv_probe_stream_bandwidth.argtypes = [vp, vp, ctypes.c_size_t, vp, ctypes.POINTER(ctypes.c_double)]
         L.conv_probe_stream_bandwidth.restype = ctypes.c_int
         L.conv_transformed_filter_bytes.argtypes = [dp]
@@ -271,6 +274,14 @@ def conv_probe_mfma_peak(dtype: int, block: int, scratch, stream=None) -> float:
     v = ctypes.c_double()
     _check(lib().conv_probe_mfma_peak(dtype, block, _ptr(scratch), _stream(stream), ctypes.byref(v)), "conv_probe_mfma_peak")
     return v.value
+
+
+def conv_probe_mfma_mix(dtype: int, block: int, waves_per_simd: int, valu_per_mfma: int, scratch, stream=None):
+    """(TFLOP/s, nanoseconds per MFMA and SIMD) of the issue loop at a fixed occupancy with interleaved vector-ALU work."""
+    t, ns = ctypes.c_double(), ctypes.c_double()
+    _check(lib().conv_probe_mfma_mix(dtype, block, waves_per_simd, valu_per_mfma, _ptr(scratch), _stream(stream),
+                                     ctypes.byref(t), ctypes.byref(ns)), "conv_probe_mfma_mix")
+    return t.value, ns.value
 
 
 def conv_probe_stream_bandwidth(src, dst, nbytes: int, stream=None) -> float:

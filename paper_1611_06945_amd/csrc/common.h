@@ -160,6 +160,7 @@ hipError_t launch_pack_filters16(const void* filt, void* out, int K, int C, int 
 
 // Device ceilings measured in place (probe_kernels.hip).
 hipError_t probe_mfma(int dtype, int block, float* sink, hipStream_t s, double* tflops);
+hipError_t probe_mfma_mix(int dtype, int block, int wps, int nv, float* sink, hipStream_t s, double* tflops, double* ns);
 hipError_t probe_copy(const void* src, void* dst, size_t bytes, hipStream_t s, double* gbs);
 
 inline const char* dtype_name(int dt) { return dt == CONV_F32 ? "f32" : dt == CONV_F16 ? "f16" : "bf16"; }

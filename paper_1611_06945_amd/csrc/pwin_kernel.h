@@ -30,6 +30,10 @@
 
 #include "igemm_kernel.h"
 
+#ifndef PWIN_EXP
+#define PWIN_EXP 0
+#endif
+
 namespace convfwd {
 
 template <int DT_, int R_, int S_, int KW_, int WN_, int TMB_, int NBW_, int AD_, int LBT_>
@@ -47,11 +51,13 @@ struct PwinCfg {
     static constexpr int CP = CB + 8;         // channel pitch of one slab position (16-bit elements)
     static constexpr int SLOTS = LBT * NT / CV;  // slab positions one buffer holds: every thread stages LBT vectors
     static constexpr int SLAB_ELEMS = SLOTS * CP;
-    static constexpr int RP = TNP + 1;        // row pitch of the reduction buffer (odd: reads along either axis spread over the banks)
-    // rows of the output tile summed per pass through LDS: all of them when the KW partial tiles fit, else 32
-    static constexpr int RB = ((size_t)KW * TM * RP * 4 <= 160 * 1024) ? TM : 32;
+    // Reduction buffer [KW][pixel][RBP]: the rows (channels) of one pixel are contiguous, so an accumulator's four
+    // consecutive rows go out as one 16-byte LDS write and come back as 16-byte reads; RBP = RB + 4 floats makes the
+    // pixel pitch = 4 banks (mod 64): 16 lanes cover all banks.  RB = rows summed per pass: all when that fits, else 32.
+    static constexpr int RB = ((size_t)KW * TNP * (TM + 4) * 4 <= 160 * 1024) ? TM : 32;
+    static constexpr int RBP = RB + 4;
     static constexpr size_t LDS_PIPE = 2 * sizeof(uint16_t) * (size_t)SLAB_ELEMS;
-    static constexpr size_t LDS_RED = sizeof(float) * (size_t)KW * RB * RP;
+    static constexpr size_t LDS_RED = sizeof(float) * (size_t)KW * TNP * RBP;
     static constexpr size_t LDS_BYTES = LDS_PIPE > LDS_RED ? LDS_PIPE : LDS_RED;
     static_assert(LDS_BYTES <= 160 * 1024, "LDS budget");
 };
@@ -101,7 +107,7 @@ __global__ __launch_bounds__(CFG::NT) void pwin_kernel(ConvArgs a)
     typedef uint16_t elem_t;
     constexpr int DT = CFG::DT, R = CFG::R, S = CFG::S, RS = CFG::RS, KW = CFG::KW, WN = CFG::WN, TMB = CFG::TMB;
     constexpr int NBW = CFG::NBW, AD = CFG::AD, LBT = CFG::LBT, NT = CFG::NT, CB = CFG::CB, CV = CFG::CV, TM = CFG::TM;
-    constexpr int TNP = CFG::TNP, CP = CFG::CP, SLAB_ELEMS = CFG::SLAB_ELEMS, RP = CFG::RP, RB = CFG::RB;
+    constexpr int TNP = CFG::TNP, CP = CFG::CP, SLAB_ELEMS = CFG::SLAB_ELEMS, RBP = CFG::RBP, RB = CFG::RB;
     typedef Mma<DT, 32> mma_t;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
     elem_t* const Bs0 = (elem_t*)smem_raw;  // [2][SLOTS][CP]
@@ -110,6 +116,10 @@ __global__ __launch_bounds__(CFG::NT) void pwin_kernel(ConvArgs a)
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int kw = wave % KW, wn = wave / KW;
     const int li = lane & 31, g = lane >> 5;
+#if PWIN_EXP & 16
+    unsigned long long* const tstamp = (unsigned long long*)a.ws + (size_t)blockIdx.x * 8;
+    if (tid == 0 && a.ws) tstamp[0] = wall_clock64();
+#endif
 
     // ---- which tile: ids b, b+8, b+16, ... run on one XCD; give each XCD a contiguous run of logical tiles ---------
     const int PT = (int)a.dX.d, PWs = a.W + a.pad, PHs = a.H + a.pad;
@@ -138,6 +148,23 @@ __global__ __launch_bounds__(CFG::NT) void pwin_kernel(ConvArgs a)
 
     const __amdgpu_buffer_rsrc_t rin = make_rsrc(a.in, a.in_bytes);
     const __amdgpu_buffer_rsrc_t rfilt = make_rsrc(a.filt, a.filt_bytes);
+
+    // ---- filter fragments: ring of AD taps, each TMB fragments of 1 KB loaded straight from the packed tensor ------
+    // (the first AD taps are requested before anything else: their latency covers the index arithmetic below)
+    const int C16 = a.C >> 4;
+    const uint32_t a_lane = (uint32_t)lane * 16u;
+    const uint32_t a_mb_stride = (uint32_t)C16 * RS * 1024u;
+    uint32_t a_soff = (uint32_t)((mt_u * TMB) * C16 + kw) * (RS * 1024u);  // chunk 0, tap 0, block 0 of this wave
+    uint4 ar[AD][TMB];
+    auto load_a = [&](auto slot_c, uint32_t soff) {
+        constexpr int slot = decltype(slot_c)::value;
+#pragma unroll
+        for (int mb = 0; mb < TMB; ++mb) {
+            const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rfilt, (int)a_lane, (int)(soff + (uint32_t)mb * a_mb_stride), 0);
+            ar[slot][mb] = make_uint4(v.x, v.y, v.z, v.w);
+        }
+    };
+    static_for<AD>([&](auto ic) { load_a(ic, a_soff + (uint32_t)decltype(ic)::value * 1024u); });
 
     // ---- staging plan of the slab (the same for every chunk: only the channel offset moves) ------------------------
     // task t = (slab position t / CV, 16-byte vector t % CV of the chunk's channels)
@@ -176,21 +203,6 @@ __global__ __launch_bounds__(CFG::NT) void pwin_kernel(ConvArgs a)
     }
     const int rowoff = PWs * CP;
 
-    // ---- filter fragments: ring of AD taps, each TMB fragments of 1 KB loaded straight from the packed tensor ------
-    const int C16 = a.C >> 4;
-    const uint32_t a_lane = (uint32_t)lane * 16u;
-    const uint32_t a_mb_stride = (uint32_t)C16 * RS * 1024u;
-    uint32_t a_soff = (uint32_t)((mt_u * TMB) * C16 + kw) * (RS * 1024u);  // chunk 0, tap 0, block 0 of this wave
-    uint4 ar[AD][TMB];
-    auto load_a = [&](auto slot_c, uint32_t soff) {
-        constexpr int slot = decltype(slot_c)::value;
-#pragma unroll
-        for (int mb = 0; mb < TMB; ++mb) {
-            const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rfilt, (int)a_lane, (int)(soff + (uint32_t)mb * a_mb_stride), 0);
-            ar[slot][mb] = make_uint4(v.x, v.y, v.z, v.w);
-        }
-    };
-
     typename mma_t::acc_t acc[TMB][NBW];
 #pragma unroll
     for (int mb = 0; mb < TMB; ++mb)
@@ -202,12 +214,14 @@ __global__ __launch_bounds__(CFG::NT) void pwin_kernel(ConvArgs a)
     const int nchunks = a.C / CB;
 
     // ---- prologue ---------------------------------------------------------------------------------------------------
-    static_for<AD>([&](auto ic) { load_a(ic, a_soff + (uint32_t)decltype(ic)::value * 1024u); });
     load_slab(0);
     store_slab(0);
-    load_slab(1);  // unconditional: past the last chunk the data is never used
+    load_slab(1);  // unconditional: with a single chunk the data is never used
     __syncthreads();
 
+#if PWIN_EXP & 16
+    if (tid == 0 && a.ws) tstamp[1] = wall_clock64();
+#endif
     uint4 bf[2][NBW];
     auto read_tap = [&](const elem_t* Bs, int r, int s, int set) {
         const int toff = r * rowoff + s * CP;
@@ -219,36 +233,44 @@ __global__ __launch_bounds__(CFG::NT) void pwin_kernel(ConvArgs a)
     constexpr int TSTORE = RS / 2;  // tap after which the next chunk's slab goes to LDS
     constexpr uint32_t kChunkStep = (uint32_t)KW * RS * 1024u;
     int buf = 0;
-    for (int chunk = 0; chunk < nchunks; ++chunk) {
+    // One chunk.  STORE: another chunk follows (its slab is written to the other buffer at tap TSTORE, and the barrier
+    // before the last tap publishes it); LOAD: a chunk follows that one (its slab is requested); the last chunk does
+    // neither and requests no filter fragments past its own taps.  The three forms are separate straight-line code: a
+    // load under a condition would make every later wait assume it was skipped and wait for too much.
+    auto do_chunk = [&](auto store_c, auto load_c, int chunk) {
+        constexpr bool STORE = decltype(store_c)::value, LOAD = decltype(load_c)::value;
         const elem_t* Bs = Bs0 + buf * SLAB_ELEMS;
         const elem_t* Bn = Bs0 + (buf ^ 1) * SLAB_ELEMS;
         static_for<RS>([&](auto tc) {
-                {
-                    constexpr int t = decltype(tc)::value, cur = t & 1, slot = t % AD;
-                    if constexpr (t + 1 < RS) {
-                        read_tap(Bs, (t + 1) / S, (t + 1) % S, cur ^ 1);
-                    } else {
-                        // every wave holds its operands of the chunk's last tap in registers: the other buffer (stored
-                        // at tap TSTORE by everyone) becomes readable, and this one may be overwritten from the next
-                        // chunk's tap TSTORE on
-                        __syncthreads();
-                        read_tap(Bn, 0, 0, cur ^ 1);
-                    }
-                    __builtin_amdgcn_sched_barrier(0);
+            constexpr int t = decltype(tc)::value, cur = t & 1, slot = t % AD;
+            if constexpr (t + 1 < RS) {
+                if constexpr (!(PWIN_EXP & 4)) read_tap(Bs, (t + 1) / S, (t + 1) % S, cur ^ 1);
+            } else if constexpr (STORE) {
+                // every wave holds its operands of the chunk's last tap in registers: the other buffer (stored at tap
+                // TSTORE by everyone) becomes readable, and this one may be overwritten from the next chunk's tap
+                // TSTORE on
+                if constexpr (!(PWIN_EXP & 8)) __syncthreads();
+                if constexpr (!(PWIN_EXP & 4)) read_tap(Bn, 0, 0, cur ^ 1);
+            } else {
+                // last tap of the last chunk: once every wave holds its last operands the slabs are dead, and the
+                // reduction buffer that overlays them may be written
+                __syncthreads();
+            }
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                    for (int mb = 0; mb < TMB; ++mb)
+            for (int mb = 0; mb < TMB; ++mb)
 #pragma unroll
-                        for (int nb = 0; nb < NBW; ++nb) acc[mb][nb] = mma_t::run(ar[slot][mb], bf[cur][nb], acc[mb][nb]);
-                    // the slot is free once its MFMAs are issued: fetch the fragments of the tap AD ahead
-                    constexpr int ta = t + AD;
-                    load_a(std::integral_constant<int, slot>{},
-                           a_soff + (ta < RS ? (uint32_t)ta * 1024u : kChunkStep + (uint32_t)(ta - RS) * 1024u));
-                    if constexpr (t == TSTORE) {
-                        store_slab(buf ^ 1);
-                        load_slab(chunk + 2);
-                    }
-                    __builtin_amdgcn_sched_barrier(0);
-                }
+                for (int nb = 0; nb < NBW; ++nb) acc[mb][nb] = mma_t::run(ar[slot][mb], bf[cur][nb], acc[mb][nb]);
+            // the slot is free once its MFMAs are issued: fetch the fragments of the tap AD ahead
+            constexpr int ta = t + AD;
+            if constexpr (!(PWIN_EXP & 1) && (ta < RS || STORE))
+                load_a(std::integral_constant<int, slot>{},
+                       a_soff + (ta < RS ? (uint32_t)ta * 1024u : kChunkStep + (uint32_t)(ta - RS) * 1024u));
+            if constexpr (t == TSTORE && !(PWIN_EXP & 2)) {
+                if constexpr (STORE) store_slab(buf ^ 1);
+                if constexpr (LOAD) load_slab(chunk + 2);
+            }
+            __builtin_amdgcn_sched_barrier(0);
         });
         if constexpr ((RS & 1) != 0) {
 #pragma unroll
@@ -256,11 +278,20 @@ __global__ __launch_bounds__(CFG::NT) void pwin_kernel(ConvArgs a)
         }
         buf ^= 1;
         a_soff += kChunkStep;
+    };
+    {
+        int chunk = 0;
+        for (; chunk + 2 < nchunks; ++chunk) do_chunk(std::true_type{}, std::true_type{}, chunk);
+        if (chunk + 1 < nchunks) do_chunk(std::true_type{}, std::false_type{}, chunk++);
+        do_chunk(std::false_type{}, std::false_type{}, chunk);
     }
 
     // ---- add the KW channel-waves' partial sums in wave order, then bias + activation + rounding + store -----------
-    // (after the loop's last barrier no wave reads anything it uses from the slabs: the buffer can be reused at once)
-    float* const red = (float*)smem_raw;  // [KW][RB][RP]
+    // (after the barrier in the last chunk's last tap no wave reads the slabs any more: the buffer is reused at once)
+#if PWIN_EXP & 16
+    if (tid == 0 && a.ws) tstamp[2] = wall_clock64();
+#endif
+    float* const red = (float*)smem_raw;  // [KW][TNP][RBP]
     const bool onhwc = a.out_nhwc != 0;
     const __amdgpu_buffer_rsrc_t rbias = make_rsrc(a.bias, a.bias ? (uint32_t)a.K * 4u : 0u);
     const __amdgpu_buffer_rsrc_t rout = make_rsrc(a.out, a.out_bytes);
@@ -268,31 +299,51 @@ __global__ __launch_bounds__(CFG::NT) void pwin_kernel(ConvArgs a)
 #pragma unroll
     for (int rd = 0; rd < ROUNDS; ++rd) {
         if (rd > 0) __syncthreads();
+        // the bias values a thread will add (channel-innermost output: its 8 channels are the same for all its vectors)
+        // are requested before the exchange through LDS, which covers their latency
+        constexpr int CG = RB / 8;
+        static_assert(NT % CG == 0, "a thread keeps its channel group over its vectors");
+        const int cg = tid % CG;
+        const int kv = m0 + rd * RB + cg * 8;
+        const bool kok = kv < a.K;  // K % 8 == 0 with that output format: the 8 channels are in or out together
+        float bs[8];
+        if (onhwc) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) bs[i] = buffer_load_elem<float>(rbias, kok ? (uint32_t)(kv + i) * 4u : kOutOfRange);
+        }
+        // accumulator registers 4i..4i+3 of a lane are rows 8i + 4g .. + 3 of its pixel column: one 16-byte write
 #pragma unroll
         for (int mbi = 0; mbi < MBR; ++mbi)
 #pragma unroll
-            for (int nb = 0; nb < NBW; ++nb)
+            for (int nb = 0; nb < NBW; ++nb) {
+                float* dst = &red[(kw * TNP + (wn * NBW + nb) * 32 + li) * RBP + mbi * 32 + 4 * g];
 #pragma unroll
-                for (int v = 0; v < 16; ++v)
-                    red[(kw * RB + mbi * 32 + acc_row<32>(v, lane)) * RP + (wn * NBW + nb) * 32 + li] = acc[rd * MBR + mbi][nb][v];
+                for (int i = 0; i < 4; ++i) {
+                    const typename mma_t::acc_t& c = acc[rd * MBR + mbi][nb];
+                    *(f32x4*)&dst[8 * i] = f32x4{c[4 * i], c[4 * i + 1], c[4 * i + 2], c[4 * i + 3]};
+                }
+            }
         __syncthreads();
         if (onhwc) {
-            // a thread takes 8 consecutive channels of one pixel: one 16-byte store
-            constexpr int CG = RB / 8, NV = (CG * TNP + NT - 1) / NT;
+            // a thread takes 8 consecutive channels of one pixel: two 16-byte LDS reads per partial sum, one 16-byte store
+            constexpr int NV = (CG * TNP + NT - 1) / NT;
+            const int k = kv;
 #pragma unroll
             for (int j = 0; j < NV; ++j) {
                 const int e = j * NT + tid;
-                const int cg = e % CG, col = e / CG;
-                const int k = m0 + rd * RB + cg * 8, p = p0 + col;
-                const bool ok = e < CG * TNP && k < a.K && p < a.P;
-                const int idx = ok ? (cg * 8) * RP + col : 0;
+                const int col = e / CG, p = p0 + col;
+                const bool ok = e < CG * TNP && kok && p < a.P;
+                const float* src = &red[(ok ? col : 0) * RBP + cg * 8];
+                f32x4 x0 = *(const f32x4*)&src[0], x1 = *(const f32x4*)&src[4];
+#pragma unroll
+                for (int q = 1; q < KW; ++q) {
+                    x0 += *(const f32x4*)&src[q * TNP * RBP];
+                    x1 += *(const f32x4*)&src[q * TNP * RBP + 4];
+                }
                 uint32_t w[4];
 #pragma unroll
                 for (int i = 0; i < 8; ++i) {
-                    float x = red[idx + i * RP];
-#pragma unroll
-                    for (int q = 1; q < KW; ++q) x += red[q * RB * RP + idx + i * RP];
-                    x += buffer_load_elem<float>(rbias, ok ? (uint32_t)(k + i) * 4u : kOutOfRange);
+                    float x = (i < 4 ? x0[i & 3] : x1[i & 3]) + bs[i];
                     if (a.relu) x = x > 0.0f ? x : 0.0f;
                     const uint32_t h = Prec<DT>::from_f32(x);
                     if (i & 1)
@@ -304,26 +355,35 @@ __global__ __launch_bounds__(CFG::NT) void pwin_kernel(ConvArgs a)
                 __builtin_amdgcn_raw_buffer_store_b128(vv, rout, ok ? (int)((uint32_t)(p * a.K + k) * 2u) : (int)kOutOfRange, 0, 0);
             }
         } else {
-            constexpr int NE = (RB * TNP + NT - 1) / NT;
+            // a thread takes 4 consecutive channels of one pixel, consecutive threads consecutive pixels: 16-byte LDS
+            // reads, four 2-byte stores that each fall into a run of consecutive pixels of one channel plane
+            constexpr int RG = RB / 4, NE = (RG * TNP + NT - 1) / NT;
 #pragma unroll
             for (int j = 0; j < NE; ++j) {
                 const int e = j * NT + tid;
-                const int row = e / TNP, col = e % TNP;
-                const int k = m0 + rd * RB + row, p = p0 + col;
-                const bool ok = e < RB * TNP && k < a.K && p < a.P;
-                const int idx = ok ? row * RP + col : 0;
-                float x = red[idx];
+                const int rg = e / TNP, col = e % TNP;
+                const int k = m0 + rd * RB + rg * 4, p = p0 + col;
+                const bool ok = e < RG * TNP && p < a.P;
+                const float* src = &red[(ok ? col : 0) * RBP + (ok ? rg : 0) * 4];
+                f32x4 x = *(const f32x4*)&src[0];
 #pragma unroll
-                for (int q = 1; q < KW; ++q) x += red[q * RB * RP + idx];
-                x += buffer_load_elem<float>(rbias, ok ? (uint32_t)k * 4u : kOutOfRange);
-                if (a.relu) x = x > 0.0f ? x : 0.0f;
+                for (int q = 1; q < KW; ++q) x += *(const f32x4*)&src[q * TNP * RBP];
                 uint32_t n, pix;
                 a.dOHW.divmod((uint32_t)(ok ? p : 0), n, pix);
-                const uint32_t o = (uint32_t)(((int)n * a.K + k) * a.OHW + (int)pix);
-                buffer_store_elem<elem_t>(Prec<DT>::from_f32(x), rout, ok ? o * 2u : kOutOfRange);
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const bool oki = ok && k + i < a.K;
+                    float y = x[i] + buffer_load_elem<float>(rbias, oki ? (uint32_t)(k + i) * 4u : kOutOfRange);
+                    if (a.relu) y = y > 0.0f ? y : 0.0f;
+                    const uint32_t o = (uint32_t)(((int)n * a.K + k + i) * a.OHW + (int)pix);
+                    buffer_store_elem<elem_t>(Prec<DT>::from_f32(y), rout, oki ? o * 2u : kOutOfRange);
+                }
             }
         }
     }
+#if PWIN_EXP & 16
+    if (tid == 0 && a.ws) tstamp[3] = wall_clock64();
+#endif
 }
 
 // bytes of the packed filter tensor: K rounded up to whole 32-row blocks
