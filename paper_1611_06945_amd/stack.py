@@ -13,8 +13,10 @@ kernel (fp16/bf16, C % 8 == 0, K % 8 == 0) is timed in both formats, the
 conversions are timed, and the cheapest assignment over the whole chain is found
 by dynamic programming.  A max-pool between two layers converts for free (it reads
 one layout and writes the other); elsewhere an explicit conversion is inserted.
-Filters of channel-innermost layers are repacked once in `prepare()`.  The
-stack's input and final output are always [N][C][H][W].
+Filters of channel-innermost layers are repacked once in `prepare()`: either
+[K][R][S][C], or the matrix-instruction operand order of the packed-filter
+kernels ("nhwc_packed"), whichever measures faster for the layer.  The stack's
+input and final output are always [N][C][H][W].
 
 Where a max-pool follows a layer whose kernels can pool their own output tile
 (CONV_FLAG_MAXPOOL_3X3S2: the paper's fusion rule applied to the pooling
@@ -29,6 +31,8 @@ from . import binding as B
 from .workloads import ConvShape
 
 NCHW, NHWC = "nchw", "nhwc"
+NHWC_PACKED = "nhwc_packed"   # a layer format: channel-innermost activations, filters in MFMA operand order
+KCRS, KRSC, PACKED = "kcrs", "krsc", "packed"
 
 
 class ConvStack:
@@ -36,7 +40,8 @@ class ConvStack:
                  pool_win: int = 3, pool_stride: int = 2, formats=None, fuse_pool: bool = False):
         """`pool_after` holds 1-based layer numbers that are followed by a max-pool.  `formats`: None = every layer
         in [N][C][H][W]; "auto" = decided by autotune(); or a list of "nchw"/"nhwc", one per layer.  `fuse_pool`: pool
-        inside the convolution wherever a kernel can (with "auto" the timings decide instead)."""
+        inside the convolution wherever a kernel can (with "auto" the timings decide instead).  A list entry may also be
+        "nhwc_packed": channel-innermost activations with the filters in MFMA operand order."""
         import torch
 
         self.torch = torch
@@ -53,12 +58,16 @@ class ConvStack:
             if tuple(got) != tuple(want):
                 raise ValueError("layer %d produces %s but layer %d expects %s" % (i + 1, tuple(got), i + 2, want))
         self.auto = formats == "auto"
-        self.formats = [NCHW] * n if formats in (None, "auto") else list(formats)
-        if len(self.formats) != n or any(f not in (NCHW, NHWC) for f in self.formats):
-            raise ValueError("formats must name nchw or nhwc for each of the %d layers" % n)
+        given = [NCHW] * n if formats in (None, "auto") else list(formats)
+        if len(given) != n or any(f not in (NCHW, NHWC, NHWC_PACKED) for f in given):
+            raise ValueError("formats must name nchw, nhwc or nhwc_packed for each of the %d layers" % n)
+        self.formats = [NHWC if f == NHWC_PACKED else f for f in given]                     # activation layout per layer
+        self.filt_formats = [{NCHW: KCRS, NHWC: KRSC, NHWC_PACKED: PACKED}[f] for f in given]  # filter format per layer
         for i, f in enumerate(self.formats):
             if f == NHWC and not self.nhwc_capable(i):
                 raise ValueError("layer %d has no channel-innermost kernel" % (i + 1))
+            if self.filt_formats[i] == PACKED and not self.packed_capable(i):
+                raise ValueError("layer %d has no packed-filter kernel" % (i + 1))
         self.packed_filts: List[Optional[object]] = [None] * n
         self.plan_times = None
         self.out_layouts = None   # set by the format selection: the output layout it timed and chose per layer
@@ -69,6 +78,14 @@ class ConvStack:
     def nhwc_capable(self, i: int) -> bool:
         s = self.shapes[i]
         return self.dtype != B.CONV_F32 and s.C % 8 == 0 and s.K % 8 == 0
+
+    def packed_capable(self, i: int) -> bool:
+        d = B.desc_of(self.shapes[i], self.dtype, relu=self.relu, in_nhwc=True, filt_packed=True)
+        return self.dtype != B.CONV_F32 and B.conv_variant_count(d) > 0
+
+    def _desc(self, i: int, fmt: str, filt_fmt: str, out_nhwc: bool, maxpool: bool = False):
+        return B.desc_of(self.shapes[i], self.dtype, relu=self.relu, in_nhwc=fmt == NHWC, out_nhwc=out_nhwc,
+                         filt_krsc=filt_fmt == KRSC, filt_packed=filt_fmt == PACKED, maxpool=maxpool)
 
     def _pooled_shape(self, i: int):
         s = self.shapes[i]
@@ -93,8 +110,7 @@ class ConvStack:
             return False
         if fmt == NCHW and out_layout == NHWC:
             return False
-        d = B.desc_of(self.shapes[i], self.dtype, relu=self.relu, in_nhwc=fmt == NHWC, out_nhwc=out_layout == NHWC,
-                      filt_krsc=fmt == NHWC, maxpool=True)
+        d = self._desc(i, fmt, KRSC if fmt == NHWC else KCRS, out_layout == NHWC, maxpool=True)
         return B.conv_variant_count(d) > 0
 
     def _conv_out_layout(self, i: int) -> str:
@@ -115,10 +131,10 @@ class ConvStack:
         self.descs, self.conv_out, self.pool_out, self.conv_layout, self.convert_out = [], [], [], [], []
         ws_bytes = 256
         for i, s in enumerate(self.shapes):
-            nh = self.formats[i] == NHWC
             lay = self._conv_out_layout(i)
-            d = B.desc_of(s, self.dtype, relu=self.relu, in_nhwc=nh, out_nhwc=(lay == NHWC), filt_krsc=nh,
-                          maxpool=self.fused[i])
+            if self.fused[i] and self.filt_formats[i] == PACKED:
+                self.filt_formats[i] = KRSC   # only the [K][R][S][C] kernels pool their own tile
+            d = self._desc(i, self.formats[i], self.filt_formats[i], lay == NHWC, maxpool=self.fused[i])
             self.descs.append(d)
             self.conv_layout.append(lay)
             # buffers are flat in memory; the shape recorded here is the logical [N][K][OH][OW] one
@@ -144,16 +160,21 @@ class ConvStack:
 
     # ---- one-time preparation ----------------------------------------------------------------------------------------
     def prepare(self, filts, stream=None) -> None:
-        """Repack the filters of channel-innermost layers ([K][C][R][S] -> [K][R][S][C]); done once, not per run."""
+        """Repack the filters of channel-innermost layers ([K][C][R][S] -> [K][R][S][C], or -> MFMA operand order); done
+        once, not per run."""
         for i, s in enumerate(self.shapes):
-            if self.formats[i] == NHWC:
+            if self.filt_formats[i] == KRSC:
                 self.packed_filts[i] = self.torch.empty_like(filts[i])
                 B.conv_convert_layout(s.K, s.C, s.R * s.S, self.dtype, filts[i], self.packed_filts[i], stream)
+            elif self.filt_formats[i] == PACKED:
+                nbytes = B.conv_transformed_filter_bytes(self.descs[i])
+                self.packed_filts[i] = self.torch.empty(nbytes // 2, dtype=self.torch.int16, device="cuda")
+                B.conv_transform_filters(self.descs[i], filts[i], self.packed_filts[i], stream)
             else:
                 self.packed_filts[i] = None
 
     def _filt(self, i: int, filts):
-        if self.formats[i] == NHWC:
+        if self.filt_formats[i] != KCRS:
             if self.packed_filts[i] is None:
                 raise RuntimeError("prepare(filts) must run before a stack with channel-innermost layers")
             return self.packed_filts[i]
@@ -222,7 +243,8 @@ class ConvStack:
     # ---- format selection --------------------------------------------------------------------------------------------
     def _time_op(self, fn, reps: int = 20) -> float:
         """Microseconds per call of a pool or conversion on the device.  The calls are recorded into a HIP graph and the
-        replay is timed: enqueued one by one from Python they would take longer to issue than to run."""
+        replay is timed: enqueued one by one from Python they would take longer to issue than to run.  `fn` must issue
+        on the current stream (stream=None): that is the stream the capture records."""
         torch = self.torch
         fn()
         torch.cuda.synchronize()
@@ -237,14 +259,18 @@ class ConvStack:
         graph.replay()
         e1.record()
         e1.synchronize()
-        return e0.elapsed_time(e1) * 1e3 / reps
+        us = e0.elapsed_time(e1) * 1e3 / reps
+        if not us > 0.0:
+            raise RuntimeError("timed an empty graph: the operation was not issued on the capturing stream")
+        return us
 
     def _choose_formats(self, x, filts, biases, stream) -> None:
         """Time each layer in each format (its best variant), each conversion and each pool, then pick per layer by
         dynamic programming over the chain, on scratch tensors filled with random values."""
         torch = self.torch
         n = len(self.shapes)
-        conv_t = [{} for _ in range(n)]      # (format, out layout) -> microseconds
+        conv_t = [{} for _ in range(n)]      # (format, out layout) -> microseconds (the faster filter format)
+        filt_pick = [{} for _ in range(n)]   # (format, out layout) -> the filter format that gave it
         fused_t = [{} for _ in range(n)]     # (format, pooled-output layout) -> microseconds of convolution + fused pool
         glue_t = [{} for _ in range(n)]      # (conv out layout, handoff layout) -> microseconds of pool / conversion
         for i, s in enumerate(self.shapes):
@@ -253,20 +279,30 @@ class ConvStack:
             f = (torch.randn(s.filt_shape(), device="cuda") * (2.0 / (s.C * s.R * s.S)) ** 0.5).to(self.tdt)
             out = torch.empty(s.out_shape(), dtype=self.tdt, device="cuda")
             for fmt in ((NCHW, NHWC) if self.nhwc_capable(i) else (NCHW,)):
+                ffmts = (KCRS,) if fmt == NCHW else ((KRSC, PACKED) if self.packed_capable(i) else (KRSC,))
                 for olay in ((NCHW, NHWC) if fmt == NHWC or self.planar_writes_nhwc(i) else (NCHW,)):
-                    d = B.desc_of(s, self.dtype, relu=self.relu, in_nhwc=fmt == NHWC, out_nhwc=olay == NHWC,
-                                  filt_krsc=fmt == NHWC)
-                    ws = torch.empty(max(256, B.conv_workspace_bytes(d)), dtype=torch.uint8, device="cuda")
-                    B.conv_autotune(d, xin, f, biases[i], out, ws, ws.numel(), stream)
-                    conv_t[i][(fmt, olay)] = B.conv_time_us(d, xin, f, biases[i], out, ws, ws.numel(), stream, launches=20)
+                    for ff in ffmts:
+                        d = self._desc(i, fmt, ff, olay == NHWC)
+                        if B.conv_variant_count(d) == 0:
+                            continue
+                        # timing only: the kernels' run time does not depend on which filter values sit where
+                        fbuf = f if ff != PACKED else torch.zeros(B.conv_transformed_filter_bytes(d) // 2, dtype=torch.int16,
+                                                                  device="cuda")
+                        if ff == PACKED:
+                            B.conv_transform_filters(d, f, fbuf, stream)
+                        ws = torch.empty(max(256, B.conv_workspace_bytes(d)), dtype=torch.uint8, device="cuda")
+                        B.conv_autotune(d, xin, fbuf, biases[i], out, ws, ws.numel(), stream)
+                        t = B.conv_time_us(d, xin, fbuf, biases[i], out, ws, ws.numel(), stream, launches=20)
+                        if t < conv_t[i].get((fmt, olay), float("inf")):
+                            conv_t[i][(fmt, olay)] = t
+                            filt_pick[i][(fmt, olay)] = ff
             pooled = (i + 1) in self.pool_after
             dst = torch.empty(self._pooled_shape(i) if pooled else s.out_shape(), dtype=self.tdt, device="cuda")
             for fmt in ((NCHW, NHWC) if self.nhwc_capable(i) else (NCHW,)):
                 for olay in (NCHW, NHWC):
                     if not self.can_fuse_pool(i, fmt, olay):
                         continue
-                    d = B.desc_of(s, self.dtype, relu=self.relu, in_nhwc=fmt == NHWC, out_nhwc=olay == NHWC,
-                                  filt_krsc=fmt == NHWC, maxpool=True)
+                    d = self._desc(i, fmt, KRSC if fmt == NHWC else KCRS, olay == NHWC, maxpool=True)
                     ws = torch.empty(max(256, B.conv_workspace_bytes(d)), dtype=torch.uint8, device="cuda")
                     B.conv_autotune(d, xin, f, biases[i], dst, ws, ws.numel(), stream)
                     fused_t[i][(fmt, olay)] = B.conv_time_us(d, xin, f, biases[i], dst, ws, ws.numel(), stream, launches=20)
@@ -274,16 +310,16 @@ class ConvStack:
                 for b in (NCHW, NHWC):
                     if pooled:
                         glue_t[i][(a, b)] = self._time_op(lambda: B.maxpool_fwd_layout(
-                            s.N, s.K, s.OH, s.OW, self.pool_win, self.pool_stride, self.dtype, a == NHWC, b == NHWC, out, dst,
-                            stream))
+                            s.N, s.K, s.OH, s.OW, self.pool_win, self.pool_stride, self.dtype, a == NHWC, b == NHWC, out, dst))
                     elif a == b:
                         glue_t[i][(a, b)] = 0.0
                     else:
                         dims = (s.N, s.K, s.OH * s.OW) if a == NCHW else (s.N, s.OH * s.OW, s.K)
-                        glue_t[i][(a, b)] = self._time_op(lambda: B.conv_convert_layout(*dims, self.dtype, out, dst, stream))
+                        glue_t[i][(a, b)] = self._time_op(lambda: B.conv_convert_layout(*dims, self.dtype, out, dst))
         s0 = self.shapes[0]
+        x_scratch = torch.empty_like(x)
         x_cvt = self._time_op(lambda: B.conv_convert_layout(
-            s0.N, s0.C, s0.H * s0.W, self.dtype, x, torch.empty_like(x), stream)) if self.nhwc_capable(0) else float("inf")
+            s0.N, s0.C, s0.H * s0.W, self.dtype, x, x_scratch)) if self.nhwc_capable(0) else float("inf")
         # best[i][fmt] = cheapest time of layers 0..i-1 plus glue, arriving at layer i with its input in layout fmt
         best = [{NCHW: 0.0, NHWC: x_cvt}]
         back = []
@@ -313,4 +349,6 @@ class ConvStack:
         self.formats = chosen
         self.out_layouts = olays
         self.fused = fused
+        self.filt_formats = [(KRSC if chosen[i] == NHWC else KCRS) if fused[i] else filt_pick[i][(chosen[i], olays[i])]
+                             for i in range(n)]
         self._build()

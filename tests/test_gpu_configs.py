@@ -146,7 +146,8 @@ def _stack_on_device(dtype, batch, **kw):
     return stack, shapes, gen, x, filts, biases
 
 
-@pytest.mark.parametrize("formats", [["nchw", "nhwc", "nchw", "nhwc", "nhwc"], "auto"])
+@pytest.mark.parametrize("formats", [["nchw", "nhwc", "nchw", "nhwc", "nhwc"],
+                                     ["nchw", "nhwc_packed", "nhwc_packed", "nhwc", "nhwc_packed"], "auto"])
 @pytest.mark.parametrize("dtype", [wl.F16, wl.BF16])
 def test_config5_stack_with_format_selection(dtype, formats):
     # the same five layers with channel-innermost formats where chosen: conversions by the pools, one explicit
@@ -154,15 +155,35 @@ def test_config5_stack_with_format_selection(dtype, formats):
     torch = torch_mod()
     stack, shapes, gen, x, filts, biases = _stack_on_device(dtype, 20, formats=formats)
     stack.autotune(x, filts, biases)
-    say("  formats: %s, pools fused: %s" % (stack.formats, stack.fused))
+    say("  formats: %s, filters: %s, pools fused: %s" % (stack.formats, stack.filt_formats, stack.fused))
     if formats == "auto":
         say("  planned total %.1f us" % stack.plan_times["total_us"])
     else:
-        assert stack.formats == formats and not any(stack.fused)
+        assert stack.formats == [f.split("_")[0] for f in formats] and not any(stack.fused)
+        assert stack.filt_formats == [{"nchw": "kcrs", "nhwc": "krsc", "nhwc_packed": "packed"}[f] for f in formats]
+        for f, d in zip(formats, stack.descs):
+            assert B.conv_variant_name(d, -1).startswith("pwin_") == (f == "nhwc_packed")
     assert stack.formats[0] == "nchw"  # three input channels: no channel-innermost kernel
     y = stack.run(x, filts, biases)
     torch.cuda.synchronize()
     _check_stack_against_oracle(stack, shapes, gen, dtype, y)
+
+
+def test_config5_format_selection_on_a_side_stream_times_the_glue():
+    # the planner times pools and conversions through a captured graph: they must land on the capturing stream also when
+    # the caller hands over a stream of its own (an empty graph would make every pool look free)
+    torch = torch_mod()
+    stack, shapes, gen, x, filts, biases = _stack_on_device(wl.F16, 5, formats="auto")
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    stack.autotune(x, filts, biases, stream=side)
+    side.synchronize()
+    pools = [stack.plan_times["glue_us"][i] for i in (0, 1)]
+    assert all(v > 0.5 for g in pools for v in g.values()), pools
+    y = stack.run(x, filts, biases, stream=side)
+    side.synchronize()
+    torch.cuda.synchronize()
+    _check_stack_against_oracle(stack, shapes, gen, wl.F16, y)
 
 
 @pytest.mark.parametrize("dtype", [wl.F16, wl.BF16])
