@@ -10,6 +10,12 @@ library's autotuner before timing starts.  The headline workload is the mid-netw
 sweep at batch 20 in fp32 (the paper's arithmetic); `layers` in the JSON line reports every benchmark layer at
 batch 1/5/20 and every storage type: ms, GFLOP/s and the fraction of the MFMA and HBM rooflines.
 
+Every timed output is checked after the timed region against the CPU oracle on a seeded sample of output elements
+(checker leg only; a figure whose output fails the check aborts the run).  `--format nhwc|nhwc_packed` runs the
+16-bit layers on channel-innermost tensors (with the filters in MFMA operand order for nhwc_packed): the explicit
+ahead-of-time conversions are timed separately and reported beside the layer.  `--probe` prints the device
+microbenchmarks the kernel designs rest on instead of running a workload.
+
 Prints ONE JSON line on stdout; everything else goes to stderr.
 """
 import argparse
@@ -43,31 +49,81 @@ def all_workloads():
     return ws
 
 
-class Resident:
-    """A workload with its tensors in device memory (optionally several rotating copies)."""
+TOL = {"f32": 1e-5, "f16": 5e-3, "bf16": 5e-3}   # max normalised error allowed per storage type
 
-    def __init__(self, w, copies=1):
+
+def executed_mfma_flops(variant, shape):
+    """FLOPs the matrix units execute per call: the direct count, except for the Winograd variants, which multiply
+    2.25x less (on tiles padded to the workgroup shape)."""
+    import re
+
+    m = re.match(r"wino_f32_M(\d+)T(\d+)_", variant)
+    if not m:
+        return float(shape.flops)
+    tm, tt = int(m.group(1)), int(m.group(2))
+    tiles = shape.N * ((shape.OH + 1) // 2) * ((shape.OW + 1) // 2)
+    return 2.0 * 16 * (-(-shape.K // tm) * tm) * (-(-tiles // tt) * tt) * shape.C
+
+
+class Resident:
+    """A workload with its tensors in device memory (optionally several rotating copies), in one of three formats:
+    "nchw" (the plain contract: [N][C][H][W], [K][C][R][S]), "nhwc" (channel-innermost tensors, filters [K][R][S][C]) or
+    "nhwc_packed" (channel-innermost tensors, filters in MFMA operand order).  The conversions of the latter two are
+    explicit library calls made here once, timed, and reported as `convert_us`."""
+
+    def __init__(self, w, copies=1, fmt="nchw"):
+        import numpy as np
         import torch
 
         from paper_1611_06945_amd import binding as B
         from paper_1611_06945_amd import workloads as wl
 
-        self.w, self.B, self.torch = w, B, torch
-        self.desc = B.desc_of(w.shape, w.dtype, relu=True)
-        data = w.generate()
+        self.w, self.B, self.torch, self.fmt = w, B, torch, fmt
+        s = w.shape
+        nh = fmt != "nchw"
+        self.desc = B.desc_of(s, w.dtype, relu=True, in_nhwc=nh, out_nhwc=nh, filt_krsc=fmt == "nhwc",
+                              filt_packed=fmt == "nhwc_packed")
+        if B.conv_variant_count(self.desc) <= 0:
+            raise ValueError("no kernel serves %s in format %s" % (w.name, fmt))
+        self.data = data = w.generate()
         tdt = {wl.F32: torch.float32, wl.F16: torch.float16, wl.BF16: torch.bfloat16}[w.dtype]
 
         def up(a):
             if w.dtype == wl.BF16:
-                import numpy as np
-
                 return torch.from_numpy(a.view(np.int16)).cuda().view(torch.bfloat16)
             return torch.from_numpy(a).cuda()
 
+        self.convert_us = None
+        x0, f0 = up(data["in"]), up(data["filt"])
+        if nh:
+            def timed(fn):
+                fn()
+                torch.cuda.synchronize()
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                for _ in range(20):
+                    fn()
+                e1.record()
+                e1.synchronize()
+                return round(e0.elapsed_time(e1) * 1e3 / 20, 2)
+
+            x1 = torch.empty((s.N, s.H, s.W, s.C), dtype=tdt, device="cuda")
+            t_in = timed(lambda: B.conv_convert_layout(s.N, s.C, s.H * s.W, w.dtype, x0, x1))
+            if fmt == "nhwc":
+                f1 = torch.empty((s.K, s.R, s.S, s.C), dtype=tdt, device="cuda")
+                t_f = timed(lambda: B.conv_convert_layout(s.K, s.C, s.R * s.S, w.dtype, f0, f1))
+            else:
+                f1 = torch.empty(B.conv_transformed_filter_bytes(self.desc) // 2, dtype=torch.int16, device="cuda")
+                t_f = timed(lambda: B.conv_transform_filters(self.desc, f0, f1))
+            self.convert_us = {"input_to_nhwc": t_in, "filters": t_f,
+                               "note": "explicit conversions, host-enqueued one by one (includes launch gaps); in a stack the "
+                                       "previous layer writes channel-innermost directly and filters convert once"}
+            x0, f0 = x1, f1
+        oshape = (s.N, s.OH, s.OW, s.K) if nh else s.out_shape()
         self.sets = []
         for _ in range(copies):
-            self.sets.append((up(data["in"]).clone(), up(data["filt"]).clone(), torch.from_numpy(data["bias"]).cuda(),
-                              torch.empty(w.shape.out_shape(), dtype=tdt, device="cuda")))
+            self.sets.append((x0.clone(), f0.clone(), torch.from_numpy(data["bias"]).cuda(),
+                              torch.full(oshape, float("nan"), dtype=tdt, device="cuda")))
         self.ws_bytes = max(256, B.conv_workspace_bytes(self.desc))
         self.ws = torch.empty(self.ws_bytes, dtype=torch.uint8, device="cuda")
         self.i = 0
@@ -108,34 +164,138 @@ class Resident:
             per.append(e0.elapsed_time(e1) / launches)
         return statistics.median(per), min(per)
 
+    def check(self, points=4096, which=0):
+        """The output buffer of tensor set `which` as the timed launches left it, against the CPU oracle on a seeded
+        sample of output elements (plus the first and last ones).  Returns the gated figure (max |gpu - ref| over the
+        sample, normalised by the largest |ref| of the sample) and the conditioning-relative error per element
+        (|gpu - ref| / (sum |in * filt| + |bias|), its maximum): the checker leg, outside every timed region."""
+        import numpy as np
 
-def layer_report(w, launches=100, batches=5, rotate_mb=0):
+        import oracle
+        from paper_1611_06945_amd import workloads as wl
+
+        w, s, torch = self.w, self.w.shape, self.torch
+        torch.cuda.synchronize()
+        o = self.sets[which][3]
+        if w.dtype == wl.BF16:
+            host = wl.storage_to_f64(o.view(torch.int16).cpu().numpy().view(np.uint16), w.dtype)
+        else:
+            host = o.cpu().numpy().astype(np.float64)
+        if self.fmt != "nchw":
+            host = np.ascontiguousarray(np.transpose(host, (0, 3, 1, 2)))
+        n_out = host.size
+        rng = np.random.default_rng(424242)
+        idx = np.unique(np.concatenate([np.arange(min(32, n_out)), n_out - 1 - np.arange(min(32, n_out)),
+                                        rng.integers(0, n_out, points)])).astype(np.int64)
+        x = wl.storage_to_f64(self.data["in"], w.dtype)
+        f = wl.storage_to_f64(self.data["filt"], w.dtype)
+        b = self.data["bias"].astype(np.float64)
+        ref = oracle.conv_fwd_points(x, f, b, idx, stride=s.stride, pad=s.pad, relu=True)
+        mag = oracle.conv_fwd_points(np.abs(x), np.abs(f), np.abs(b), idx, stride=s.stride, pad=s.pad, relu=False)
+        got = host.ravel()[idx]
+        if not np.all(np.isfinite(got)):
+            raise RuntimeError("%s via %s: output holds NaN/Inf (unwritten or overflowed elements)" % (w.name, self.variant))
+        diff = np.abs(got - ref)
+        err = float(diff.max() / max(float(np.abs(ref).max()), 1e-30))
+        cond = float((diff / np.maximum(mag, 1e-30)).max())
+        lim = TOL[wl.DTYPE_NAMES[w.dtype]]
+        if err > lim:
+            raise RuntimeError("%s via %s: max normalised error %.3g over the limit %g" % (w.name, self.variant, err, lim))
+        return {"max_norm_err": float("%.3g" % err), "limit": lim, "max_cond_rel_err": float("%.3g" % cond),
+                "points": int(idx.size)}
+
+
+_cpu_cache = {}
+
+
+def cpu_layer_baseline(w, one_thread=False, budget_s=0.6):
+    """The oracle timed on this host's cores on one whole layer (a warm-up pass on one image, then full passes for about
+    `budget_s` seconds, at least one); cached per shape -- the oracle computes in fp64 whatever the storage type."""
+    import numpy as np
+
+    import oracle
+    from paper_1611_06945_amd import workloads as wl
+
+    s = w.shape
+    key = (tuple(s.in_shape()), tuple(s.filt_shape()), s.stride, s.pad, one_thread)
+    if key in _cpu_cache:
+        return _cpu_cache[key]
+    data = w.generate()
+    x = wl.storage_to_f64(data["in"], w.dtype)
+    f = wl.storage_to_f64(data["filt"], w.dtype)
+    b = data["bias"].astype(np.float64)
+    full = oracle.threads()
+    if one_thread:
+        oracle.set_threads(1)
+    try:
+        oracle.conv_fwd(x[:1], f, b, stride=s.stride, pad=s.pad, relu=True)
+        n, t0 = 0, time.perf_counter()
+        while True:
+            oracle.conv_fwd(x, f, b, stride=s.stride, pad=s.pad, relu=True)
+            n += 1
+            dt = time.perf_counter() - t0
+            if dt >= budget_s or n >= 2000:
+                break
+        cores = oracle.threads()
+    finally:
+        oracle.set_threads(full)
+    rep = {"ms": round(dt / n * 1e3, 4), "gflops": round(s.flops * n / dt / 1e9, 3), "cores": cores, "passes": n, "kind": "oracle"}
+    _cpu_cache[key] = rep
+    return rep
+
+
+def cpu_model():
+    try:
+        with open("/proc/cpuinfo") as fh:
+            for line in fh:
+                if line.startswith("model name"):
+                    return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
+def layer_report(w, launches=100, batches=5, rotate_mb=0, fmt="nchw", cpu=True, cpu_one_thread=False):
     from paper_1611_06945_amd import workloads as wl
 
     dt = wl.DTYPE_NAMES[w.dtype]
     abytes = w.shape.algorithmic_bytes(w.dtype)
-    r = Resident(w)
+    r = Resident(w, fmt=fmt)
     variant = r.autotune()
     med_h, _ = r.time_batches(launches, batches, warmup=20)
     med, mn = r.time_device(launches, batches)
+    chk = r.check()
+    executed = executed_mfma_flops(variant, w.shape)
     rep = {
-        "layer": w.name, "N": w.shape.N, "dtype": dt, "variant": variant,
+        "layer": w.name + ("" if fmt == "nchw" else "+" + fmt), "N": w.shape.N, "dtype": dt, "format": fmt, "variant": variant,
         "ms": round(med, 6), "ms_min": round(mn, 6), "ms_host_loop": round(med_h, 6),
         "gflops": round(w.shape.flops / (med * 1e-3) / 1e9, 1),
-        "frac_mfma_peak": round(w.shape.flops / (med * 1e-3) / (PEAK_TFLOPS[dt] * 1e12), 5),
+        # fraction of the MFMA peak the matrix units really sustain (never above 1); for a Winograd variant the rate by
+        # the paper's FLOP convention (FLOPs of the direct definition) is the separate `effective_frac_direct_flops`
+        "frac_mfma_peak": round(executed / (med * 1e-3) / (PEAK_TFLOPS[dt] * 1e12), 5),
         "hbm_gbs_algorithmic": round(abytes / (med * 1e-3) / 1e9, 1),
         "frac_hbm_peak": round(abytes / (med * 1e-3) / (PEAK_HBM_GBS * 1e9), 5),
         "flops": w.shape.flops, "algorithmic_bytes": abytes,
+        "max_norm_err": chk["max_norm_err"], "max_cond_rel_err": chk["max_cond_rel_err"], "checked_points": chk["points"],
     }
+    if executed != w.shape.flops:
+        rep["effective_frac_direct_flops"] = round(w.shape.flops / (med * 1e-3) / (PEAK_TFLOPS[dt] * 1e12), 5)
+    if r.convert_us:
+        rep["convert_us"] = r.convert_us
     if rotate_mb:
         # enough distinct tensor sets to exceed the last-level cache, so the figure is an HBM figure
         copies = max(2, int(rotate_mb * 1e6 / abytes) + 1)
-        rr = Resident(w, copies=copies)
+        rr = Resident(w, copies=copies, fmt=fmt)
         rr.autotune()
         med_r, _ = rr.time_batches(max(launches, copies), batches, warmup=copies)
+        rr.check(which=copies - 1)
         rep["ms_rotated"] = round(med_r, 6)
         rep["frac_hbm_peak_rotated"] = round(abytes / (med_r * 1e-3) / (PEAK_HBM_GBS * 1e9), 5)
         rep["rotated_copies"] = copies
+    if cpu:
+        rep["cpu_baseline"] = cpu_layer_baseline(w)
+        if cpu_one_thread:
+            rep["cpu_baseline_1_thread"] = cpu_layer_baseline(w, one_thread=True)
     return rep
 
 
@@ -181,7 +341,7 @@ def stack_report(dtype, batch=20, reps=50):
             e1.synchronize()
             per.append(e0.elapsed_time(e1) / reps)
         ms = statistics.median(per)
-        rep[tag] = {"formats": st.formats, "pool_fused": st.fused, "ms": round(ms, 5),
+        rep[tag] = {"formats": st.formats, "filter_formats": st.filt_formats, "pool_fused": st.fused, "ms": round(ms, 5),
                     "gflops": round(flops / (ms * 1e-3) / 1e9, 1),
                     "variants": [B.conv_variant_name(d, -1) for d in st.descs]}
         # the same chain recorded once into a HIP graph and replayed: one launch per pass instead of one per operation
@@ -226,7 +386,7 @@ def cpu_baseline(w, budget_s=12.0):
         if dt >= budget_s or n >= 1000:
             break
     return {"value": round(w.shape.flops * n / dt / 1e9, 3), "unit": "GFLOP/s", "cores": oracle.threads(),
-            "kind": "oracle", "ms_per_step": round(dt / n * 1e3, 3),
+            "kind": "oracle", "ms_per_step": round(dt / n * 1e3, 3), "cpu_model": cpu_model(),
             "sample": "%d full passes of %s (fp64 direct convolution, %.1f s)" % (n, w.name, dt)}
 
 
@@ -307,14 +467,18 @@ def sweep_appendix_a(batch, dtype, table_out=None, launches=100, batches=5):
 
 
 def stored_traffic(kernel_key):
-    """HBM bytes per launch measured offline with rocprofv3 --pmc (see profiles/); None if not recorded."""
+    """HBM bytes per launch measured offline with rocprofv3 --pmc (see profiles/).  A variant without a record gets an
+    explicit text instead of a number, so that a missing measurement cannot pass for one."""
     path = os.path.join(ROOT, "profiles", "hbm_traffic.json")
     try:
         with open(path) as fh:
             rec = json.load(fh).get(kernel_key)
-            return None if rec is None else rec.get("total_bytes")
     except (OSError, ValueError):
-        return None
+        rec = None
+    if rec is None or rec.get("total_bytes") is None:
+        log("warning: no FETCH_SIZE/WRITE_SIZE record for %s in profiles/hbm_traffic.json" % kernel_key)
+        return "not recorded for %s" % kernel_key
+    return rec["total_bytes"]
 
 
 def main():
@@ -325,6 +489,11 @@ def main():
     ap.add_argument("--workload", default="cfg4_mid3x3_n20_f32")
     ap.add_argument("--variant", help="run the headline workload on this variant instead of the autotuned one "
                                       "(for profiling one kernel; the figure is then not the headline)")
+    ap.add_argument("--format", choices=["nchw", "nhwc", "nhwc_packed"], default="nchw",
+                    help="tensor formats of the workload (16-bit layers only for the channel-innermost ones); anything but "
+                         "nchw is for profiling one kernel: the headline stays on the plain contract")
+    ap.add_argument("--probe", action="store_true", help="print the device microbenchmarks (MFMA issue rate by occupancy and "
+                                                         "interleaved vector-ALU work, copy bandwidth) and exit")
     ap.add_argument("--no-layers", action="store_true", help="skip the per-layer table")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--sweep", choices=["appendix_a"], help="time the paper's whole benchmark set instead of one workload")
@@ -349,6 +518,25 @@ def main():
     torch.cuda.set_device(0)
     log("device:", torch.cuda.get_device_name(0))
 
+    if a.probe:
+        scratch = torch.zeros(64, device="cuda")
+        rows = []
+        for code, name in ((wl.F16, "f16"), (wl.BF16, "bf16"), (wl.F32, "f32")):
+            for block in (32, 16):
+                for wps in (1, 2, 4):
+                    for nv in (0, 2, 4, 8):
+                        tf, ns = B.conv_probe_mfma_mix(code, block, wps, nv, scratch)
+                        rows.append({"dtype": name, "block": block, "waves_per_simd": wps, "valu_per_mfma": nv,
+                                     "tflops": round(tf, 1), "ns_per_mfma": round(ns, 2)})
+                        log("mfma %-4s %2dx%-2d  %d waves/SIMD  %d VALU per MFMA: %8.1f TFLOP/s  %6.2f ns per MFMA and SIMD" % (
+                            name, block, block, wps, nv, tf, ns))
+        big = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
+        big2 = torch.empty_like(big)
+        copy = round(B.conv_probe_stream_bandwidth(big, big2, big.numel()), 1)
+        log("1 GiB device-to-device copy: %.1f GB/s (read + written bytes)" % copy)
+        print(json.dumps({"probe": "mfma_mix", "rows": rows, "stream_copy_gbs": copy}), flush=True)
+        return
+
     if a.sweep:
         code = {"f32": wl.F32, "f16": wl.F16, "bf16": wl.BF16}[a.sweep_dtype]
         summary, ops = sweep_appendix_a(a.sweep_batch, code, a.table_out)
@@ -368,7 +556,7 @@ def main():
     dt = wl.DTYPE_NAMES[w.dtype]
 
     # ---- headline: exactly `steps` timed steps after `warmup` untimed ones --------------------------------
-    r = Resident(w)
+    r = Resident(w, fmt=a.format)
     variant = r.autotune()
     if a.variant:
         names = [B.conv_variant_name(r.desc, i) for i in range(B.conv_variant_count(r.desc))]
@@ -393,12 +581,22 @@ def main():
     ms_per_step = wall_ms / a.steps
     kern_ms = ev_ms / a.steps  # device-side average per launch over the timed region
     gflops = w.shape.flops / (ms_per_step * 1e-3) / 1e9
+    check = r.check()          # the output the timed launches left behind, against the oracle (raises over the limit)
+    log("checked %d outputs of the timed run against the oracle: max normalised error %.3g (limit %g), conditioning-relative %.3g" % (
+        check["points"], check["max_norm_err"], check["limit"], check["max_cond_rel_err"]))
 
     mfma_bound = w.shape.flops / (PEAK_TFLOPS[dt] * 1e12) >= w.shape.algorithmic_bytes(w.dtype) / (PEAK_HBM_GBS * 1e9)
+    executed = executed_mfma_flops(variant, w.shape)
     if mfma_bound:
-        ach = w.shape.flops / (kern_ms * 1e-3) / 1e12
+        # `achieved` / `frac`: what the matrix units sustain (FLOPs they execute / time), which cannot exceed the peak.  For
+        # a Winograd variant that is 2.25x fewer FLOPs than the direct definition's; the rate by the paper's FLOP
+        # convention (how it also rates the vendor library's Winograd kernels) is `effective_*_direct_flops`.
+        ach = executed / (kern_ms * 1e-3) / 1e12
         roof = {"bound": "mfma", "achieved": round(ach, 3), "peak": PEAK_TFLOPS[dt], "unit": "TFLOP/s",
-                "frac": round(ach / PEAK_TFLOPS[dt], 5)}
+                "frac": round(ach / PEAK_TFLOPS[dt], 5), "flops_counted": "executed by the matrix units",
+                "mfma_flops_executed": executed, "algorithmic_flops": w.shape.flops,
+                "effective_tflops_direct_flops": round(w.shape.flops / (kern_ms * 1e-3) / 1e12, 3),
+                "effective_frac_direct_flops": round(w.shape.flops / (kern_ms * 1e-3) / 1e12 / PEAK_TFLOPS[dt], 5)}
     else:
         ach = w.shape.algorithmic_bytes(w.dtype) / (kern_ms * 1e-3) / 1e9
         roof = {"bound": "hbm", "achieved": round(ach, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
@@ -417,24 +615,11 @@ def main():
     roof["kernel"] = variant
     roof["kernel_ms"] = round(kern_ms, 6)
     if variant.startswith("wino_"):
-        # `achieved` above counts the FLOPs of the direct definition (the paper's per-operation FLOP count, which is how it
-        # also rates the vendor library's Winograd kernels); the MFMA units execute 2.25x fewer multiplications, on tiles
-        # padded to the workgroup shape.  Both views are reported, next to the fastest direct variant the tuner measured.
-        import re
+        # next to the fastest direct variant the tuner measured, and the same layer with pre-transformed filters
         sh = w.shape
-        tiles = sh.N * ((sh.OH + 1) // 2) * ((sh.OW + 1) // 2)
-
-        def executed_flops(name):
-            m = re.match(r"wino_f32_M(\d+)T(\d+)_", name)
-            tm, tt = int(m.group(1)), int(m.group(2))
-            return 2.0 * 16 * (-(-sh.K // tm) * tm) * (-(-tiles // tt) * tt) * sh.C
-
-        executed = executed_flops(variant)
         fused = variant.endswith("_ff")
         roof["algorithm"] = ("winograd F(2x2,3x3): one kernel per launch (filter, input and output transforms around the MFMA planes)"
                              if fused else "winograd F(2x2,3x3): filter transform kernel + fused product kernel per launch")
-        roof["mfma_flops_executed"] = executed
-        roof["frac_executed"] = round(executed / (kern_ms * 1e-3) / 1e12 / PEAK_TFLOPS[dt], 5)
         n = B.conv_variant_count(r.desc)
         direct = [(B.conv_variant_time_us(r.desc, i), B.conv_variant_name(r.desc, i)) for i in range(n)]
         direct = [x for x in direct if not x[1].startswith("wino_") and x[0] > 0]
@@ -450,8 +635,8 @@ def main():
             pre_variant = B.conv_variant_name(pre, -1)
             roof["pretransformed_filters"] = {"variant": pre_variant, "us": round(us, 2),
                                               "tflops": round(sh.flops / (us * 1e-6) / 1e12, 2),
-                                              "frac": round(sh.flops / (us * 1e-6) / 1e12 / PEAK_TFLOPS[dt], 5),
-                                              "frac_executed": round(executed_flops(pre_variant) / (us * 1e-6) / 1e12 / PEAK_TFLOPS[dt], 5)}
+                                              "frac": round(executed_mfma_flops(pre_variant, sh) / (us * 1e-6) / 1e12 / PEAK_TFLOPS[dt], 5),
+                                              "effective_frac_direct_flops": round(sh.flops / (us * 1e-6) / 1e12 / PEAK_TFLOPS[dt], 5)}
         if direct:
             t_us, nm = min(direct)
             roof["best_direct"] = {"variant": nm, "tuner_us": round(t_us, 2),
@@ -463,27 +648,38 @@ def main():
         "scaling": "weak", "vs_baseline": None, "dtype": dt, "data": "synthetic",
         "config": {"workload": w.name, "N": w.shape.N, "C": w.shape.C, "H": w.shape.H, "W": w.shape.W,
                    "K": w.shape.K, "R": w.shape.R, "S": w.shape.S, "stride": w.shape.stride, "pad": w.shape.pad,
-                   "fused": "bias+relu", "variant": variant, "paper_row": w.paper_row},
+                   "fused": "bias+relu", "format": a.format, "variant": variant, "paper_row": w.paper_row},
+        "variant": variant, "max_norm_err": check["max_norm_err"], "max_cond_rel_err": check["max_cond_rel_err"],
+        "checked_points": check["points"], "tolerance": check["limit"],
         "roofline": roof,
         "measured_peaks": measured,
     }
 
     if not a.no_layers:
         layers = []
-        for lw in all_workloads():
+        entries = [(lw, "nchw") for lw in all_workloads()]
+        # the 16-bit 3x3 / 5x5 layers again on channel-innermost tensors with the filters in MFMA operand order (explicit
+        # ahead-of-time conversions, timed separately in `convert_us`): the format the stack planner selects for them
+        entries += [(lw, "nhwc_packed") for lw in all_workloads()
+                    if lw.dtype == wl.F16 and (lw.name.startswith("cfg4") or lw.name[:7] in ("cfg5_L2", "cfg5_L3", "cfg5_L4", "cfg5_L5"))]
+        for lw, fmt in entries:
             hbmish = lw.name.startswith("cfg2") or lw.name.startswith("cfg5_L1") or (lw.shape.N == 1 and lw.dtype != wl.F32)
-            rep = layer_report(lw, rotate_mb=300 if hbmish else 0)
+            small = lw.name.startswith(("cfg1", "cfg2")) or (lw.name.startswith("cfg4") and lw.shape.N == 1)
+            rep = layer_report(lw, rotate_mb=300 if hbmish else 0, fmt=fmt, cpu=not a.no_cpu, cpu_one_thread=small)
             layers.append(rep)
-            log("%-26s %-44s %9.4f ms %10.1f GFLOP/s  mfma %.3f  hbm %.3f" % (
-                rep["layer"], rep["variant"], rep["ms"], rep["gflops"], rep["frac_mfma_peak"], rep["frac_hbm_peak"]))
+            log("%-34s %-44s %9.4f ms %10.1f GFLOP/s  mfma %.3f  hbm %.3f  err %.2g%s" % (
+                rep["layer"], rep["variant"], rep["ms"], rep["gflops"], rep["frac_mfma_peak"], rep["frac_hbm_peak"],
+                rep["max_norm_err"], "  cpu %.1f GFLOP/s" % rep["cpu_baseline"]["gflops"] if "cpu_baseline" in rep else ""))
         out["layers"] = layers
         out["stack"] = stack_report(wl.F16)
-        log("stack f16: all-NCHW %.4f ms (HIP graph %.4f), formats selected %s pools fused %s %.4f ms (HIP graph %.4f)" % (
+        log("stack f16: all-NCHW %.4f ms (HIP graph %.4f), formats selected %s filters %s pools fused %s %.4f ms (HIP graph %.4f)" % (
             out["stack"]["nchw"]["ms"], out["stack"]["nchw"]["graph_ms"], out["stack"]["selected"]["formats"],
-            out["stack"]["selected"]["pool_fused"], out["stack"]["selected"]["ms"], out["stack"]["selected"]["graph_ms"]))
+            out["stack"]["selected"]["filter_formats"], out["stack"]["selected"]["pool_fused"], out["stack"]["selected"]["ms"],
+            out["stack"]["selected"]["graph_ms"]))
 
     if not a.no_cpu:
         out["cpu_baseline"] = cpu_baseline(w)
+        out["cpu_model"] = cpu_model()
         log("cpu oracle:", out["cpu_baseline"])
 
     print(json.dumps(out), flush=True)

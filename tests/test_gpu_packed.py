@@ -176,20 +176,3 @@ def test_stack_layers_at_full_size_on_sampled_outputs(li):
         assert np.all(np.isfinite(got)), name
         err = float(np.max(np.abs(got.ravel()[idx] - ref))) / scale
         assert err <= TOL[wl.F16], "%s: error %.3g" % (name, err)
-
-
-def test_packed_flag_host_rules():
-    # no kernel: fp32, C not a multiple of 16, stride 2, planar input, or the flag combined with another filter format
-    ok = B.desc_of(ConvShape(1, 64, 13, 13, 64, 3, 3, 1, 1), wl.F16, in_nhwc=True, filt_packed=True)
-    assert B.conv_variant_count(ok) > 0 and B.conv_transformed_filter_bytes(ok) == 64 * 64 * 9 * 2
-    for shape, dt, kw in [
-        (ConvShape(1, 64, 13, 13, 64, 3, 3, 1, 1), wl.F32, dict(in_nhwc=True)),
-        (ConvShape(1, 40, 13, 13, 64, 3, 3, 1, 1), wl.F16, dict(in_nhwc=True)),
-        (ConvShape(1, 64, 13, 13, 64, 3, 3, 2, 1), wl.F16, dict(in_nhwc=True)),
-        (ConvShape(1, 64, 13, 13, 64, 3, 3, 1, 1), wl.F16, dict(in_nhwc=False)),
-        (ConvShape(1, 64, 13, 13, 64, 3, 3, 1, 1), wl.F16, dict(in_nhwc=True, filt_krsc=True)),
-        (ConvShape(1, 64, 13, 13, 64, 3, 3, 1, 1), wl.F16, dict(in_nhwc=True, maxpool=True)),
-        (ConvShape(1, 64, 13, 13, 64, 3, 3, 1, 3), wl.F16, dict(in_nhwc=True)),
-    ]:
-        d = B.desc_of(shape, dt, filt_packed=True, **kw)
-        assert B.conv_variant_count(d) == 0, (shape, dt, kw)

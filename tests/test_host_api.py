@@ -52,7 +52,7 @@ def test_out_shape_of_benchmark_configs():
 
 
 @pytest.mark.parametrize("field,value", [("N", 0), ("C", 0), ("H", 0), ("W", -1), ("K", 0), ("R", 0), ("S", 0),
-                                         ("stride", 0), ("pad", -1), ("flags", 64)])
+                                         ("stride", 0), ("pad", -1), ("flags", 128)])
 def test_invalid_descriptor_fields(field, value):
     d = B.make_desc(1, 3, 8, 8, 4, 3, 3, 1, 1)
     setattr(d, field, value)
@@ -409,3 +409,37 @@ def test_static_scratch_entry_point_validates_and_refuses_oversized_variants_on_
     # the header's constant and the binding's agree
     text = open(os.path.join(ROOT, "include", "convfwd.h")).read()
     assert "#define CONV_STATIC_SCRATCH_BYTES (32u << 20)" in text and B.CONV_STATIC_SCRATCH_BYTES == 32 << 20
+
+
+def test_packed_filter_flag_host_rules():
+    # kernels that read filters in MFMA operand order: fp16/bf16, stride 1, C % 16 == 0, 3x3 / 5x5 windows with a border
+    # narrower than the window, channel-innermost input; every other use of the flag finds no kernel
+    from paper_1611_06945_amd.workloads import ConvShape
+
+    ok = B.desc_of(ConvShape(1, 64, 13, 13, 64, 3, 3, 1, 1), wl.F16, in_nhwc=True, filt_packed=True)
+    assert B.conv_variant_count(ok) > 0
+    assert all(B.conv_variant_name(ok, i).startswith("pwin_") for i in range(B.conv_variant_count(ok)))
+    assert B.conv_transformed_filter_bytes(ok) == 64 * 64 * 9 * 2
+    ragged = B.desc_of(ConvShape(1, 64, 13, 13, 40, 3, 3, 1, 1), wl.BF16, in_nhwc=True, filt_packed=True)
+    assert B.conv_transformed_filter_bytes(ragged) == 64 * 64 * 9 * 2   # rows padded to whole 32-row blocks
+    for shape, dt, kw in [
+        (ConvShape(1, 64, 13, 13, 64, 3, 3, 1, 1), wl.F32, dict(in_nhwc=True)),
+        (ConvShape(1, 40, 13, 13, 64, 3, 3, 1, 1), wl.F16, dict(in_nhwc=True)),
+        (ConvShape(1, 64, 13, 13, 64, 3, 3, 2, 1), wl.F16, dict(in_nhwc=True)),
+        (ConvShape(1, 64, 13, 13, 64, 3, 3, 1, 1), wl.F16, dict(in_nhwc=False)),
+        (ConvShape(1, 64, 13, 13, 64, 3, 3, 1, 1), wl.F16, dict(in_nhwc=True, filt_krsc=True)),
+        (ConvShape(1, 64, 13, 13, 64, 3, 3, 1, 1), wl.F16, dict(in_nhwc=True, maxpool=True)),
+        (ConvShape(1, 64, 13, 13, 64, 3, 3, 1, 3), wl.F16, dict(in_nhwc=True)),
+        (ConvShape(1, 64, 13, 13, 64, 7, 7, 1, 3), wl.F16, dict(in_nhwc=True)),
+    ]:
+        d = B.desc_of(shape, dt, filt_packed=True, **kw)
+        assert B.conv_variant_count(d) == 0, (shape, dt, kw)
+    # the conversion call validates before any GPU call and names the target by the flag
+    with pytest.raises(B.ConvError) as ei:
+        B.conv_transform_filters(ok, 256, 512 + 16, None)   # output not 256-byte aligned
+    assert ei.value.status == B.CONV_EINVAL
+    none = B.desc_of(ConvShape(1, 40, 13, 13, 64, 3, 3, 1, 1), wl.F16, in_nhwc=True, filt_packed=True)
+    assert B.conv_transformed_filter_bytes(none) == 0
+    with pytest.raises(B.ConvError) as ei:
+        B.conv_transform_filters(none, 256, 512, None)
+    assert ei.value.status == B.CONV_ENOVARIANT
