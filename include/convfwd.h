@@ -161,6 +161,14 @@ int conv_fwd_static(const conv_desc* desc, const void* in, const void* filt, con
  * the in-process cache used by conv_fwd/conv_fwd_ws (two entries: best overall,
  * best without workspace).  `out` is overwritten.  Synchronises `stream`.
  * `workspace` may be NULL (then only variants without workspace are tried).
+ * Every candidate's output is cross-checked before it may win (the paper's tuning flow verifies outputs numerically,
+ * Section 4 "Experimental Setup"): the output of a reference candidate (the first unsplit direct variant that fits)
+ * is kept, and a candidate whose output differs from it by more than 2e-5 (fp32), 5e-3 (fp16) or 1e-2 (bf16: one
+ * rounding step of an 8-bit significand) in the max-normalised sense of conv_compare_outputs() is neither timed nor
+ * selected; conv_variant_time_us() then reports -2 for it.  For this check -- and only here -- the call allocates and
+ * frees a temporary device buffer of the size of `out`.  Test hook: when the environment variable
+ * CONVFWD_AUTOTUNE_CORRUPT names a variant, the first bytes of that candidate's output are overwritten from the host
+ * before the check, so that the rejection path can be exercised without a wrong kernel.
  */
 int conv_autotune(const conv_desc* desc, const void* in, const void* filt, const float* bias, void* out,
                   void* workspace, size_t workspace_bytes, void* stream);
@@ -183,7 +191,8 @@ long long conv_variant_workspace(const conv_desc* desc, int idx);
  * way); idx = -1 removes the override. */
 int conv_force_variant(const conv_desc* desc, int idx);
 
-/* Last measured time (microseconds per launch) of variant `idx` from conv_autotune in this process; < 0 if none. */
+/* Last measured time (microseconds per launch) of variant `idx` from conv_autotune in this process; -1 if it was not
+ * tried (no autotune yet, or it did not fit the workspace), -2 if the cross-check rejected its output. */
 double conv_variant_time_us(const conv_desc* desc, int idx);
 
 /*
@@ -197,9 +206,22 @@ int conv_time_us(const conv_desc* desc, const void* in, const void* filt, const 
                  size_t workspace_bytes, void* stream, int launches, double* us_per_launch);
 
 /*
+ * The error metric of the parity tests and of the autotuner's cross-check on two device tensors of `elements`
+ * elements of `dtype`: max_i |got_i - ref_i| / max(max_j |ref_j|, 1e-30); infinity if `got` holds a NaN, or an
+ * infinity where `ref` is finite (the paper compares outputs with relative tolerances, Section 4 "Experimental
+ * Setup").  Synchronises `stream`; allocates 256 bytes of device scratch for the duration of the call.
+ */
+int conv_compare_outputs(int32_t dtype, const void* got, const void* ref, size_t elements, void* stream,
+                         double* max_norm_err);
+
+/*
  * Autotune cache persistence: a text file, one line per descriptor
  * ("N C H W K R S stride pad dtype flags | best-name | best-no-workspace-name").
- * Load merges into the in-process cache and ignores lines naming unknown
+ * A saved file starts with an identity line ("#! convfwd-cache device=<arch/name/CUs> registry=<hash of the
+ * library's variant list>"): measurements are only valid for the device model and the set of kernels they were
+ * taken with, so load refuses (CONV_EIO) a file whose identity line names another registry, or another device
+ * when both sides know theirs ("none" = written or read on a host without a GPU); a file without an identity line
+ * (hand-written) is accepted.  Load merges into the in-process cache and ignores lines naming unknown
  * variants; a missing, unreadable or malformed file gives CONV_EIO and leaves
  * the cache as it was.  conv_cache_clear drops every cached and forced choice.
  */

@@ -73,6 +73,8 @@ def lib() -> ctypes.CDLL:
         L.conv_fwd_static.restype = ctypes.c_int
         L.conv_autotune.argtypes = [dp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
         L.conv_autotune.restype = ctypes.c_int
+        L.conv_compare_outputs.argtypes = [ctypes.c_int32, vp, vp, ctypes.c_size_t, vp, ctypes.POINTER(ctypes.c_double)]
+        L.conv_compare_outputs.restype = ctypes.c_int
         L.conv_variant_count.argtypes = [dp]
         L.conv_variant_count.restype = ctypes.c_int
         L.conv_variant_name.argtypes = [dp, ctypes.c_int, ctypes.c_char_p, ctypes.c_size_t]
@@ -205,6 +207,13 @@ def conv_time_us(desc, inp, filt, bias, out, workspace=None, workspace_bytes=0, 
     _check(lib().conv_time_us(ctypes.byref(desc), _ptr(inp), _ptr(filt), _ptr(bias), _ptr(out), _ptr(workspace),
                               int(workspace_bytes), _stream(stream), int(launches), ctypes.byref(us)), "conv_time_us")
     return float(us.value)
+
+
+def conv_compare_outputs(dtype: int, got, ref, elements: int, stream=None) -> float:
+    v = ctypes.c_double()
+    _check(lib().conv_compare_outputs(dtype, _ptr(got), _ptr(ref), int(elements), _stream(stream), ctypes.byref(v)),
+           "conv_compare_outputs")
+    return v.value
 
 
 def conv_variant_count(desc) -> int:

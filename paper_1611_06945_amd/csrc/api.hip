@@ -5,6 +5,7 @@
 #include <array>
 #include <cmath>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <fstream>
 #include <map>
@@ -74,6 +75,31 @@ State& state()
         return s;
     }();
     return *st;
+}
+
+// Identity written into saved autotune caches: measurements belong to one device model and one set of kernels.
+std::string registry_id(State& st)
+{
+    uint64_t h = 1469598103934665603ull;  // FNV-1a over every variant name, in registration order
+    for (const Variant& v : st.variants)
+        for (unsigned char c : v.name + "\n") h = (h ^ c) * 1099511628211ull;
+    char buf[32];
+    snprintf(buf, sizeof buf, "%016llx", (unsigned long long)h);
+    return buf;
+}
+
+std::string device_id()
+{
+    int dev = 0;
+    hipDeviceProp_t p;
+    if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&p, dev) != hipSuccess) {
+        (void)hipGetLastError();  // a host without a GPU: not an error of the caller's
+        return "none";
+    }
+    std::string s = std::string(p.gcnArchName) + "/" + p.name + "/" + std::to_string(p.multiProcessorCount) + "cu";
+    for (char& c : s)
+        if (c == ' ' || c == '\t') c = '_';
+    return s;
 }
 
 thread_local std::string g_hip_msg;
@@ -540,6 +566,45 @@ int conv_autotune(const conv_desc* desc, const void* in, const void* filt, const
     std::vector<double> times(valid.size(), -1.0);
     int status = CONV_OK;
     int best = -1, best_nows = -1;
+    // Cross-check (the paper's tuning flow compares every candidate's output numerically before it may be kept, Section
+    // 4 "Experimental Setup"): the output of a reference candidate -- the first unsplit direct variant that fits, else
+    // the first that fits -- is kept in a temporary device buffer, and a candidate whose output differs from it by more
+    // than the storage type's bound is not eligible, however fast.
+    ConvArgs a0;
+    fill_args(a0, *desc, OH, OW, in, filt, bias, out, workspace);
+    const size_t out_bytes = a0.out_bytes;
+    const size_t n_out = out_bytes / dtype_size(desc->dtype);
+    int ref_i = -1;
+    for (size_t i = 0; i < valid.size(); ++i) {
+        const Variant& v = st.variants[valid[i]];
+        if (ws_bytes_of(v, *desc, OH, OW) > workspace_bytes) continue;
+        if (ref_i < 0) ref_i = (int)i;
+        if (v.split == 1 && v.family != FAM_WINOGRAD) {
+            ref_i = (int)i;
+            break;
+        }
+    }
+    void* ref = nullptr;
+    uint32_t* stats = nullptr;
+    if (ref_i >= 0) {
+        e = hipMalloc(&ref, out_bytes + 256);
+        if (e == hipSuccess) e = hipMalloc((void**)&stats, 256);
+        if (e != hipSuccess) {
+            if (ref) (void)hipFree(ref);
+            hipEventDestroy(e0);
+            hipEventDestroy(e1);
+            return hip_fail(e, "hipMalloc (autotune cross-check buffer)");
+        }
+        ConvArgs a;
+        fill_args(a, *desc, OH, OW, in, filt, bias, out, workspace);
+        status = run_variant(st.variants[valid[ref_i]], *desc, a, s);
+        if (status == CONV_OK) {
+            e = hipMemcpyAsync(ref, out, out_bytes, hipMemcpyDeviceToDevice, s);
+            if (e != hipSuccess) status = hip_fail(e, "hipMemcpyAsync");
+        }
+    }
+    const char* corrupt = getenv("CONVFWD_AUTOTUNE_CORRUPT");
+    const double check_limit = desc->dtype == CONV_F32 ? 2e-5 : desc->dtype == CONV_F16 ? 5e-3 : 1e-2;
     for (size_t i = 0; i < valid.size() && status == CONV_OK; ++i) {
         const Variant& v = st.variants[valid[i]];
         const size_t need = ws_bytes_of(v, *desc, OH, OW);
@@ -549,6 +614,26 @@ int conv_autotune(const conv_desc* desc, const void* in, const void* filt, const
         // warm-up, then a first timed launch pair to size the batch
         for (int w = 0; w < 2 && status == CONV_OK; ++w) status = run_variant(v, *desc, a, s);
         if (status) break;
+        if (corrupt && v.name == corrupt) {
+            // test hook (see include/convfwd.h): make this candidate's output wrong from the host side
+            e = hipMemsetAsync(out, 0x7b, std::min<size_t>(out_bytes, 64), s);
+            if (e != hipSuccess) {
+                status = hip_fail(e, "hipMemsetAsync");
+                break;
+            }
+        }
+        if ((int)i != ref_i) {
+            double err = 0.0;
+            e = compare_outputs(desc->dtype, out, ref, n_out, stats, s, &err);
+            if (e != hipSuccess) {
+                status = hip_fail(e, "compare_outputs");
+                break;
+            }
+            if (!(err <= check_limit)) {
+                times[i] = -2.0;  // rejected: not timed, never selected
+                continue;
+            }
+        }
         auto timed = [&](int reps, float& ms) -> int {
             hipError_t ee = hipEventRecord(e0, s);
             if (ee != hipSuccess) return hip_fail(ee, "hipEventRecord");
@@ -579,6 +664,11 @@ int conv_autotune(const conv_desc* desc, const void* in, const void* filt, const
         if (best < 0 || best_us < times[best]) best = (int)i;
         if (need == 0 && (best_nows < 0 || best_us < times[best_nows])) best_nows = (int)i;
     }
+    if (ref) {
+        (void)hipStreamSynchronize(s);
+        (void)hipFree(ref);
+        (void)hipFree(stats);
+    }
     hipEventDestroy(e0);
     hipEventDestroy(e1);
     if (status) return status;
@@ -591,6 +681,19 @@ int conv_autotune(const conv_desc* desc, const void* in, const void* filt, const
         st.cache[key_of(*desc)] = c;
         st.times_us[key_of(*desc)] = times;
     }
+    return CONV_OK;
+}
+
+int conv_compare_outputs(int32_t dtype, const void* got, const void* ref, size_t elements, void* stream, double* max_norm_err)
+{
+    if (dtype != CONV_F32 && dtype != CONV_F16 && dtype != CONV_BF16) return CONV_EDTYPE;
+    if (!got || !ref || !max_norm_err || elements < 1 || elements >= ((size_t)1 << 31)) return CONV_EINVAL;
+    uint32_t* stats = nullptr;
+    hipError_t e = hipMalloc((void**)&stats, 256);
+    if (e != hipSuccess) return hip_fail(e, "hipMalloc");
+    e = compare_outputs(dtype, got, ref, elements, stats, (hipStream_t)stream, max_norm_err);
+    (void)hipFree(stats);
+    if (e != hipSuccess) return hip_fail(e, "compare_outputs");
     return CONV_OK;
 }
 
@@ -673,6 +776,20 @@ int conv_cache_load(const char* path)
     std::map<Key, Choice> loaded;
     std::string line;
     while (std::getline(f, line)) {
+        if (line.rfind("#! convfwd-cache", 0) == 0) {
+            // identity line of a saved cache: measurements of another device model or another set of kernels are refused
+            std::istringstream hs(line.substr(2));
+            std::string tok, dev, reg;
+            while (hs >> tok) {
+                if (tok.rfind("device=", 0) == 0) dev = tok.substr(7);
+                if (tok.rfind("registry=", 0) == 0) reg = tok.substr(9);
+            }
+            if (dev.empty() || reg.empty()) return CONV_EIO;
+            const std::string here = device_id();
+            if (reg != registry_id(st)) return CONV_EIO;
+            if (dev != "none" && here != "none" && dev != here) return CONV_EIO;
+            continue;
+        }
         if (line.empty() || line[0] == '#') continue;
         // "N C H W K R S stride pad dtype flags | best | best_nows"
         std::vector<std::string> parts;
@@ -716,6 +833,7 @@ int conv_cache_save(const char* path)
     State& st = state();
     std::ofstream f(path);
     if (!f) return CONV_EIO;
+    f << "#! convfwd-cache device=" << device_id() << " registry=" << registry_id(st) << "\n";
     f << "# convfwd autotune cache: N C H W K R S stride pad dtype flags | best | best without workspace\n";
     std::lock_guard<std::mutex> g(st.mu);
     for (auto& kv : st.cache) {

@@ -3,6 +3,9 @@
 #include <mutex>
 #include <utility>
 
+#include <algorithm>
+#include <cmath>
+
 #include "igemm_kernel.h"
 
 namespace convfwd {
@@ -357,6 +360,72 @@ hipError_t launch_pack_filters16(const void* filt, void* out, int K, int C, int 
     hipLaunchKernelGGL(pack_filters16_kernel, dim3((unsigned)((nvec + 255) / 256)), dim3(256), 0, s, (const uint16_t*)filt,
                        (uint4*)out, K, C, RS, (int)nvec);
     return hipGetLastError();
+}
+
+// Reduction behind compare_outputs: stats[0] = bits of max |got - ref|, stats[1] = bits of max |ref| (non-negative floats
+// order like their bit patterns), stats[2] = count of elements where got is NaN, or infinite while ref is finite.
+template <int DT>
+__global__ __launch_bounds__(256) void compare_kernel(const void* got_, const void* ref_, size_t n, uint32_t* stats)
+{
+    typedef typename Prec<DT>::elem_t elem_t;
+    const elem_t* got = (const elem_t*)got_;
+    const elem_t* ref = (const elem_t*)ref_;
+    float md = 0.0f, mr = 0.0f;
+    uint32_t bad = 0;
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) {
+        const float g = Prec<DT>::to_f32(got[i]), r = Prec<DT>::to_f32(ref[i]);
+        const bool rfin = fabsf(r) <= 3.4e38f;
+        if (g != g || (!(fabsf(g) <= 3.4e38f) && rfin)) {
+            ++bad;
+            continue;
+        }
+        if (!rfin) continue;  // both infinite the same way, or the reference itself overflowed: nothing to compare
+        const float d = fabsf(g - r);
+        md = d > md ? d : md;
+        mr = fabsf(r) > mr ? fabsf(r) : mr;
+    }
+    __shared__ float smd[256], smr[256];
+    __shared__ uint32_t sbad[256];
+    smd[threadIdx.x] = md;
+    smr[threadIdx.x] = mr;
+    sbad[threadIdx.x] = bad;
+    __syncthreads();
+    for (int w = 128; w > 0; w >>= 1) {
+        if ((int)threadIdx.x < w) {
+            smd[threadIdx.x] = fmaxf(smd[threadIdx.x], smd[threadIdx.x + w]);
+            smr[threadIdx.x] = fmaxf(smr[threadIdx.x], smr[threadIdx.x + w]);
+            sbad[threadIdx.x] += sbad[threadIdx.x + w];
+        }
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) {
+        atomicMax(&stats[0], __builtin_bit_cast(uint32_t, smd[0]));
+        atomicMax(&stats[1], __builtin_bit_cast(uint32_t, smr[0]));
+        if (sbad[0]) atomicAdd(&stats[2], sbad[0]);
+    }
+}
+
+hipError_t compare_outputs(int dtype, const void* got, const void* ref, size_t n, uint32_t* stats, hipStream_t s, double* err)
+{
+    hipError_t e = hipMemsetAsync(stats, 0, 16, s);
+    if (e != hipSuccess) return e;
+    const unsigned blocks = (unsigned)std::min<size_t>((n + 255) / 256, 2048);
+    if (dtype == CONV_F32)
+        hipLaunchKernelGGL(compare_kernel<CONV_F32>, dim3(blocks), dim3(256), 0, s, got, ref, n, stats);
+    else if (dtype == CONV_F16)
+        hipLaunchKernelGGL(compare_kernel<CONV_F16>, dim3(blocks), dim3(256), 0, s, got, ref, n, stats);
+    else
+        hipLaunchKernelGGL(compare_kernel<CONV_BF16>, dim3(blocks), dim3(256), 0, s, got, ref, n, stats);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    uint32_t h[4] = {0, 0, 0, 0};
+    e = hipMemcpyAsync(h, stats, 16, hipMemcpyDeviceToHost, s);
+    if (e != hipSuccess) return e;
+    e = hipStreamSynchronize(s);
+    if (e != hipSuccess) return e;
+    const double md = __builtin_bit_cast(float, h[0]), mr = __builtin_bit_cast(float, h[1]);
+    *err = h[2] ? (double)INFINITY : md / std::max(mr, 1e-30);
+    return hipSuccess;
 }
 
 hipError_t launch_transpose(int A, int B, int S, int esize, const void* in, void* out, hipStream_t s)

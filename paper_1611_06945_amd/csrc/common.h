@@ -158,6 +158,10 @@ size_t wino_transformed_filter_bytes(int K, int C);
 // KCRS 16-bit filters -> MFMA operand order of the packed-filter kernels (aux_kernels.hip); C % 16 == 0
 hipError_t launch_pack_filters16(const void* filt, void* out, int K, int C, int RS, hipStream_t s);
 
+// max_i |got_i - ref_i| / max(max_j |ref_j|, 1e-30) of two device tensors of `n` elements (infinity when `got` holds a
+// non-finite value where `ref` is finite, or a NaN); `stats` is 16 bytes of device scratch.  Synchronises `s`.
+hipError_t compare_outputs(int dtype, const void* got, const void* ref, size_t n, uint32_t* stats, hipStream_t s, double* err);
+
 // Device ceilings measured in place (probe_kernels.hip).
 hipError_t probe_mfma(int dtype, int block, float* sink, hipStream_t s, double* tflops);
 hipError_t probe_mfma_mix(int dtype, int block, int wps, int nv, float* sink, hipStream_t s, double* tflops, double* ns);

@@ -203,6 +203,57 @@ def test_autotune_records_times_and_selects_the_fastest():
     B.conv_cache_clear()
 
 
+@pytest.mark.parametrize("dtype", DTYPES)
+def test_compare_outputs_is_the_parity_metric(dtype):
+    torch = torch_mod()
+    rng = np.random.default_rng(77)
+    ref = wl.to_storage(rng.normal(0.0, 1.0, 70001).astype(np.float32), dtype)
+    got = ref.copy()
+    d_ref, d_got = to_device(ref, dtype), to_device(got, dtype)
+    assert B.conv_compare_outputs(dtype, d_got, d_ref, ref.size) == 0.0
+    # one element moved by a known amount, near the end of the tensor (past every whole block of threads)
+    r64 = wl.storage_to_f64(ref, dtype)
+    g64 = r64.copy()
+    g64[69990] += 0.25
+    got = wl.to_storage(g64.astype(np.float32), dtype)
+    want = oracle.max_normalised_error(wl.storage_to_f64(got, dtype), r64)
+    err = B.conv_compare_outputs(dtype, to_device(got, dtype), d_ref, ref.size)
+    assert want > 0.01 and abs(err - want) <= 1e-6 * want, (err, want)
+    # a NaN or an infinity in the tested tensor is an infinite error, wherever it sits
+    for bad in (np.nan, np.inf):
+        g64 = r64.copy()
+        g64[12345] = bad
+        err = B.conv_compare_outputs(dtype, to_device(wl.to_storage(g64.astype(np.float32), dtype), dtype), d_ref, ref.size)
+        assert err == float("inf")
+    torch.cuda.synchronize()
+
+
+def test_autotune_rejects_a_candidate_whose_output_is_wrong(monkeypatch):
+    # the candidate named by the test hook gets its output overwritten from the host before the cross-check: it must be
+    # neither timed nor selected, even though it would otherwise be eligible; everything else is unaffected
+    B.conv_cache_clear()
+    case = random_case(ConvShape(2, 20, 12, 12, 200, 3, 3, 1, 1), wl.F32, 82)
+    out = empty_out(case.shape.out_shape(), wl.F32)
+    ws = case.workspace()
+    B.conv_autotune(case.desc, case.d_in, case.d_filt, case.d_bias, out, ws, ws.numel())
+    names = case.variant_names()
+    winner = B.conv_variant_name(case.desc, -1)
+    assert all(B.conv_variant_time_us(case.desc, i) > 0 for i in range(len(names)))  # nothing rejected on a clean run
+    B.conv_cache_clear()
+    monkeypatch.setenv("CONVFWD_AUTOTUNE_CORRUPT", winner)
+    B.conv_autotune(case.desc, case.d_in, case.d_filt, case.d_bias, out, ws, ws.numel())
+    monkeypatch.delenv("CONVFWD_AUTOTUNE_CORRUPT")
+    times = [B.conv_variant_time_us(case.desc, i) for i in range(len(names))]
+    wi = names.index(winner)
+    if wi == 0:
+        pytest.skip("the fastest variant is the cross-check's own reference")
+    assert times[wi] == -2.0, times[wi]
+    assert all(t > 0 for i, t in enumerate(times) if i != wi)
+    assert B.conv_variant_name(case.desc, -1) != winner
+    assert case.error(case.run()) <= TOL[wl.F32]
+    B.conv_cache_clear()
+
+
 def test_device_side_timing_entry_point():
     case = random_case(ConvShape(2, 20, 12, 12, 200, 3, 3, 1, 1), wl.F32, 81)
     out = empty_out(case.shape.out_shape(), wl.F32)

@@ -443,3 +443,43 @@ def test_packed_filter_flag_host_rules():
     with pytest.raises(B.ConvError) as ei:
         B.conv_transform_filters(none, 256, 512, None)
     assert ei.value.status == B.CONV_ENOVARIANT
+
+
+def test_saved_cache_carries_the_identity_of_device_and_kernels(tmp_path):
+    B.conv_cache_clear()
+    d = B.desc_of(config4(5).shape, 0)
+    names = [B.conv_variant_name(d, i) for i in range(B.conv_variant_count(d))]
+    other = names[-1]
+    src = tmp_path / "in.txt"
+    src.write_text("5 256 13 13 384 3 3 1 1 0 1 | %s | %s\n" % (other, other))
+    B.conv_cache_load(str(src))
+    out = tmp_path / "saved.txt"
+    B.conv_cache_save(str(out))
+    text = out.read_text()
+    head = text.splitlines()[0]
+    m = re.match(r"#! convfwd-cache device=(\S+) registry=([0-9a-f]{16})$", head)
+    assert m, head
+    B.conv_cache_clear()
+    B.conv_cache_load(str(out))                      # its own file loads
+    assert B.conv_variant_name(d, -1) == other
+    B.conv_cache_clear()
+    default = B.conv_variant_name(d, -1)
+    # another set of kernels: refused, cache untouched
+    reg = m.group(2)
+    wrong = tmp_path / "wrong_registry.txt"
+    wrong.write_text(text.replace(reg, ("0" if reg[0] != "0" else "1") + reg[1:]))
+    with pytest.raises(B.ConvError) as e:
+        B.conv_cache_load(str(wrong))
+    assert e.value.status == B.CONV_EIO and B.conv_variant_name(d, -1) == default
+    # a malformed identity line: refused
+    wrong.write_text("#! convfwd-cache device=x\n" + "\n".join(text.splitlines()[1:]) + "\n")
+    with pytest.raises(B.ConvError):
+        B.conv_cache_load(str(wrong))
+    # another device: refused when this host knows its own device; a host without a GPU ("none") accepts any
+    wrong.write_text(text.replace("device=" + m.group(1), "device=gfx000/Other_Device/1cu"))
+    if m.group(1) == "none":
+        B.conv_cache_load(str(wrong))
+    else:
+        with pytest.raises(B.ConvError):
+            B.conv_cache_load(str(wrong))
+    B.conv_cache_clear()
