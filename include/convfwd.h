@@ -68,7 +68,9 @@ enum {
      * OH*OW <= 192 for 3x3 and 5x5 windows, <= 768 for 5x5 channel-innermost; fp32: 3x3 windows, OH*OW <= 208, planar
      * tensors); other descriptors give CONV_ENOVARIANT and the caller
      * runs maxpool_fwd() behind the convolution.  The result is bit-identical to that sequence run with the same
-     * variant.  Not combinable with CONV_FLAG_FILT_WINOGRAD. */
+     * variant, NaN sums included (with the activation they become 0 before the pool, as in the sequence; without it a
+     * NaN in the window is the result); only the sign of a zero result can differ when the activation is the identity.
+     * Not combinable with CONV_FLAG_FILT_WINOGRAD. */
     CONV_FLAG_MAXPOOL_3X3S2 = 32u,
     /* Filters handed over in the order the 16-bit matrix instructions consume them, as written by
      * conv_transform_filters() for the same descriptor with this bit set: the other ahead-of-time filter conversion
@@ -243,7 +245,9 @@ int conv_coop_load_plan(int threads, int words, int* loads_per_thread, int* last
  * Per-channel spatial max-pool, window win x win, stride `stride`, no padding,
  * OH = floor((H-win)/stride)+1 (the glue between layers of a convolution stack;
  * paper, Section 2).  in [N][C][H][W] -> out [N][C][OH][OW], element type
- * `dtype`, device pointers, asynchronous on `stream`.
+ * `dtype`, device pointers, asynchronous on `stream`.  On every path (either layout, and the pool fused into a
+ * convolution without activation) the window is scanned row by row, the first of equal values is kept (so the sign
+ * of a zero is that of the first zero) and a NaN anywhere in the window is the result.
  */
 int maxpool_fwd(int32_t N, int32_t C, int32_t H, int32_t W, int32_t win, int32_t stride, int32_t dtype,
                 const void* in, void* out, void* stream);

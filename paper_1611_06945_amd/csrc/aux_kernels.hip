@@ -112,7 +112,7 @@ __global__ __launch_bounds__(256) void maxpool_kernel(const typename Prec<DT>::e
 #pragma unroll
         for (int t = 1; t < WIN * WIN; ++t) {
             const float vf = Prec<DT>::to_f32(v[t]);
-            if (vf > bestf) {
+            if (vf > bestf || vf != vf) {  // a NaN anywhere in the window is the window's result
                 bestf = vf;
                 best = v[t];
             }
@@ -122,7 +122,7 @@ __global__ __launch_bounds__(256) void maxpool_kernel(const typename Prec<DT>::e
             for (int s = 0; s < win; ++s) {
                 const elem_t v = src[r * sy + s * sx];
                 const float vf = Prec<DT>::to_f32(v);
-                if (vf > bestf) {
+                if (vf > bestf || vf != vf) {
                     bestf = vf;
                     best = v;
                 }
@@ -155,7 +155,9 @@ __global__ __launch_bounds__(256) void maxpool_nhwc8_kernel(const uint16_t* __re
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
             const uint16_t h = (uint16_t)(e & 1 ? w[e >> 1] >> 16 : w[e >> 1] & 0xFFFFu);
-            best[e] = __builtin_fmaxf(best[e], Prec<DT>::to_f32(h));
+            // the rule of every pooling path: the first of equal values stays (so -0 before +0 stays -0), a NaN sticks
+            const float x = Prec<DT>::to_f32(h);
+            best[e] = (x > best[e] || x != x) ? x : best[e];
         }
     };
     if constexpr (WIN > 0) {
@@ -211,7 +213,7 @@ __global__ __launch_bounds__(256) void maxpool_xlayout_kernel(const typename Pre
 #pragma unroll
                 for (int t = 1; t < WIN * WIN; ++t) {
                     const float vf = Prec<DT>::to_f32(v[t]);
-                    if (vf > bestf) {
+                    if (vf > bestf || vf != vf) {
                         bestf = vf;
                         best = v[t];
                     }
@@ -221,7 +223,7 @@ __global__ __launch_bounds__(256) void maxpool_xlayout_kernel(const typename Pre
                     for (int s = 0; s < win; ++s) {
                         const elem_t v = src[r * sy + s * sx];
                         const float vf = Prec<DT>::to_f32(v);
-                        if (vf > bestf) {
+                        if (vf > bestf || vf != vf) {
                             bestf = vf;
                             best = v;
                         }
@@ -274,7 +276,8 @@ hipError_t launch_maxpool_typed(int N, int C, int H, int W, int win, int stride,
     const size_t total = (size_t)N * C * OH * OW;
     const FastDiv dOHW = make_fastdiv((uint32_t)(OH * OW)), dOW = make_fastdiv((uint32_t)OW), dC = make_fastdiv((uint32_t)C);
     if constexpr (DT != CONV_F32) {
-        if (in_nhwc && out_nhwc && (C % 8) == 0 && total / 8 < (1u << 31)) {
+        const bool aligned = ((((uintptr_t)in) | ((uintptr_t)out)) & 15u) == 0;  // its 16-byte loads and stores
+        if (in_nhwc && out_nhwc && (C % 8) == 0 && aligned && total / 8 < (1u << 31)) {
             const FastDiv dC8 = make_fastdiv((uint32_t)(C / 8));
             dim3 grid8((unsigned)((total / 8 + 255) / 256));
             hipLaunchKernelGGL((maxpool_nhwc8_kernel<DT, WIN>), grid8, dim3(256), 0, s, (const uint16_t*)in, (uint16_t*)out, N, C,

@@ -355,7 +355,7 @@ __global__ __launch_bounds__(CFG::NT) void wconv16_kernel(ConvArgs a)
                             float x = red[idx];
 #pragma unroll
                             for (int q = 1; q < KW; ++q) x += red[q * 32 * TNP + idx];
-                            m = x > m ? x : m;
+                            m = (x > m || (!a.relu && x != x)) ? x : m;  // NaN: dropped by the activation, else it is the result
                         }
                     const bool ok = k < a.K;
                     m += buffer_load_elem<float>(rbias, ok ? (uint32_t)k * 4u : kOutOfRange);

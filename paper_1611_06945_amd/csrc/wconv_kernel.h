@@ -266,7 +266,7 @@ void wconv_kernel(ConvArgs a)
                         x += red[16 * TNP + idx];
                         x += red[32 * TNP + idx];
                         x += red[48 * TNP + idx];
-                        m = x > m ? x : m;
+                        m = (x > m || (!a.relu && x != x)) ? x : m;  // NaN: dropped by the activation, else it is the result
                     }
                 const bool ok = k < a.K;
                 m += buffer_load_elem<float>(rbias, ok ? (uint32_t)k * 4u : kOutOfRange);

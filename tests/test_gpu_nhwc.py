@@ -141,3 +141,64 @@ def test_layout_flags_without_a_kernel_are_refused():
     assert B.conv_variant_count(d) == 0
     d = B.desc_of(ConvShape(1, 16, 8, 8, 16, 3, 3, 1, 1), wl.F16, in_nhwc=True)  # filters still [K][C][R][S]
     assert B.conv_variant_count(d) == 0
+
+
+def _pool_rule(x, win, stride):
+    """The pooling rule the library documents, written out: scan the window row by row, keep the first of equal values
+    (so the sign of a zero result is that of the first zero), and let a NaN anywhere in the window be the result."""
+    N, C, H, W = x.shape
+    OH, OW = (H - win) // stride + 1, (W - win) // stride + 1
+    out = np.empty((N, C, OH, OW), dtype=x.dtype)
+    for n in range(N):
+        for c in range(C):
+            for oy in range(OH):
+                for ox in range(OW):
+                    m = x[n, c, oy * stride, ox * stride]
+                    for r in range(win):
+                        for s in range(win):
+                            v = x[n, c, oy * stride + r, ox * stride + s]
+                            if v > m or v != v:
+                                m = v
+                    out[n, c, oy, ox] = m
+    return out
+
+
+@pytest.mark.parametrize("dtype", [wl.F32, wl.F16, wl.BF16])
+def test_maxpool_nan_and_signed_zero_on_every_path(dtype):
+    # NaN in a tap that is not the window's first, and windows whose maximum is a zero met first as -0 or first as +0:
+    # every pooling kernel (planar, channel-innermost 8 channels at a time, the two converting ones) must follow one rule
+    torch = torch_mod()
+    N, C, H, W = 2, 16, 9, 9
+    x = -np.abs(wl.draw(("normal", 1.0), (N, C, H, W), 21)).astype(np.float32) - 0.5   # all negative: zeros are maxima
+    x[0, :, 1, 1] = np.nan          # inside window (0,0) at tap (1,1); also tap (1,1)->(1,?)... of no other stride-2 window start
+    x[0, :, 4, 6] = -0.0            # window (1,2) (rows 2-4, cols 4-6) and (2,2), (1,3), (2,3): -0 met first
+    x[0, :, 4, 7] = 0.0
+    x[1, :, 2, 2] = 0.0             # window (0,0) and (0,1), (1,0), (1,1) of image 1: +0 met first
+    x[1, :, 2, 3] = -0.0
+    x[1, :, 6, 5] = np.nan          # last tap of window (2,... ) rows 4-6
+    stored = wl.to_storage(x, dtype)
+    as_f = wl.storage_to_f64(stored, dtype)
+    want = _pool_rule(as_f, 3, 2)
+    assert np.isnan(want[0, 0, 0, 0]) and np.signbit(want[0, 0, 1, 2]) and not np.signbit(want[1, 0, 0, 0])
+    for in_nhwc in (False, True):
+        for out_nhwc in (False, True):
+            src = to_device(nhwc(stored) if in_nhwc else stored, dtype)
+            oshape = want.shape if not out_nhwc else (N, want.shape[2], want.shape[3], C)
+            out = empty_out(oshape, dtype)
+            B.maxpool_fwd_layout(N, C, H, W, 3, 2, dtype, in_nhwc, out_nhwc, src, out)
+            torch.cuda.synchronize()
+            got = to_host_f64(out, dtype)
+            got = nchw(got) if out_nhwc else got
+            assert np.array_equal(np.isnan(got), np.isnan(want)), (in_nhwc, out_nhwc)
+            ok = ~np.isnan(want)
+            assert np.array_equal(got[ok], want[ok]) and np.array_equal(np.signbit(got[ok]), np.signbit(want[ok])), (in_nhwc, out_nhwc)
+    # a channel-innermost tensor that is not 16-byte aligned takes the element-wise kernel instead of the 16-byte one
+    if dtype != wl.F32:
+        base = torch.zeros(N * H * W * C + 8, dtype=torch.int16, device="cuda")
+        view = base[4:4 + N * H * W * C]   # 8 bytes past a 16-byte boundary
+        view.copy_(to_device(nhwc(stored), dtype).view(torch.int16).reshape(-1))
+        out = empty_out((N, want.shape[2], want.shape[3], C), dtype)
+        B.maxpool_fwd_layout(N, C, H, W, 3, 2, dtype, True, True, view, out)
+        torch.cuda.synchronize()
+        got = nchw(to_host_f64(out, dtype))
+        assert np.array_equal(got, want, equal_nan=True)

@@ -176,3 +176,40 @@ def test_fused_maxpool_fp32_every_variant(si):
             else:
                 err = oracle.max_normalised_error(got.astype(np.float64), want)
                 assert err <= TOL[dtype], "%s: error %.3g" % (name, err)
+
+
+@pytest.mark.parametrize("relu", [True, False])
+@pytest.mark.parametrize("dtype", [wl.F32, wl.F16])
+def test_fused_maxpool_matches_the_sequence_on_nan_sums(dtype, relu):
+    # a NaN in the input makes every convolution sum whose window holds it a NaN.  With the activation those become 0
+    # before the pool in the two-call sequence; without it the NaN is the pooled result.  The fused call must agree.
+    torch = torch_mod()
+    shape = ConvShape(2, 32, 13, 13, 32, 3, 3, 1, 1)
+    data = data_for(shape, dtype, 3900, False)
+    x = wl.storage_to_f64(data["in"], dtype).astype(np.float32)
+    x[0, 3, 6, 6] = np.nan
+    x[1, 0, 0, 12] = np.nan
+    data["in"] = wl.to_storage(x, dtype)
+    PH, PW = (shape.OH - 3) // 2 + 1, (shape.OW - 3) // 2 + 1
+    layouts = [(False, False)] if dtype == wl.F32 else [(False, False), (True, True), (True, False)]
+    for in_nhwc, out_nhwc in layouts:
+        d_in = to_device(nhwc(data["in"]) if in_nhwc else data["in"], dtype)
+        d_filt = to_device(nhwc(data["filt"]) if in_nhwc else data["filt"], dtype)
+        d_bias = to_device(data["bias"], wl.F32)
+        kw = dict(relu=relu, in_nhwc=in_nhwc, out_nhwc=out_nhwc, filt_krsc=in_nhwc)
+        fused, plain = B.desc_of(shape, dtype, maxpool=True, **kw), B.desc_of(shape, dtype, **kw)
+        names = [B.conv_variant_name(fused, i) for i in range(B.conv_variant_count(fused))]
+        plain_names = [B.conv_variant_name(plain, i) for i in range(B.conv_variant_count(plain))]
+        assert names
+        oshape = (shape.N, PH, PW, shape.K) if out_nhwc else (shape.N, shape.K, PH, PW)
+        for vi, name in enumerate(names):
+            say("  %s relu=%s in_nhwc=%s out_nhwc=%s" % (name, relu, in_nhwc, out_nhwc))
+            out = run(fused, d_in, d_filt, d_bias, oshape, dtype, vi)
+            full = run(plain, d_in, d_filt, d_bias,
+                       (shape.N, shape.OH, shape.OW, shape.K) if out_nhwc else shape.out_shape(), dtype, plain_names.index(name))
+            seq = empty_out(oshape, dtype)
+            B.maxpool_fwd_layout(shape.N, shape.K, shape.OH, shape.OW, 3, 2, dtype, out_nhwc, out_nhwc, full, seq)
+            torch.cuda.synchronize()
+            got, want = to_host_f64(out, dtype), to_host_f64(seq, dtype)
+            assert np.isnan(want).any() != relu, "the sequence's own NaN handling is not what this test assumes"
+            assert np.array_equal(got, want, equal_nan=True), "%s: differs from conv + maxpool" % name
