@@ -549,6 +549,8 @@ def main():
         return
 
     table = {w.name: w for w in all_workloads()}
+    for code in (wl.F32, wl.F16, wl.BF16):   # the rows of the paper's Appendix A at batch 5, for profiling single operations
+        table.update({w.name: w for w in wl.appendix_a(5, code)})
     if a.workload not in table:
         log("unknown workload %r; choose from %s" % (a.workload, sorted(table)))
         sys.exit(2)

@@ -17,7 +17,9 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "conv_oracle.c")
-_LIB = os.path.join(_HERE, "liboracle_conv.so")
+# ORACLE_CONV_LIB names another build of the same source to load instead (the sanitizer job of the test suite)
+_LIB_OVERRIDE = os.environ.get("ORACLE_CONV_LIB")
+_LIB = _LIB_OVERRIDE or os.path.join(_HERE, "liboracle_conv.so")
 _lock = threading.Lock()
 _lib = None
 
@@ -27,6 +29,8 @@ _c_int64_p = ctypes.POINTER(ctypes.c_int64)
 
 def build(force: bool = False) -> str:
     """Compile ``conv_oracle.c`` into ``liboracle_conv.so`` (gcc -O2 -fopenmp)."""
+    if _LIB_OVERRIDE:
+        return _LIB
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
         tmp = _LIB + ".tmp.%d" % os.getpid()
         subprocess.check_call(

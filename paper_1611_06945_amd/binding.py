@@ -15,7 +15,8 @@ import os
 from typing import Optional, Tuple
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_PKG, "libconvfwd.so")
+# CONVFWD_LIB names another build of the library to load instead (the sanitizer job of the test suite)
+LIB_PATH = os.environ.get("CONVFWD_LIB") or os.path.join(_PKG, "libconvfwd.so")
 
 CONV_F32, CONV_F16, CONV_BF16 = 0, 1, 2
 CONV_FLAG_RELU, CONV_FLAG_IN_NHWC, CONV_FLAG_OUT_NHWC, CONV_FLAG_FILT_KRSC, CONV_FLAG_FILT_WINOGRAD = 1, 2, 4, 8, 16
