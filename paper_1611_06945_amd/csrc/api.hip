@@ -247,6 +247,8 @@ double heuristic_cost(const Variant& v, const conv_desc& d, int OH, int OW)
     const double sharing = std::min(wg_per_cu, std::max(1.0, tiles / 256.0));
     double t = 4.0 + rounds * steps * t_step * std::pow(sharing, 0.4);
     if (v.split > 1) t += 2.0 + (double)v.split * d.K * P * 4.0 / 2.0e6;
+    // a conversion launch ahead of the kernel: its launch plus input and filters read and written once
+    if (v.traits & TRAIT_CONVERTS_FIRST) t += 3.0 + 2.0 * ((double)d.N * d.C * d.H * d.W + (double)d.K * Q) * 2.0 / 2.0e6;
     return t * (1.0 - 0.002 * v.specificity);  // ties go to the kernel written for the narrower class of shapes
 }
 

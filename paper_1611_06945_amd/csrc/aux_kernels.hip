@@ -357,6 +357,67 @@ __global__ __launch_bounds__(256) void pack_filters16_kernel(const uint16_t* __r
     out[v] = make_uint4(w[0], w[1], w[2], w[3]);
 }
 
+// Both conversions a packed-filter kernel needs when it serves a layer handed over in the plain formats, in ONE launch
+// ahead of it: blocks [0, in_blocks) transpose the input [N][C][HW] -> [N][HW][C] (32 x 32 tiles through LDS), the
+// remaining blocks write the filters in MFMA operand order (as pack_filters16_kernel).
+__global__ __launch_bounds__(256) void prep16_kernel(const uint16_t* __restrict__ in, uint16_t* __restrict__ in_out, int C, int HW,
+                                                    int tiles_s, int tiles_c, int in_blocks, const uint16_t* __restrict__ filt,
+                                                    uint4* __restrict__ filt_out, int K, int RS, int nvec)
+{
+    __shared__ uint16_t tile[32][33];
+    const int b = blockIdx.x;
+    if (b < in_blocks) {
+        const int per_img = tiles_s * tiles_c;
+        const int a = b / per_img, rem = b - a * per_img;
+        const int b0 = (rem / tiles_s) * 32, s0 = (rem % tiles_s) * 32;
+        const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+        const uint16_t* src = in + (size_t)a * C * HW;
+        uint16_t* dst = in_out + (size_t)a * C * HW;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int c = b0 + ty + 8 * j, sidx = s0 + tx;
+            if (c < C && sidx < HW) tile[ty + 8 * j][tx] = src[(size_t)c * HW + sidx];
+        }
+        __syncthreads();
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int sidx = s0 + ty + 8 * j, c = b0 + tx;
+            if (c < C && sidx < HW) dst[(size_t)sidx * C + c] = tile[tx][ty + 8 * j];
+        }
+        return;
+    }
+    const int v = (b - in_blocks) * 256 + threadIdx.x;
+    if (v >= nvec) return;
+    const int m = v & 31, g = (v >> 5) & 1;
+    int rest = v >> 6;
+    const int t = rest % RS;
+    rest /= RS;
+    const int C16 = C >> 4, c16 = rest % C16, rb = rest / C16;
+    const int k = rb * 32 + m, c = c16 * 16 + g * 8;
+    uint32_t w[4] = {0, 0, 0, 0};
+    if (k < K) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const uint32_t h = filt[((size_t)k * C + c + j) * RS + t];
+            w[j >> 1] |= h << ((j & 1) * 16);
+        }
+    }
+    filt_out[v] = make_uint4(w[0], w[1], w[2], w[3]);
+}
+
+hipError_t launch_prep16(const void* in, void* in_out, int N, int C, int HW, const void* filt, void* filt_out, int K, int RS,
+                         hipStream_t s)
+{
+    const int tiles_s = (HW + 31) / 32, tiles_c = (C + 31) / 32;
+    const long long in_blocks = (long long)N * tiles_s * tiles_c;
+    const long long nvec = (long long)((K + 31) / 32) * 32 * (C / 16) * RS * 2;
+    const long long blocks = in_blocks + (nvec + 255) / 256;
+    if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(prep16_kernel, dim3((unsigned)blocks), dim3(256), 0, s, (const uint16_t*)in, (uint16_t*)in_out, C, HW,
+                       tiles_s, tiles_c, (int)in_blocks, (const uint16_t*)filt, (uint4*)filt_out, K, RS, (int)nvec);
+    return hipGetLastError();
+}
+
 hipError_t launch_pack_filters16(const void* filt, void* out, int K, int C, int RS, hipStream_t s)
 {
     const long long nvec = (long long)((K + 31) / 32) * 32 * (C / 16) * RS * 2;

@@ -117,7 +117,8 @@ enum { TRAIT_SCALAR_LOADS = 1u,  // filter tile fetched element by element (no a
        TRAIT_PLANAR_TO_NHWC = 32u,    // reads [N][C][H][W] and [K][C][R][S], can write [N][OH][OW][K] (CONV_FLAG_OUT_NHWC alone)
        TRAIT_FILTERS_IN_KERNEL = 64u,  // Winograd: the filter transform runs inside the product kernel
        TRAIT_POOL_EPILOGUE = 128u,     // can max-pool its output tile before the store (CONV_FLAG_MAXPOOL_3X3S2)
-       TRAIT_PACKED_FILTERS = 256u };  // reads filters in MFMA operand order (CONV_FLAG_FILT_PACKED); checks the tensor formats itself
+       TRAIT_PACKED_FILTERS = 256u,    // reads filters in MFMA operand order (CONV_FLAG_FILT_PACKED); checks the tensor formats itself
+       TRAIT_CONVERTS_FIRST = 512u };  // serves the plain formats by converting input and filters into the workspace first
 
 enum { FAM_IGEMM = 0, FAM_POINTWISE = 1, FAM_FIRSTLAYER = 2, FAM_WINDOW = 3, FAM_FC = 4, FAM_NHWC = 5, FAM_WINOGRAD = 6 };
 
@@ -156,6 +157,9 @@ hipError_t launch_transpose(int A, int B, int S, int esize, const void* in, void
 hipError_t launch_wino_filter_transform(const float* filt, float* out, int K, int C, hipStream_t s);
 size_t wino_transformed_filter_bytes(int K, int C);
 // KCRS 16-bit filters -> MFMA operand order of the packed-filter kernels (aux_kernels.hip); C % 16 == 0
+// input [N][C][HW] -> [N][HW][C] and filters -> MFMA operand order in one launch (aux_kernels.hip); C % 16 == 0
+hipError_t launch_prep16(const void* in, void* in_out, int N, int C, int HW, const void* filt, void* filt_out, int K, int RS,
+                         hipStream_t s);
 hipError_t launch_pack_filters16(const void* filt, void* out, int K, int C, int RS, hipStream_t s);
 
 // max_i |got_i - ref_i| / max(max_j |ref_j|, 1e-30) of two device tensors of `n` elements (infinity when `got` holds a

@@ -403,12 +403,45 @@ hipError_t pwin_launch(const Variant&, ConvArgs& a, hipStream_t s)
     return hipGetLastError();
 }
 
+// The same kernel behind one conversion launch, for layers handed over in the plain formats ([N][C][H][W], [K][C][R][S]):
+// the workspace receives the channel-innermost input and the packed filters, the kernel reads those and writes the
+// output in the plain format.  Costs a launch and the conversion traffic; pays where the planar window kernels are far
+// from the packed kernel's speed (5x5 layers, small batches).
+inline size_t pwin_prep_in_bytes(const conv_desc& d) { return (((size_t)d.N * d.C * d.H * d.W * 2) + 255) & ~(size_t)255; }
+
 template <class CFG>
+size_t pwin_prep_workspace(const Variant&, const conv_desc& d, int, int)
+{
+    return pwin_prep_in_bytes(d) + packed_filter_bytes(d.K, d.C, CFG::RS);
+}
+
+template <class CFG>
+hipError_t pwin_prep_launch(const Variant& v, ConvArgs& a, hipStream_t s)
+{
+    conv_desc d{};
+    d.N = a.N; d.C = a.C; d.H = a.H; d.W = a.W; d.K = a.K;
+    unsigned char* ws = (unsigned char*)a.ws;
+    void* ws_in = ws;
+    void* ws_filt = ws + pwin_prep_in_bytes(d);
+    const hipError_t e = launch_prep16(a.in, ws_in, a.N, a.C, a.HW, a.filt, ws_filt, a.K, a.RS, s);
+    if (e != hipSuccess) return e;
+    ConvArgs b = a;
+    b.in = ws_in;
+    b.filt = ws_filt;
+    return pwin_launch<CFG>(v, b, s);
+}
+
+template <class CFG, bool PREP = false>
 bool pwin_valid(const Variant&, const conv_desc& d, int OH, int OW)
 {
     if (d.dtype != CFG::DT || d.R != CFG::R || d.S != CFG::S || d.stride != 1) return false;
-    const uint32_t fmt = d.flags & (CONV_FLAG_IN_NHWC | CONV_FLAG_FILT_KRSC | CONV_FLAG_FILT_PACKED | CONV_FLAG_FILT_WINOGRAD);
-    if (fmt != (CONV_FLAG_IN_NHWC | CONV_FLAG_FILT_PACKED)) return false;
+    const uint32_t fmt = d.flags & (CONV_FLAG_IN_NHWC | CONV_FLAG_FILT_KRSC | CONV_FLAG_FILT_PACKED | CONV_FLAG_FILT_WINOGRAD |
+                                    CONV_FLAG_OUT_NHWC);
+    if (PREP) {
+        if (fmt != 0) return false;  // plain formats in and out
+    } else if ((fmt & ~CONV_FLAG_OUT_NHWC) != (CONV_FLAG_IN_NHWC | CONV_FLAG_FILT_PACKED)) {
+        return false;
+    }
     if (d.flags & CONV_FLAG_MAXPOOL_3X3S2) return false;
     if ((d.C % CFG::CB) != 0) return false;
     if ((d.flags & CONV_FLAG_OUT_NHWC) && (d.K % 8) != 0) return false;
@@ -442,6 +475,15 @@ void pwin_register(std::vector<Variant>& out)
     v.traits = TRAIT_PACKED_FILTERS;
     v.valid = &pwin_valid<CFG>;
     v.launch = &pwin_launch<CFG>;
+    out.push_back(v);
+    // the twin for the plain formats: one conversion launch into the workspace, then the same kernel
+    v.name += "_prep";
+    v.family = FAM_WINDOW;
+    v.specificity = 4;
+    v.traits = TRAIT_CONVERTS_FIRST;
+    v.valid = &pwin_valid<CFG, true>;
+    v.launch = &pwin_prep_launch<CFG>;
+    v.ws_extra = &pwin_prep_workspace<CFG>;
     out.push_back(v);
 }
 
