@@ -57,7 +57,7 @@ struct PwinCfg {
     static constexpr int RB = ((size_t)KW * TNP * (TM + 4) * 4 <= 160 * 1024) ? TM : 32;
     static constexpr int RBP = RB + 4;
     static constexpr size_t LDS_PIPE = 2 * sizeof(uint16_t) * (size_t)SLAB_ELEMS;
-    static constexpr size_t LDS_RED = sizeof(float) * (size_t)KW * TNP * RBP;
+    static constexpr size_t LDS_RED = sizeof(float) * ((size_t)KW * TNP * RBP + RB);  // partial tiles + the bias values of the pass
     static constexpr size_t LDS_BYTES = LDS_PIPE > LDS_RED ? LDS_PIPE : LDS_RED;
     static_assert(LDS_BYTES <= 160 * 1024, "LDS budget");
 };
@@ -323,6 +323,10 @@ __global__ __launch_bounds__(CFG::NT) void pwin_kernel(ConvArgs a)
                     *(f32x4*)&dst[8 * i] = f32x4{c[4 * i], c[4 * i + 1], c[4 * i + 2], c[4 * i + 3]};
                 }
             }
+        if (!onhwc && tid < RB) {
+            const int kb = m0 + rd * RB + tid;
+            red[KW * TNP * RBP + tid] = buffer_load_elem<float>(rbias, kb < a.K ? (uint32_t)kb * 4u : kOutOfRange);
+        }
         __syncthreads();
         if (onhwc) {
             // a thread takes 8 consecutive channels of one pixel: two 16-byte LDS reads per partial sum, one 16-byte store
@@ -355,28 +359,39 @@ __global__ __launch_bounds__(CFG::NT) void pwin_kernel(ConvArgs a)
                 __builtin_amdgcn_raw_buffer_store_b128(vv, rout, ok ? (int)((uint32_t)(p * a.K + k) * 2u) : (int)kOutOfRange, 0, 0);
             }
         } else {
-            // a thread takes 4 consecutive channels of one pixel, consecutive threads consecutive pixels: 16-byte LDS
-            // reads, four 2-byte stores that each fall into a run of consecutive pixels of one channel plane
-            constexpr int RG = RB / 4, NE = (RG * TNP + NT - 1) / NT;
+            // a thread keeps one pixel and walks down the channels four at a time (16-byte LDS reads); consecutive
+            // threads hold consecutive pixels, so each of its 2-byte stores falls into a 128-byte run of one channel
+            // plane.  The pixel's image and offset are worked out once; from one group of channels to the next the
+            // output offset moves by a constant.
+            constexpr int RG = RB / 4;
+            constexpr int CPT = NT / TNP > 0 ? NT / TNP : 1;           // channel groups handled side by side
+            constexpr int COLS = NT / TNP > 0 ? 1 : (TNP + NT - 1) / NT;  // pixels per thread when the tile is wider than the workgroup
+            const float* bsm = &red[KW * TNP * RBP];
 #pragma unroll
-            for (int j = 0; j < NE; ++j) {
-                const int e = j * NT + tid;
-                const int rg = e / TNP, col = e % TNP;
-                const int k = m0 + rd * RB + rg * 4, p = p0 + col;
-                const bool ok = e < RG * TNP && p < a.P;
-                const float* src = &red[(ok ? col : 0) * RBP + (ok ? rg : 0) * 4];
-                f32x4 x = *(const f32x4*)&src[0];
-#pragma unroll
-                for (int q = 1; q < KW; ++q) x += *(const f32x4*)&src[q * TNP * RBP];
+            for (int cc = 0; cc < COLS; ++cc) {
+                const int col = (NT / TNP > 0 ? tid % TNP : tid + cc * NT), rg0 = NT / TNP > 0 ? tid / TNP : 0;
+                const int p = p0 + col;
+                const bool pok = col < TNP && rg0 < CPT && p < a.P;
                 uint32_t n, pix;
-                a.dOHW.divmod((uint32_t)(ok ? p : 0), n, pix);
+                a.dOHW.divmod((uint32_t)(pok ? p : 0), n, pix);
+                const int kbase = m0 + rd * RB;
+                uint32_t o = (uint32_t)(((int)n * a.K + kbase + rg0 * 4) * a.OHW + (int)pix) * 2u;
+                const uint32_t ostep = (uint32_t)a.OHW * 2u;
+                const float* src = &red[(pok ? col : 0) * RBP];
+#pragma unroll 4
+                for (int rg = rg0; rg < RG; rg += CPT) {
+                    f32x4 x = *(const f32x4*)&src[rg * 4];
 #pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    const bool oki = ok && k + i < a.K;
-                    float y = x[i] + buffer_load_elem<float>(rbias, oki ? (uint32_t)(k + i) * 4u : kOutOfRange);
-                    if (a.relu) y = y > 0.0f ? y : 0.0f;
-                    const uint32_t o = (uint32_t)(((int)n * a.K + k + i) * a.OHW + (int)pix);
-                    buffer_store_elem<elem_t>(Prec<DT>::from_f32(y), rout, oki ? o * 2u : kOutOfRange);
+                    for (int q = 1; q < KW; ++q) x += *(const f32x4*)&src[q * TNP * RBP + rg * 4];
+                    const f32x4 bv = *(const f32x4*)&bsm[rg * 4];
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        float y = x[i] + bv[i];
+                        if (a.relu) y = y > 0.0f ? y : 0.0f;
+                        const bool oki = pok && kbase + rg * 4 + i < a.K;
+                        buffer_store_elem<elem_t>(Prec<DT>::from_f32(y), rout, oki ? o + (uint32_t)i * ostep : kOutOfRange);
+                    }
+                    o += 4u * CPT * ostep;
                 }
             }
         }
