@@ -4,7 +4,7 @@
 namespace convfwd {
 
 //                                     DT       R  S  KW WN TMB NBW AD LBT
-#define PW(R, S, KW, WN, TMB, NBW, AD, LBT) PwinCfg<CONV_F16, R, S, KW, WN, TMB, NBW, AD, LBT>
+#define PW(...) PwinCfg<CONV_F16, __VA_ARGS__>
 
 void register_pwin_f16(std::vector<Variant>& out)
 {
@@ -19,6 +19,8 @@ void register_pwin_f16(std::vector<Variant>& out)
     // 5x5
     pwin_register<PW(5, 5, 2, 2, 2, 4, 5, 9)>(out);  // M64 N256 C32, 4 waves: 64x128 wave tiles, 576 slab positions
     pwin_register<PW(5, 5, 2, 2, 2, 3, 5, 8)>(out);  // M64 N192 C32, 4 waves
+    pwin_register<PW(5, 5, 2, 2, 2, 4, 5, 10, true)>(out);  // M64 N256 C32 with the conflict-free row pitch
+    pwin_register<PW(5, 5, 2, 2, 2, 2, 5, 6)>(out);         // M64 N128 C32, 4 waves: small enough for two workgroups per CU
 }
 
 }  // namespace convfwd

@@ -36,10 +36,15 @@
 
 namespace convfwd {
 
-template <int DT_, int R_, int S_, int KW_, int WN_, int TMB_, int NBW_, int AD_, int LBT_>
+template <int DT_, int R_, int S_, int KW_, int WN_, int TMB_, int NBW_, int AD_, int LBT_, bool ALIGN8_ = false>
 struct PwinCfg {
     static_assert(DT_ == CONV_F16 || DT_ == CONV_BF16, "16-bit storage only");
     static constexpr int DT = DT_, R = R_, S = S_, KW = KW_, WN = WN_, TMB = TMB_, NBW = NBW_, AD = AD_, LBT = LBT_;
+    // ALIGN8: widen the slab's row pitch until it equals the output row length modulo 8.  Eight lanes' 16-byte reads are
+    // served per cycle and fall on distinct banks when their positions differ modulo 8; consecutive pixels are
+    // consecutive positions except across a row end, where the pitch minus the row length is skipped -- a multiple of 8
+    // keeps every read conflict free, at the price of more (zero) positions to stage.
+    static constexpr bool ALIGN8 = ALIGN8_;
     static constexpr int RS = R * S;
     static_assert(RS % AD == 0, "the filter-fragment ring must divide the taps of a chunk");
     static constexpr int NT = 64 * KW * WN;
@@ -86,6 +91,7 @@ inline PwinGeom pwin_geom(int N, int H, int W, int K, int pad, int OH, int OW)
 {
     PwinGeom g;
     g.PWs = W + pad;
+    if (CFG::ALIGN8) g.PWs += (((OW - g.PWs) % 8) + 8) % 8;
     g.PHs = H + pad;
     const long long P = (long long)N * OH * OW;
     g.PT = (int)((P + CFG::TNP - 1) / CFG::TNP);
@@ -122,7 +128,7 @@ __global__ __launch_bounds__(CFG::NT) void pwin_kernel(ConvArgs a)
 #endif
 
     // ---- which tile: ids b, b+8, b+16, ... run on one XCD; give each XCD a contiguous run of logical tiles ---------
-    const int PT = (int)a.dX.d, PWs = a.W + a.pad, PHs = a.H + a.pad;
+    const int PT = (int)a.dX.d, PWs = (int)a.dY.d, PHs = (int)a.dZ.d;
     const int MT = (a.K + TM - 1) / TM;
     const int T = MT * PT;
     int logical;
@@ -176,7 +182,7 @@ __global__ __launch_bounds__(CFG::NT) void pwin_kernel(ConvArgs a)
         uint32_t Y, X, n, yy;
         a.dY.divmod((uint32_t)(lo + j), Y, X);
         a.dZ.divmod(Y, n, yy);
-        const bool ok = j < nposw && (int)X >= a.pad && (int)yy >= a.pad && (int)n < a.N;
+        const bool ok = j < nposw && (int)X >= a.pad && (int)X < a.pad + a.W && (int)yy >= a.pad && (int)n < a.N;
         t_goff[i] = ok ? (uint32_t)((((int)n * a.H + (int)yy - a.pad) * a.W + (int)X - a.pad) * a.C + v8 * 8) * 2u : kOutOfRange;
     }
     uint4 b_reg[LBT];
@@ -476,8 +482,8 @@ void pwin_register(std::vector<Variant>& out)
 {
     Variant v;
     char buf[160];
-    snprintf(buf, sizeof buf, "pwin_%s_%dx%d_M%dN%dC%d_w%dx%d_a%d", dtype_name(CFG::DT), CFG::R, CFG::S, CFG::TM, CFG::TNP,
-             CFG::CB, CFG::KW, CFG::WN, CFG::AD);
+    snprintf(buf, sizeof buf, "pwin_%s_%dx%d_M%dN%dC%d_w%dx%d_a%d%s", dtype_name(CFG::DT), CFG::R, CFG::S, CFG::TM, CFG::TNP,
+             CFG::CB, CFG::KW, CFG::WN, CFG::AD, CFG::ALIGN8 ? "_p8" : "");
     v.name = buf;
     v.dtype = CFG::DT;
     v.split = 1;
