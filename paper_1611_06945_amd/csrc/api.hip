@@ -69,6 +69,7 @@ State& state()
         register_swin_bf16(s->variants);
         register_wconv_f16(s->variants);
         register_wconv_bf16(s->variants);
+        register_pwk_f32(s->variants);
         register_pwin_f16(s->variants);
         register_pwin_bf16(s->variants);
         for (size_t i = 0; i < s->variants.size(); ++i) s->by_name[s->variants[i].name] = (int)i;
@@ -225,6 +226,16 @@ double heuristic_cost(const Variant& v, const conv_desc& d, int OH, int OW)
         const double wgs = std::max(1.0, std::min(std::floor(256.0 / ktiles), tiles));
         const double per_tile = 1.3 + (0.5 + 0.0156 * v.tm) * v.tk / 416.0;  // two tiles of a workgroup run side by side
         return 1.05 + 0.058 * v.tm + std::ceil(tiles / wgs) * per_tile;
+    }
+    if (v.traits & TRAIT_WAVE_SPLIT) {
+        // every wave of the tile's workgroup multiplies its share of the channels straight from global memory: one round
+        // of memory latency, then 27 ns per fp32 32x32x2 MFMA and SIMD, then the exchange of the partial sums
+        const double kw = v.threads / 64.0, tiles = std::ceil(d.K / (double)v.tm) * std::ceil(P / (double)v.tn);
+        const double per_cu = std::max(1.0, std::floor(16.0 / kw));
+        const double rounds = std::ceil(tiles / (256.0 * per_cu));
+        const double mfmas = std::ceil(d.C / 8.0 / kw) * 4.0 * (v.tm / 32.0) * (v.tn / 32.0);
+        const double share = std::min(per_cu, std::max(1.0, tiles / 256.0)) * kw / 4.0;  // waves per SIMD
+        return 3.2 + rounds * (0.9 + mfmas * 0.027 * std::max(1.0, share)) + 0.3 + 0.02 * kw;
     }
     const bool window = v.family == FAM_WINDOW || (v.traits & TRAIT_WINDOW_TILES);
     double tiles;

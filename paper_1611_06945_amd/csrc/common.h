@@ -118,7 +118,8 @@ enum { TRAIT_SCALAR_LOADS = 1u,  // filter tile fetched element by element (no a
        TRAIT_FILTERS_IN_KERNEL = 64u,  // Winograd: the filter transform runs inside the product kernel
        TRAIT_POOL_EPILOGUE = 128u,     // can max-pool its output tile before the store (CONV_FLAG_MAXPOOL_3X3S2)
        TRAIT_PACKED_FILTERS = 256u,    // reads filters in MFMA operand order (CONV_FLAG_FILT_PACKED); checks the tensor formats itself
-       TRAIT_CONVERTS_FIRST = 512u };  // serves the plain formats by converting input and filters into the workspace first
+       TRAIT_CONVERTS_FIRST = 512u,    // serves the plain formats by converting input and filters into the workspace first
+       TRAIT_WAVE_SPLIT = 1024u };     // the waves of a workgroup split the reduction of one tile (v.threads / 64 ways), operands from global memory
 
 enum { FAM_IGEMM = 0, FAM_POINTWISE = 1, FAM_FIRSTLAYER = 2, FAM_WINDOW = 3, FAM_FC = 4, FAM_NHWC = 5, FAM_WINOGRAD = 6 };
 
@@ -140,6 +141,7 @@ void register_wconv_f32(std::vector<Variant>& out);
 void register_wconv_f16(std::vector<Variant>& out);
 void register_wconv_bf16(std::vector<Variant>& out);
 void register_wino_f32(std::vector<Variant>& out);
+void register_pwk_f32(std::vector<Variant>& out);
 void register_pwin_f16(std::vector<Variant>& out);
 void register_pwin_bf16(std::vector<Variant>& out);
 
