@@ -530,6 +530,13 @@ def main():
                                      "tflops": round(tf, 1), "ns_per_mfma": round(ns, 2)})
                         log("mfma %-4s %2dx%-2d  %d waves/SIMD  %d VALU per MFMA: %8.1f TFLOP/s  %6.2f ns per MFMA and SIMD" % (
                             name, block, block, wps, nv, tf, ns))
+        for code, name in ((wl.F16, "f16"), (wl.BF16, "bf16")):
+            for wps in (1, 2, 4):
+                tf, ns = B.conv_probe_mfma_mix(code, 32, wps, 0, scratch, distinct_operands=True)
+                rows.append({"dtype": name, "block": 32, "waves_per_simd": wps, "valu_per_mfma": 0, "distinct_operands": True,
+                             "tflops": round(tf, 1), "ns_per_mfma": round(ns, 2)})
+                log("mfma %-4s 32x32  %d waves/SIMD  operand registers of its own per MFMA: %8.1f TFLOP/s  %6.2f ns per MFMA and SIMD" % (
+                    name, wps, tf, ns))
         big = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
         big2 = torch.empty_like(big)
         copy = round(B.conv_probe_stream_bandwidth(big, big2, big.numel()), 1)
@@ -559,14 +566,16 @@ def main():
 
     # ---- headline: exactly `steps` timed steps after `warmup` untimed ones --------------------------------
     r = Resident(w, fmt=a.format)
-    variant = r.autotune()
     if a.variant:
+        # profiling one kernel: no autotuning pass, so that a trace of this run holds this variant's launches only
         names = [B.conv_variant_name(r.desc, i) for i in range(B.conv_variant_count(r.desc))]
         if a.variant not in names:
             log("variant %r is not valid for %s; choose from %s" % (a.variant, w.name, names))
             sys.exit(2)
         B.conv_force_variant(r.desc, names.index(a.variant))
         variant = r.variant = a.variant
+    else:
+        variant = r.autotune()
     log("headline %s -> %s%s" % (w.name, variant, " (forced)" if a.variant else ""))
     for _ in range(a.warmup):
         r.step()
@@ -616,7 +625,7 @@ def main():
     roof["traffic"] = stored_traffic("%s|%s" % (w.name, variant))
     roof["kernel"] = variant
     roof["kernel_ms"] = round(kern_ms, 6)
-    if variant.startswith("wino_"):
+    if variant.startswith("wino_") and not a.variant:
         # next to the fastest direct variant the tuner measured, and the same layer with pre-transformed filters
         sh = w.shape
         fused = variant.endswith("_ff")

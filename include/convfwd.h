@@ -290,12 +290,13 @@ int conv_transform_filters(const conv_desc* desc, const void* filt, void* out, v
  *    both device pointers, 16-byte aligned, not overlapping.
  *  - conv_probe_mfma_mix: the same issue loop with exactly `waves_per_simd` (1..4) waves on every SIMD and
  *    `valu_per_mfma` (0, 2, 4 or 8) vector-ALU instructions between consecutive MFMAs: how much of the issue rate a
- *    given occupancy reaches, and whether vector-ALU work hides behind matrix work.  Writes TFLOP/s and the
- *    nanoseconds one SIMD spends per MFMA.
+ *    given occupancy reaches, and whether vector-ALU work hides behind matrix work.  With `distinct_operands` != 0
+ *    (16-bit types, valu_per_mfma = 0) every MFMA of a round reads operand registers of its own, as a real kernel
+ *    does, instead of one shared pair.  Writes TFLOP/s and the nanoseconds one SIMD spends per MFMA.
  */
 int conv_probe_mfma_peak(int32_t dtype, int32_t block, void* scratch, void* stream, double* tflops);
-int conv_probe_mfma_mix(int32_t dtype, int32_t block, int32_t waves_per_simd, int32_t valu_per_mfma, void* scratch,
-                        void* stream, double* tflops, double* ns_per_mfma);
+int conv_probe_mfma_mix(int32_t dtype, int32_t block, int32_t waves_per_simd, int32_t valu_per_mfma,
+                        int32_t distinct_operands, void* scratch, void* stream, double* tflops, double* ns_per_mfma);
 int conv_probe_stream_bandwidth(const void* src, void* dst, size_t bytes, void* stream, double* gbytes_per_s);
 
 /* Text for a conv_status; for CONV_EHIP it includes the message of the last failed HIP call of this thread. */

@@ -105,7 +105,7 @@ def lib() -> ctypes.CDLL:
         L.conv_convert_layout.restype = ctypes.c_int
         L.conv_probe_mfma_peak.argtypes = [ctypes.c_int32, ctypes.c_int32, vp, vp, ctypes.POINTER(ctypes.c_double)]
         L.conv_probe_mfma_peak.restype = ctypes.c_int
-        L.conv_probe_mfma_mix.argtypes = [ctypes.c_int32] * 4 + [vp, vp, ctypes.POINTER(ctypes.c_double),
+        L.conv_probe_mfma_mix.argtypes = [ctypes.c_int32] * 5 + [vp, vp, ctypes.POINTER(ctypes.c_double),
                                           ctypes.POINTER(ctypes.c_double)]
         L.conv_probe_mfma_mix.restype = ctypes.c_int
         L.conv_probe_stream_bandwidth.argtypes = [vp, vp, ctypes.c_size_t, vp, ctypes.POINTER(ctypes.c_double)]
@@ -286,10 +286,11 @@ def conv_probe_mfma_peak(dtype: int, block: int, scratch, stream=None) -> float:
     return v.value
 
 
-def conv_probe_mfma_mix(dtype: int, block: int, waves_per_simd: int, valu_per_mfma: int, scratch, stream=None):
+def conv_probe_mfma_mix(dtype: int, block: int, waves_per_simd: int, valu_per_mfma: int, scratch, stream=None,
+                        distinct_operands: bool = False):
     """(TFLOP/s, nanoseconds per MFMA and SIMD) of the issue loop at a fixed occupancy with interleaved vector-ALU work."""
     t, ns = ctypes.c_double(), ctypes.c_double()
-    _check(lib().conv_probe_mfma_mix(dtype, block, waves_per_simd, valu_per_mfma, _ptr(scratch), _stream(stream),
+    _check(lib().conv_probe_mfma_mix(dtype, block, waves_per_simd, valu_per_mfma, int(bool(distinct_operands)), _ptr(scratch), _stream(stream),
                                      ctypes.byref(t), ctypes.byref(ns)), "conv_probe_mfma_mix")
     return t.value, ns.value
 

@@ -967,14 +967,15 @@ int conv_probe_mfma_peak(int32_t dtype, int32_t block, void* scratch, void* stre
     return CONV_OK;
 }
 
-int conv_probe_mfma_mix(int32_t dtype, int32_t block, int32_t waves_per_simd, int32_t valu_per_mfma, void* scratch,
-                        void* stream, double* tflops, double* ns_per_mfma)
+int conv_probe_mfma_mix(int32_t dtype, int32_t block, int32_t waves_per_simd, int32_t valu_per_mfma,
+                        int32_t distinct_operands, void* scratch, void* stream, double* tflops, double* ns_per_mfma)
 {
     if (dtype != CONV_F32 && dtype != CONV_F16 && dtype != CONV_BF16) return CONV_EDTYPE;
     if ((block != 16 && block != 32) || !scratch || !tflops || !ns_per_mfma) return CONV_EINVAL;
     if (waves_per_simd < 1 || waves_per_simd > 4) return CONV_EINVAL;
-    if (valu_per_mfma != 0 && valu_per_mfma != 2 && valu_per_mfma != 4 && valu_per_mfma != 8 && valu_per_mfma < 100) return CONV_EINVAL;
-    const hipError_t e = probe_mfma_mix(dtype, block, waves_per_simd, valu_per_mfma, (float*)scratch, (hipStream_t)stream,
+    if (valu_per_mfma != 0 && valu_per_mfma != 2 && valu_per_mfma != 4 && valu_per_mfma != 8) return CONV_EINVAL;
+    if (distinct_operands && (valu_per_mfma != 0 || dtype == CONV_F32)) return CONV_EINVAL;
+    const hipError_t e = probe_mfma_mix(dtype, block, waves_per_simd, valu_per_mfma, distinct_operands, (float*)scratch, (hipStream_t)stream,
                                         tflops, ns_per_mfma);
     if (e != hipSuccess) return hip_fail(e, "probe_mfma_mix");
     return CONV_OK;

@@ -170,7 +170,7 @@ hipError_t compare_outputs(int dtype, const void* got, const void* ref, size_t n
 
 // Device ceilings measured in place (probe_kernels.hip).
 hipError_t probe_mfma(int dtype, int block, float* sink, hipStream_t s, double* tflops);
-hipError_t probe_mfma_mix(int dtype, int block, int wps, int nv, float* sink, hipStream_t s, double* tflops, double* ns);
+hipError_t probe_mfma_mix(int dtype, int block, int wps, int nv, int distinct, float* sink, hipStream_t s, double* tflops, double* ns);
 hipError_t probe_copy(const void* src, void* dst, size_t bytes, hipStream_t s, double* gbs);
 
 inline const char* dtype_name(int dt) { return dt == CONV_F32 ? "f32" : dt == CONV_F16 ? "f16" : "bf16"; }

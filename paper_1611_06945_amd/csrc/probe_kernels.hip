@@ -53,6 +53,7 @@ __global__ void mfma_mix_kernel(float* sink, int iters, float seed)
     const uint4 a16 = make_uint4(w, w, w, w), b16 = make_uint4(w ^ 1u, w, w, w);
     const float a32 = seed + threadIdx.x, b32 = seed * 0.5f;
     // OPM: 0 = every MFMA reads the same two operand registers; 1 = a different B operand per MFMA; 2 = different A and B
+    // (16-bit types; what a real kernel does)
     uint4 av[NACC], bv[NACC];
 #pragma unroll
     for (int i = 0; i < NACC; ++i) {
@@ -122,32 +123,28 @@ static hipError_t time_mfma_mix(int wps, float* sink, hipStream_t s, double* tfl
 }
 
 template <int DT, int MB>
-static hipError_t mix_by_nv(int nv, int wps, float* sink, hipStream_t s, double* tflops, double* ns)
+static hipError_t mix_by_nv(int nv, int distinct, int wps, float* sink, hipStream_t s, double* tflops, double* ns)
 {
+    if (distinct) return nv == 0 ? time_mfma_mix<DT, MB, 0, 2>(wps, sink, s, tflops, ns) : hipErrorInvalidValue;
     switch (nv) {
         case 0: return time_mfma_mix<DT, MB, 0>(wps, sink, s, tflops, ns);
         case 2: return time_mfma_mix<DT, MB, 2>(wps, sink, s, tflops, ns);
         case 4: return time_mfma_mix<DT, MB, 4>(wps, sink, s, tflops, ns);
         case 8: return time_mfma_mix<DT, MB, 8>(wps, sink, s, tflops, ns);
-        // temporary experiment codes: operand rotation (16-bit types only)
-        case 101: return time_mfma_mix<DT, MB, 0, 1>(wps, sink, s, tflops, ns);
-        case 102: return time_mfma_mix<DT, MB, 0, 2>(wps, sink, s, tflops, ns);
-        case 106: return time_mfma_mix<DT, MB, 0, 2, 6>(wps, sink, s, tflops, ns);
-        case 108: return time_mfma_mix<DT, MB, 0, 0, 8>(wps, sink, s, tflops, ns);
         default: return hipErrorInvalidValue;
     }
 }
 
-hipError_t probe_mfma_mix(int dtype, int block, int wps, int nv, float* sink, hipStream_t s, double* tflops, double* ns)
+hipError_t probe_mfma_mix(int dtype, int block, int wps, int nv, int distinct, float* sink, hipStream_t s, double* tflops, double* ns)
 {
     if (block == 32) {
-        if (dtype == CONV_F32) return mix_by_nv<CONV_F32, 32>(nv, wps, sink, s, tflops, ns);
-        if (dtype == CONV_F16) return mix_by_nv<CONV_F16, 32>(nv, wps, sink, s, tflops, ns);
-        return mix_by_nv<CONV_BF16, 32>(nv, wps, sink, s, tflops, ns);
+        if (dtype == CONV_F32) return mix_by_nv<CONV_F32, 32>(nv, distinct, wps, sink, s, tflops, ns);
+        if (dtype == CONV_F16) return mix_by_nv<CONV_F16, 32>(nv, distinct, wps, sink, s, tflops, ns);
+        return mix_by_nv<CONV_BF16, 32>(nv, distinct, wps, sink, s, tflops, ns);
     }
-    if (dtype == CONV_F32) return mix_by_nv<CONV_F32, 16>(nv, wps, sink, s, tflops, ns);
-    if (dtype == CONV_F16) return mix_by_nv<CONV_F16, 16>(nv, wps, sink, s, tflops, ns);
-    return mix_by_nv<CONV_BF16, 16>(nv, wps, sink, s, tflops, ns);
+    if (dtype == CONV_F32) return mix_by_nv<CONV_F32, 16>(nv, distinct, wps, sink, s, tflops, ns);
+    if (dtype == CONV_F16) return mix_by_nv<CONV_F16, 16>(nv, distinct, wps, sink, s, tflops, ns);
+    return mix_by_nv<CONV_BF16, 16>(nv, distinct, wps, sink, s, tflops, ns);
 }
 
 __global__ __launch_bounds__(256) void stream_copy_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, size_t n)
