@@ -300,7 +300,8 @@ def layer_report(w, launches=100, batches=5, rotate_mb=0, fmt="nchw", cpu=True, 
 
 
 def stack_report(dtype, batch=20, reps=50):
-    """The five-layer stack end to end (all operations enqueued back to back, one synchronisation at the end):
+    """The five-layer stack end to end (all operations enqueued back to back by one conv_run_ops call per pass, one
+    synchronisation at the end):
     every layer in [N][C][H][W], and with the data format chosen per layer (channel-innermost where it pays)."""
     import torch
 
@@ -341,7 +342,17 @@ def stack_report(dtype, batch=20, reps=50):
             e1.synchronize()
             per.append(e0.elapsed_time(e1) / reps)
         ms = statistics.median(per)
-        rep[tag] = {"formats": st.formats, "filter_formats": st.filt_formats, "pool_fused": st.fused, "ms": round(ms, 5),
+        per = []
+        for _ in range(3):   # the same chain issued with one Python call per operation, for comparison
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(reps):
+                st.run_stepwise(x, filts, biases)
+            e1.record()
+            e1.synchronize()
+            per.append(e0.elapsed_time(e1) / reps)
+        ms_step = statistics.median(per)
+        rep[tag] = {"ms_call_per_operation": round(ms_step, 5), "formats": st.formats, "filter_formats": st.filt_formats, "pool_fused": st.fused, "ms": round(ms, 5),
                     "gflops": round(flops / (ms * 1e-3) / 1e9, 1),
                     "variants": [B.conv_variant_name(d, -1) for d in st.descs]}
         # the same chain recorded once into a HIP graph and replayed: one launch per pass instead of one per operation

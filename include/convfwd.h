@@ -259,6 +259,32 @@ int maxpool_fwd_layout(int32_t N, int32_t C, int32_t H, int32_t W, int32_t win, 
                        int32_t in_nhwc, int32_t out_nhwc, const void* in, void* out, void* stream);
 
 /*
+ * A straight-line schedule of operations issued with ONE call (paper, Section 3 "Code Generation, Scheduling, and
+ * Execution": every ND-Array is allocated up front and the operations are issued in a topological order): each
+ * element is a conv_fwd_ws, maxpool_fwd_layout or conv_convert_layout call with its arguments, and conv_run_ops
+ * enqueues them in array order on `stream` exactly as those calls would -- same validation, same variant selection,
+ * same kernels -- without returning to the caller in between, so that a chain of microsecond kernels is not paced by
+ * the caller's own per-call cost.  Stops at the first element that fails and returns its status (*failed_index, if not
+ * NULL, receives its index; earlier elements stay enqueued); CONV_EINVAL for a NULL array, count < 0 or an unknown kind.
+ *   kind CONV_OP_CONV:    desc, in, filt, bias, out, workspace, workspace_bytes as conv_fwd_ws
+ *   kind CONV_OP_MAXPOOL: in, out; p[0..8] = N, C, H, W, win, stride, dtype, in_nhwc, out_nhwc as maxpool_fwd_layout
+ *   kind CONV_OP_CONVERT: in, out; p[0..3] = A, B, S, dtype as conv_convert_layout
+ */
+typedef enum { CONV_OP_CONV = 0, CONV_OP_MAXPOOL = 1, CONV_OP_CONVERT = 2 } conv_op_kind;
+typedef struct {
+    int32_t kind;           /* conv_op_kind */
+    conv_desc desc;         /* CONV_OP_CONV only */
+    const void* in;
+    const void* filt;       /* CONV_OP_CONV only */
+    const float* bias;      /* CONV_OP_CONV only; may be NULL */
+    void* out;
+    void* workspace;        /* CONV_OP_CONV only; may be NULL */
+    size_t workspace_bytes;
+    int32_t p[9];           /* CONV_OP_MAXPOOL / CONV_OP_CONVERT parameters */
+} conv_op;
+int conv_run_ops(const conv_op* ops, int32_t count, void* stream, int32_t* failed_index);
+
+/*
  * Explicit data-format conversion (paper, Section 3, "Graph-level Optimizations"): out[a][s][b] = in[a][b][s] for
  * dense tensors of `dtype` elements.  (A,B,S) = (N,C,H*W) turns [N][C][H][W] into [N][H][W][C]; (N,H*W,C) turns it
  * back; (K,C,R*S) turns filters [K][C][R][S] into [K][R][S][C].  Device pointers, out must not alias in; enqueued on

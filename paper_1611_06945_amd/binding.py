@@ -36,6 +36,15 @@ class conv_desc(ctypes.Structure):
             self.N, self.C, self.H, self.W, self.K, self.R, self.S, self.stride, self.pad, self.dtype, self.flags)
 
 
+CONV_OP_CONV, CONV_OP_MAXPOOL, CONV_OP_CONVERT = 0, 1, 2
+
+
+class conv_op(ctypes.Structure):
+    _fields_ = [("kind", ctypes.c_int32), ("desc", conv_desc), ("inp", ctypes.c_void_p), ("filt", ctypes.c_void_p),
+                ("bias", ctypes.c_void_p), ("out", ctypes.c_void_p), ("workspace", ctypes.c_void_p),
+                ("workspace_bytes", ctypes.c_size_t), ("p", ctypes.c_int32 * 9)]
+
+
 class ConvError(RuntimeError):
     def __init__(self, status: int, where: str):
         self.status = status
@@ -76,6 +85,8 @@ def lib() -> ctypes.CDLL:
         L.conv_autotune.restype = ctypes.c_int
         L.conv_compare_outputs.argtypes = [ctypes.c_int32, vp, vp, ctypes.c_size_t, vp, ctypes.POINTER(ctypes.c_double)]
         L.conv_compare_outputs.restype = ctypes.c_int
+        L.conv_run_ops.argtypes = [ctypes.POINTER(conv_op), ctypes.c_int32, vp, i32p]
+        L.conv_run_ops.restype = ctypes.c_int
         L.conv_variant_count.argtypes = [dp]
         L.conv_variant_count.restype = ctypes.c_int
         L.conv_variant_name.argtypes = [dp, ctypes.c_int, ctypes.c_char_p, ctypes.c_size_t]
@@ -215,6 +226,30 @@ def conv_compare_outputs(dtype: int, got, ref, elements: int, stream=None) -> fl
     _check(lib().conv_compare_outputs(dtype, _ptr(got), _ptr(ref), int(elements), _stream(stream), ctypes.byref(v)),
            "conv_compare_outputs")
     return v.value
+
+
+def op_conv(desc, inp, filt, bias, out, workspace=None, workspace_bytes=0) -> conv_op:
+    return conv_op(CONV_OP_CONV, desc, _ptr(inp), _ptr(filt), _ptr(bias), _ptr(out), _ptr(workspace), int(workspace_bytes),
+                   (ctypes.c_int32 * 9)())
+
+
+def op_maxpool(N, C, H, W, win, stride, dtype, in_nhwc, out_nhwc, inp, out) -> conv_op:
+    return conv_op(CONV_OP_MAXPOOL, conv_desc(), _ptr(inp), None, None, _ptr(out), None, 0,
+                   (ctypes.c_int32 * 9)(N, C, H, W, win, stride, dtype, int(bool(in_nhwc)), int(bool(out_nhwc))))
+
+
+def op_convert(A, Bdim, S, dtype, inp, out) -> conv_op:
+    return conv_op(CONV_OP_CONVERT, conv_desc(), _ptr(inp), None, None, _ptr(out), None, 0,
+                   (ctypes.c_int32 * 9)(A, Bdim, S, dtype))
+
+
+def conv_run_ops(ops, stream=None) -> None:
+    """Enqueue a list (or a prepared ctypes array) of conv_op in order with one call into the library."""
+    arr = ops if isinstance(ops, ctypes.Array) else (conv_op * len(ops))(*ops)
+    failed = ctypes.c_int32(-1)
+    rc = lib().conv_run_ops(arr, len(arr), _stream(stream), ctypes.byref(failed))
+    if rc < 0:
+        raise ConvError(rc, "conv_run_ops (operation %d)" % failed.value)
 
 
 def conv_variant_count(desc) -> int:

@@ -919,6 +919,33 @@ static uint32_t filter_target(const conv_desc* desc)
     return desc->dtype == CONV_F32 ? CONV_FLAG_FILT_WINOGRAD : CONV_FLAG_FILT_PACKED;
 }
 
+int conv_run_ops(const conv_op* ops, int32_t count, void* stream, int32_t* failed_index)
+{
+    if (!ops || count < 0) return CONV_EINVAL;
+    for (int32_t i = 0; i < count; ++i) {
+        const conv_op& o = ops[i];
+        int rc;
+        switch (o.kind) {
+            case CONV_OP_CONV:
+                rc = fwd_common(&o.desc, o.in, o.filt, o.bias, o.out, o.workspace, o.workspace_bytes, stream);
+                break;
+            case CONV_OP_MAXPOOL:
+                rc = maxpool_fwd_layout(o.p[0], o.p[1], o.p[2], o.p[3], o.p[4], o.p[5], o.p[6], o.p[7], o.p[8], o.in, o.out, stream);
+                break;
+            case CONV_OP_CONVERT:
+                rc = conv_convert_layout(o.p[0], o.p[1], o.p[2], o.p[3], o.in, o.out, stream);
+                break;
+            default:
+                rc = CONV_EINVAL;
+        }
+        if (rc != CONV_OK) {
+            if (failed_index) *failed_index = i;
+            return rc;
+        }
+    }
+    return CONV_OK;
+}
+
 size_t conv_transformed_filter_bytes(const conv_desc* desc)
 {
     int OH, OW;

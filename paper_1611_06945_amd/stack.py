@@ -127,6 +127,7 @@ class ConvStack:
 
     def _build(self) -> None:
         torch = self.torch
+        self._ops_key = None
         n = len(self.shapes)
         self.descs, self.conv_out, self.pool_out, self.conv_layout, self.convert_out = [], [], [], [], []
         ws_bytes = 256
@@ -212,8 +213,44 @@ class ConvStack:
             cur = self.layer_output(i)
         return cur
 
+    def _ops(self, x, filts, biases):
+        """The whole chain as an array of library operations (built once per set of tensors, then reused)."""
+        key = (int(x.data_ptr()), tuple(int(f.data_ptr()) for f in filts), tuple(0 if b is None else int(b.data_ptr()) for b in biases),
+               tuple(0 if p is None else int(p.data_ptr()) for p in self.packed_filts), id(self.workspace))
+        if getattr(self, "_ops_key", None) == key:
+            return self._ops_arr
+        ops = []
+        cur = x
+        if self.in_convert is not None:
+            s0 = self.shapes[0]
+            ops.append(B.op_convert(s0.N, s0.C, s0.H * s0.W, self.dtype, x, self.in_convert))
+            cur = self.in_convert
+        for i, d in enumerate(self.descs):
+            s = self.shapes[i]
+            out = self.pool_out[i] if self.fused[i] else self.conv_out[i]
+            ops.append(B.op_conv(d, cur, self._filt(i, filts), biases[i], out, self.workspace, self.workspace.numel()))
+            if not self.fused[i]:
+                if self.pool_out[i] is not None:
+                    ops.append(B.op_maxpool(s.N, s.K, s.OH, s.OW, self.pool_win, self.pool_stride, self.dtype,
+                                            self.conv_layout[i] == NHWC, self._handoff_layout(i) == NHWC, self.conv_out[i],
+                                            self.pool_out[i]))
+                elif self.convert_out[i] is not None:
+                    dims = (s.N, s.K, s.OH * s.OW) if self.conv_layout[i] == NCHW else (s.N, s.OH * s.OW, s.K)
+                    ops.append(B.op_convert(*dims, self.dtype, self.conv_out[i], self.convert_out[i]))
+            cur = self.layer_output(i)
+        self._ops_arr = (B.conv_op * len(ops))(*ops)
+        self._ops_key = key
+        return self._ops_arr
+
     def run(self, x, filts, biases, stream=None):
-        """Enqueue every operation; returns the last layer's output tensor, [N][K][OH][OW] (not synchronised)."""
+        """Enqueue every operation with one call into the library (`conv_run_ops`: the chain is issued from native code,
+        not paced by a Python call per kernel); returns the last layer's output tensor, [N][K][OH][OW] (not
+        synchronised)."""
+        B.conv_run_ops(self._ops(x, filts, biases), stream)
+        return self.layer_output(len(self.shapes) - 1)
+
+    def run_stepwise(self, x, filts, biases, stream=None):
+        """The same chain issued one binding call per operation (what `run` did before the native schedule existed)."""
         return self._walk(x, filts, biases, stream, tune=False)
 
     def capture(self, x, filts, biases):

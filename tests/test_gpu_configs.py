@@ -167,6 +167,12 @@ def test_config5_stack_with_format_selection(dtype, formats):
     y = stack.run(x, filts, biases)
     torch.cuda.synchronize()
     _check_stack_against_oracle(stack, shapes, gen, dtype, y)
+    # the native schedule (one library call for the chain) and the call-per-operation walk run the same kernels
+    want = to_host_stored(y, dtype).copy()
+    y.fill_(float("nan"))
+    y2 = stack.run_stepwise(x, filts, biases)
+    torch.cuda.synchronize()
+    assert np.array_equal(to_host_stored(y2, dtype).view(np.uint16), want.view(np.uint16))
 
 
 def test_config5_format_selection_on_a_side_stream_times_the_glue():

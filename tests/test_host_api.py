@@ -483,3 +483,27 @@ def test_saved_cache_carries_the_identity_of_device_and_kernels(tmp_path):
         with pytest.raises(B.ConvError):
             B.conv_cache_load(str(wrong))
     B.conv_cache_clear()
+
+
+def test_run_ops_validates_each_element_and_reports_the_failing_index():
+    L = B.lib()
+    assert L.conv_run_ops(None, 0, None, None) == B.CONV_EINVAL
+    empty = (B.conv_op * 1)()
+    assert L.conv_run_ops(empty, 0, None, None) == B.CONV_OK          # nothing to do
+    assert L.conv_run_ops(empty, -1, None, None) == B.CONV_EINVAL
+    bad_kind = B.conv_op(7, B.conv_desc(), 256, None, None, 512, None, 0, (ctypes.c_int32 * 9)())
+    failed = ctypes.c_int32(-1)
+    assert L.conv_run_ops((B.conv_op * 1)(bad_kind), 1, None, ctypes.byref(failed)) == B.CONV_EINVAL and failed.value == 0
+    # element 0 is refused by its own validation before any GPU call (a pool window larger than the image), and nothing
+    # after it is looked at
+    ops = [B.op_maxpool(1, 8, 2, 2, 3, 2, B.CONV_F16, False, False, 256, 512),
+           B.op_convert(0, 0, 0, B.CONV_F16, 256, 512)]
+    with pytest.raises(B.ConvError) as e:
+        B.conv_run_ops(ops)
+    assert e.value.status == B.CONV_EINVAL and "operation 0" in str(e.value)
+    # a convolution element is validated like conv_fwd_ws: a misaligned input pointer
+    d = B.make_desc(1, 16, 8, 8, 16, 3, 3, 1, 1, B.CONV_F16, relu=True)
+    with pytest.raises(B.ConvError) as e:
+        B.conv_run_ops([B.op_conv(d, 256 + 2, 512, None, 1024)])
+    assert e.value.status == B.CONV_EINVAL
+    assert ctypes.sizeof(B.conv_op) == 4 + 44 + 5 * 8 + 8 + 36 + 4   # the C layout: int32, conv_desc, 5 pointers, size_t, 9 int32, tail padding
