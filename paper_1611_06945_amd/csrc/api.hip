@@ -70,6 +70,7 @@ State& state()
         register_wconv_f16(s->variants);
         register_wconv_bf16(s->variants);
         register_pwk_f32(s->variants);
+        register_pwin32_f32(s->variants);
         register_pwin_f16(s->variants);
         register_pwin_bf16(s->variants);
         for (size_t i = 0; i < s->variants.size(); ++i) s->by_name[s->variants[i].name] = (int)i;
@@ -236,6 +237,15 @@ double heuristic_cost(const Variant& v, const conv_desc& d, int OH, int OW)
         const double mfmas = std::ceil(d.C / 8.0 / kw) * 4.0 * (v.tm / 32.0) * (v.tn / 32.0);
         const double share = std::min(per_cu, std::max(1.0, tiles / 256.0)) * kw / 4.0;  // waves per SIMD
         return 3.2 + rounds * (0.9 + mfmas * 0.027 * std::max(1.0, share)) + 0.3 + 0.02 * kw;
+    }
+    if (v.traits & TRAIT_CHANNEL_WAVES) {
+        // one workgroup per (channel tile, run of v.tn pixels); its v.threads / 64 waves split the channels, so a SIMD
+        // multiplies tm*tn/1024 * Q/2 / (waves per workgroup) MFMAs of 30 ns (27 ns at the issue limit) per resident wave
+        const double waves = v.threads / 64.0, tiles = std::ceil(d.K / (double)v.tm) * std::ceil(P / (double)v.tn);
+        const double rounds = std::ceil(tiles / 256.0);
+        const double pix_waves = (v.tn / 32.0 >= 4.0 && waves >= 8.0) ? 2.0 : 1.0;
+        const double mfmas = (v.tm / 32.0) * (v.tn / 32.0 / pix_waves) * (Q / 2.0) / (waves / pix_waves);
+        return 5.0 + 0.05 * waves + rounds * mfmas * 0.030 * std::max(1.0, waves / 4.0);
     }
     const bool window = v.family == FAM_WINDOW || (v.traits & TRAIT_WINDOW_TILES);
     double tiles;

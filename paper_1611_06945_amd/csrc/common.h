@@ -119,7 +119,8 @@ enum { TRAIT_SCALAR_LOADS = 1u,  // filter tile fetched element by element (no a
        TRAIT_POOL_EPILOGUE = 128u,     // can max-pool its output tile before the store (CONV_FLAG_MAXPOOL_3X3S2)
        TRAIT_PACKED_FILTERS = 256u,    // reads filters in MFMA operand order (CONV_FLAG_FILT_PACKED); checks the tensor formats itself
        TRAIT_CONVERTS_FIRST = 512u,    // serves the plain formats by converting input and filters into the workspace first
-       TRAIT_WAVE_SPLIT = 1024u };     // the waves of a workgroup split the reduction of one tile (v.threads / 64 ways), operands from global memory
+       TRAIT_WAVE_SPLIT = 1024u,       // the waves of a workgroup split the reduction of one tile (v.threads / 64 ways), operands from global memory
+       TRAIT_CHANNEL_WAVES = 2048u };  // fp32 window kernel on linear pixel tiles whose waves split the channels of a chunk
 
 enum { FAM_IGEMM = 0, FAM_POINTWISE = 1, FAM_FIRSTLAYER = 2, FAM_WINDOW = 3, FAM_FC = 4, FAM_NHWC = 5, FAM_WINOGRAD = 6 };
 
@@ -142,6 +143,7 @@ void register_wconv_f16(std::vector<Variant>& out);
 void register_wconv_bf16(std::vector<Variant>& out);
 void register_wino_f32(std::vector<Variant>& out);
 void register_pwk_f32(std::vector<Variant>& out);
+void register_pwin32_f32(std::vector<Variant>& out);
 void register_pwin_f16(std::vector<Variant>& out);
 void register_pwin_bf16(std::vector<Variant>& out);
 

@@ -64,6 +64,7 @@ SMALL_SHAPES = [
     ConvShape(5, 16, 6, 6, 70, 6, 6, 1, 0),     # fully connected (window = image), 5 images, K ragged against the row blocks
     ConvShape(3, 1032, 1, 1, 33, 1, 1, 1, 0),   # fully connected 1x1 on 1x1: 258 / 129 vectors against 256 threads
     ConvShape(8, 24, 2, 2, 10, 2, 2, 1, 0),     # fully connected, 8 images
+    ConvShape(4, 16, 7, 9, 24, 5, 5, 1, 2),     # fp32 window kernel with channel-waves, 5x5: chunks of 8 channels, pixel tiles straddle images
     ConvShape(3, 72, 6, 10, 50, 1, 1, 1, 0),    # pointwise with the channels split over the waves of a workgroup: 9 groups of 8 channels over 4 or 8 waves, ragged K and pixel tiles
     ConvShape(2, 136, 5, 7, 100, 1, 1, 1, 0),   # the same over 16 waves (17 groups), tiles straddle images, odd row length
 ]
