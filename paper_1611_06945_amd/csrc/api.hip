@@ -67,6 +67,8 @@ State& state()
         register_wino_f32(s->variants);
         register_swin_f16(s->variants);
         register_swin_bf16(s->variants);
+        register_swinp_f16(s->variants);
+        register_swinp_bf16(s->variants);
         register_wconv_f16(s->variants);
         register_wconv_bf16(s->variants);
         register_pwk_f32(s->variants);
@@ -218,6 +220,15 @@ double heuristic_cost(const Variant& v, const conv_desc& d, int OH, int OW)
         if (v.traits & TRAIT_FILTERS_IN_KERNEL) t_filters = 0.0, t_step *= 1.12;
         if (d.flags & CONV_FLAG_FILT_WINOGRAD) t_filters = 0.0;
         return 4.62 + t_filters + rounds * (d.C / cb) * t_step;
+    }
+    if (v.family == FAM_FIRSTLAYER && (v.traits & TRAIT_POOL_EPILOGUE)) {
+        // one workgroup per tile of pooled outputs and channel tile, one per CU at a time: filters re-laid, input rows
+        // staged, one 32-pixel block per wave (v.threads / 256 per SIMD), then the pooling pass
+        const double side = std::sqrt((double)v.tn), pt = (side - 1.0) / 2.0;
+        const double POH = (OH - 3) / 2 + 1, POW = (OW - 3) / 2 + 1;
+        const double wgs = (double)d.N * std::ceil(POH / pt) * std::ceil(POW / pt) * std::ceil(d.K / (double)v.tm);
+        const double per_wg = 2.0 + 0.03 * v.tm + (v.threads / 256.0) * (v.tk / 16.0) * (v.tm / 32.0) * 0.016 + 1.5;
+        return 2.5 + std::ceil(wgs / 256.0) * per_wg;
     }
     if (v.family == FAM_FIRSTLAYER) {
         // persistent workgroups, one per CU and channel tile, walking over tiles of v.tn pixels of one image: a start-up

@@ -138,6 +138,8 @@ void register_nwin_f16(std::vector<Variant>& out);
 void register_nwin_bf16(std::vector<Variant>& out);
 void register_swin_f16(std::vector<Variant>& out);
 void register_swin_bf16(std::vector<Variant>& out);
+void register_swinp_f16(std::vector<Variant>& out);
+void register_swinp_bf16(std::vector<Variant>& out);
 void register_wconv_f32(std::vector<Variant>& out);
 void register_wconv_f16(std::vector<Variant>& out);
 void register_wconv_bf16(std::vector<Variant>& out);

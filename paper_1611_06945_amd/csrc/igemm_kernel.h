@@ -86,6 +86,13 @@ struct Prec<CONV_F16> {
         return __builtin_bit_cast(uint16_t, h);
     }
     static __device__ __forceinline__ float to_f32(elem_t x) { return (float)__builtin_bit_cast(_Float16, x); }
+    // two values rounded and packed (a in the low half): one v_cvt_pk_f16_f32
+    static __device__ __forceinline__ uint32_t pack2_from_f32(float a, float b)
+    {
+        typedef float f32x2_t __attribute__((ext_vector_type(2)));
+        typedef _Float16 f16x2_t __attribute__((ext_vector_type(2)));
+        return __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2_t{a, b}, f16x2_t));
+    }
 };
 
 template <>
@@ -94,12 +101,17 @@ struct Prec<CONV_BF16> {
     static constexpr int KPACK = 8;
     static __device__ __forceinline__ elem_t from_f32(float x)
     {
-        uint32_t u = __builtin_bit_cast(uint32_t, x);
-        if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);  // NaN stays NaN
-        u += 0x7fffu + ((u >> 16) & 1u);  // round to nearest, ties to even
-        return (uint16_t)(u >> 16);
+        __bf16 h = (__bf16)x;  // v_cvt_pk_bf16_f32 (gfx950): round to nearest even, a NaN stays a NaN
+        return __builtin_bit_cast(uint16_t, h);
     }
     static __device__ __forceinline__ float to_f32(elem_t x) { return __builtin_bit_cast(float, (uint32_t)x << 16); }
+    // two values rounded and packed (a in the low half): one v_cvt_pk_bf16_f32
+    static __device__ __forceinline__ uint32_t pack2_from_f32(float a, float b)
+    {
+        typedef float f32x2_t __attribute__((ext_vector_type(2)));
+        typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+        return __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2_t{a, b}, bf16x2_t));
+    }
 };
 
 // ---------------------------------------------------------------------------

@@ -35,6 +35,7 @@ struct Swin16Cfg {
     static_assert(PITCH_ % 4 == 0, "staged rows keep the groups' alignment");
     static constexpr int DT = DT_, C = C_, R = R_, S = S_, ST = ST_, TMB = TMB_, IRMAX = IRMAX_, PITCH = PITCH_;
     static constexpr int CWAVES = 4;                 // waves of a group: one 32-pixel block each
+    static constexpr int NBW = 1;
     static constexpr int WAVES = 8, NT = 64 * WAVES; // two groups, each on its own tile and patch buffer; all waves re-lay the filters
     static constexpr int TM = 32 * TMB;              // output channels per workgroup
     static constexpr int TN = 32 * CWAVES;           // pixels per tile
@@ -55,6 +56,135 @@ inline int swin16_rows_spanned(int OH, int OW, int TN)
 {
     int rows = (TN - 1 + OW - 1) / OW + 1;
     return rows < OH ? rows : OH;
+}
+
+// ---- filters: KCRS rows -> LDS [TM][KP] (+ the tile's biases) -----------------------------------------------------
+// Reduction element kk = 16*j + 8*half + 4*g + e of MFMA step j belongs to line 2t + half (line = r*C + c) and tap
+// 4*sq + e, where (t, sq) = divmod(2j + g, SQ); lines and taps that do not exist are zeros.  A thread owns one group
+// slot (4 taps, 8 bytes of LDS) and walks down the filter rows, NT/128 at a time per workgroup.  The caller's barrier
+// publishes the result.
+template <class CFG>
+__device__ __forceinline__ void swin16_stage_filters(uint16_t* As, float* bias_s, __amdgpu_buffer_rsrc_t rfilt, const ConvArgs& a,
+                                                     int m0, int tid)
+{
+    constexpr int C = CFG::C, R = CFG::R, S = CFG::S, SQ = CFG::SQ, NROW = CFG::NROW, KP = CFG::KP, LDA = CFG::LDA;
+    constexpr int TM = CFG::TM, NT = CFG::NT, Q = C * R * S;
+    static_assert(S % 4 == 0 || S % 4 == 3, "a filter row's last group holds 3 or 4 taps");
+    constexpr int GS = KP / 4;
+    static_assert(GS <= 128, "a filter row's groups fit 128 threads");
+    constexpr int MR = NT / 128;  // filter rows per pass of the workgroup (even: a thread's rows keep their parity)
+    static_assert(NT % 128 == 0 && MR % 2 == 0, "rows per pass");
+    const int gs = tid & 127, mrow = __builtin_amdgcn_readfirstlane(tid >> 7);
+    const int j = gs >> 2, gh = (gs >> 1) & 1, g = gs & 1;
+    const int i2 = 2 * j + g, t = i2 / SQ, sq = i2 - t * SQ;
+    const int line = 2 * t + gh;
+    const int fr = line / C, fc = line - fr * C;
+    const bool g_ok = gs < GS && line < NROW;
+    const int src = (fc * R + fr) * S + 4 * sq;                 // first tap of the group in the filter row
+    const bool three = S - 4 * sq < 4;
+    // The group's 8 bytes start at element m*Q + src, even or odd: they are cut out of three aligned dwords (a
+    // misaligned dword load runs at a fraction of the rate).  The rows of a thread are MR apart, so m*Q keeps its
+    // parity pm and the cut is the same for every row: vector part 2*((src+pm) & ~1), scalar part 2*(m*Q & ~1).
+    const int pm = ((m0 + mrow) * Q) & 1;
+    const int par = (pm + src) & 1;
+    const uint32_t v0 = g_ok ? (uint32_t)((src + pm) & ~1) * 2u : kFarOffset;
+    constexpr int NIT = (TM + MR - 1) / MR;
+    // the last pass may reach past the tile's rows when MR does not divide TM (decided at compile time otherwise)
+    auto row_in = [&](int it) { return TM % MR == 0 || MR * it + MR <= TM || mrow + MR * it < TM; };
+    u32x3 f[NIT];
+#pragma unroll
+    for (int it = 0; it < NIT; ++it) {
+        const int m = m0 + mrow + MR * it;
+        const uint32_t soff = (m < a.K && row_in(it)) ? (uint32_t)((m * Q) & ~1) * 2u : kFarScalar;
+        f[it] = __builtin_bit_cast(u32x3, __builtin_amdgcn_raw_buffer_load_b96(rfilt, (int)v0, (int)soff, 0));
+    }
+    if (tid < TM) {
+        const __amdgpu_buffer_rsrc_t rbias = make_rsrc(a.bias, a.bias ? (uint32_t)a.K * 4u : 0u);
+        bias_s[tid] = buffer_load_elem<float>(rbias, m0 + tid < a.K ? (uint32_t)(m0 + tid) * 4u : kOutOfRange);
+    }
+    if (gs < GS) {
+        const uint32_t sh = par ? 16u : 0u, mhi = three ? 0x0000FFFFu : 0xFFFFFFFFu;
+#pragma unroll
+        for (int it = 0; it < NIT; ++it) {
+            const uint32_t lo = __builtin_amdgcn_alignbit(f[it].y, f[it].x, sh);
+            const uint32_t hi = __builtin_amdgcn_alignbit(f[it].z, f[it].y, sh);
+            if (row_in(it)) *(uint2*)&As[(mrow + MR * it) * LDA + 4 * gs] = make_uint2(lo, hi & mhi);
+        }
+    }
+}
+
+// ---- the reduction of a wave's NBW 32-pixel blocks: acc[mb][nb] += filters[mb*32 + ..][:] * window_nb[:] -----------------
+// Ap: the lane's filter row and half (As + li*LDA + 8*h); Bp[nb]: the first element of the lane's window of block nb in
+// line h (staged row (window's first input row)*C + h, column ST * ox).  Operands of step j+1 are read while step j
+// multiplies; a filter fragment serves NBW products, a window fragment TMB.
+template <class CFG>
+__device__ __forceinline__ void swin16_mma_loop(const uint16_t* __restrict__ Ap, const uint16_t* const (&Bp)[CFG::NBW],
+                                                uint32_t last_pair_mask,
+                                                typename Mma<CFG::DT, 32>::acc_t (&acc)[CFG::TMB][CFG::NBW])
+{
+    constexpr int S = CFG::S, ST = CFG::ST, TMB = CFG::TMB, NBW = CFG::NBW, PITCH = CFG::PITCH, SQ = CFG::SQ, NROW = CFG::NROW;
+    constexpr int KSTEPS = CFG::KSTEPS, LDA = CFG::LDA;
+    typedef Mma<CFG::DT, 32> mma_t;
+    uint4 af[2][TMB], bf[2][NBW];
+    auto read_step = [&](int j, int slot) {
+#pragma unroll
+        for (int nb = 0; nb < NBW; ++nb) {
+            uint32_t bw[4];
+#pragma unroll
+            for (int g = 0; g < 2; ++g) {
+                const int i2 = 2 * j + g, t = i2 / SQ, sq = i2 % SQ;
+                // compile-time, an immediate offset of the read; slots past the last line read the window's start
+                const int off = 2 * t >= NROW ? 0 : 2 * t * PITCH + 4 * sq;
+                uint32_t lo, hi;
+                if constexpr (ST % 4 == 0) {
+                    const uint2 w = *(const uint2*)&Bp[nb][off];
+                    lo = w.x;
+                    hi = w.y;
+                } else {
+                    const uint32_t* w = (const uint32_t*)&Bp[nb][off];
+                    lo = w[0];
+                    hi = w[1];
+                }
+                bw[2 * g] = lo;
+                bw[2 * g + 1] = hi;
+            }
+            bf[slot][nb] = make_uint4(bw[0], bw[1], bw[2], bw[3]);
+        }
+#pragma unroll
+        for (int mb = 0; mb < TMB; ++mb) af[slot][mb] = *(const uint4*)&Ap[mb * 32 * LDA + 16 * j];
+    };
+    read_step(0, 0);
+#pragma unroll
+    for (int j = 0; j < KSTEPS; ++j) {
+        if (j + 1 < KSTEPS) read_step(j + 1, (j + 1) & 1);
+        __builtin_amdgcn_sched_barrier(0);  // keep the reads ahead of the products they overlap with
+        // padding taps and lines that do not exist are cleared here, one step after their read was issued
+        uint4 b[NBW];
+#pragma unroll
+        for (int nb = 0; nb < NBW; ++nb) {
+            b[nb] = bf[j & 1][nb];
+            uint32_t* bw = (uint32_t*)&b[nb];
+#pragma unroll
+            for (int g = 0; g < 2; ++g) {
+                const int i2 = 2 * j + g, t = i2 / SQ, sq = i2 % SQ;
+                const int ntap = 2 * t >= NROW ? 0 : (S - 4 * sq >= 4 ? 4 : S - 4 * sq);
+                // (asm: a plain AND has no tie to this point of the program and is moved up to its read, where it waits;
+                // the s_nop is the gap the hardware needs between a VALU write and an MFMA reading the register, which the
+                // compiler does not insert after inline assembly)
+                if (ntap < 2) asm volatile("v_and_b32 %0, %1, %0\n\ts_nop 1" : "+v"(bw[2 * g]) : "v"(ntap == 1 ? 0x0000FFFFu : 0u));
+                if (ntap < 4) asm volatile("v_and_b32 %0, %1, %0\n\ts_nop 1" : "+v"(bw[2 * g + 1]) : "v"(ntap == 3 ? 0x0000FFFFu : 0u));
+                if (2 * t + 1 >= NROW) {
+                    asm volatile("v_and_b32 %0, %1, %0\n\ts_nop 1" : "+v"(bw[2 * g]) : "v"(last_pair_mask));
+                    asm volatile("v_and_b32 %0, %1, %0\n\ts_nop 1" : "+v"(bw[2 * g + 1]) : "v"(last_pair_mask));
+                }
+            }
+        }
+#pragma unroll
+        for (int mb = 0; mb < TMB; ++mb)
+#pragma unroll
+            for (int nb = 0; nb < NBW; ++nb) acc[mb][nb] = mma_t::run(af[j & 1][mb], b[nb], acc[mb][nb]);
+        __builtin_amdgcn_sched_barrier(0);
+    }
 }
 
 template <class CFG>
@@ -139,8 +269,11 @@ __global__ __launch_bounds__(CFG::NT) void swin16_kernel(ConvArgs a)
                 if (row_ok && (origin & 1)) shifted |= 1u << (k * C + c);
                 // two dword loads, not one of 8 bytes: before the tensor's start (padding of the very first row) the bounds
                 // check has to refuse one dword and pass the next
-                st_reg[k * C + c].x = (uint32_t)__builtin_amdgcn_raw_buffer_load_b32(rin, lane * 8 + rowoff, 0, 0);
-                st_reg[k * C + c].y = (uint32_t)__builtin_amdgcn_raw_buffer_load_b32(rin, lane * 8 + rowoff + 4, 0, 0);
+                // (a negative offset is replaced explicitly: left to wrap, it could be split into a register part and an
+                // immediate part whose sum the bounds check forms in more than 32 bits)
+                const int o0 = lane * 8 + rowoff, o1 = o0 + 4;
+                st_reg[k * C + c].x = (uint32_t)__builtin_amdgcn_raw_buffer_load_b32(rin, o0 < 0 ? (int)kFarOffset : o0, 0, 0);
+                st_reg[k * C + c].y = (uint32_t)__builtin_amdgcn_raw_buffer_load_b32(rin, o1 < 0 ? (int)kFarOffset : o1, 0, 0);
             }
         }
         return shifted;
@@ -170,56 +303,11 @@ __global__ __launch_bounds__(CFG::NT) void swin16_kernel(ConvArgs a)
     stage_t st_a;
     uint32_t sh_a = load_rows(tile, st_a);
 
-    // ---- filters: KCRS rows -> [TM][KP] -------------------------------------------------------------------------
-    // Reduction element kk = 16*j + 8*half + 4*g + e of MFMA step j belongs to line 2t + half (line = r*C + c) and
-    // tap 4*sq + e, where (t, sq) = divmod(2j + g, SQ); lines and taps that do not exist are zeros.  A thread owns one
-    // group slot (4 taps, 8 bytes of LDS) and walks down the filter rows, two at a time per workgroup.
-    {
-        static_assert(S % 4 == 0 || S % 4 == 3, "a filter row's last group holds 3 or 4 taps");
-        constexpr int GS = KP / 4;
-        static_assert(GS <= 128, "two filter rows per pass of the workgroup");
-        constexpr int MR = NT / 128;  // filter rows per pass of the workgroup (even: a thread's rows keep their parity)
-        static_assert(MR % 2 == 0 && TM % MR == 0, "rows per pass");
-        const int gs = tid & 127, mrow = __builtin_amdgcn_readfirstlane(tid >> 7);
-        const int j = gs >> 2, gh = (gs >> 1) & 1, g = gs & 1;
-        const int i2 = 2 * j + g, t = i2 / SQ, sq = i2 - t * SQ;
-        const int line = 2 * t + gh;
-        const int fr = line / C, fc = line - fr * C;
-        const bool g_ok = gs < GS && line < NROW;
-        const int src = (fc * R + fr) * S + 4 * sq;                 // first tap of the group in the filter row
-        const bool three = S - 4 * sq < 4;
-        // The group's 8 bytes start at element m*Q + src, even or odd: they are cut out of three aligned dwords (a
-        // misaligned dword load runs at a fraction of the rate).  The rows of a thread are MR apart, so m*Q keeps its
-        // parity pm and the cut is the same for every row: vector part 2*((src+pm) & ~1), scalar part 2*(m*Q & ~1).
-        const int pm = ((m0 + mrow) * Q) & 1;
-        const int par = (pm + src) & 1;
-        const uint32_t v0 = g_ok ? (uint32_t)((src + pm) & ~1) * 2u : kFarOffset;
-        constexpr int NIT = TM / MR;
-        u32x3 f[NIT];
-#pragma unroll
-        for (int it = 0; it < NIT; ++it) {
-            const int m = m0 + mrow + MR * it;
-            const uint32_t soff = m < a.K ? (uint32_t)((m * Q) & ~1) * 2u : kFarScalar;
-            f[it] = __builtin_bit_cast(u32x3, __builtin_amdgcn_raw_buffer_load_b96(rfilt, (int)v0, (int)soff, 0));
-        }
-        if (tid < TM) {
-            const __amdgpu_buffer_rsrc_t rbias = make_rsrc(a.bias, a.bias ? (uint32_t)a.K * 4u : 0u);
-            bias_s[tid] = buffer_load_elem<float>(rbias, m0 + tid < a.K ? (uint32_t)(m0 + tid) * 4u : kOutOfRange);
-        }
-        // the extra row of both patch buffers stays zero
-        if (tid < PITCH / 2) {
-            ((uint32_t*)(Bs0 + SROWS * PITCH))[tid] = 0u;
-            ((uint32_t*)(Bs0 + B_ELEMS + SROWS * PITCH))[tid] = 0u;
-        }
-        if (gs < GS) {
-            const uint32_t sh = par ? 16u : 0u, mhi = three ? 0x0000FFFFu : 0xFFFFFFFFu;
-#pragma unroll
-            for (int it = 0; it < NIT; ++it) {
-                const uint32_t lo = __builtin_amdgcn_alignbit(f[it].y, f[it].x, sh);
-                const uint32_t hi = __builtin_amdgcn_alignbit(f[it].z, f[it].y, sh);
-                *(uint2*)&As[(mrow + MR * it) * LDA + 4 * gs] = make_uint2(lo, hi & mhi);
-            }
-        }
+    swin16_stage_filters<CFG>(As, bias_s, rfilt, a, m0, tid);
+    // the extra row of both patch buffers stays zero
+    if (tid < PITCH / 2) {
+        ((uint32_t*)(Bs0 + SROWS * PITCH))[tid] = 0u;
+        ((uint32_t*)(Bs0 + B_ELEMS + SROWS * PITCH))[tid] = 0u;
     }
     store_rows(grp, st_a, sh_a);
     __syncthreads();
@@ -246,67 +334,17 @@ __global__ __launch_bounds__(CFG::NT) void swin16_kernel(ConvArgs a)
         const elem_t* __restrict__ Bp = Bs0 + buf * B_ELEMS + (((int)oy - row0) * ST * C + h) * PITCH + ST * (int)ox;
         const elem_t* __restrict__ Ap = As + li * LDA + 8 * h;
 
-        typename mma_t::acc_t acc[TMB];
+        typename mma_t::acc_t acc[TMB][1];
 #pragma unroll
         for (int mb = 0; mb < TMB; ++mb)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) acc[mb][v] = 0.0f;
+            for (int v = 0; v < 16; ++v) acc[mb][0][v] = 0.0f;
 
-        // operands of step j+1 are read while step j multiplies
-        uint4 af[2][TMB], bf[2];
-        auto read_step = [&](int j, int slot) {
-            uint32_t bw[4];
-#pragma unroll
-            for (int g = 0; g < 2; ++g) {
-                const int i2 = 2 * j + g, t = i2 / SQ, sq = i2 % SQ;
-                // compile-time, an immediate offset of the read; slots past the last line read the window's start
-                const int off = 2 * t >= NROW ? 0 : 2 * t * PITCH + 4 * sq;
-                uint32_t lo, hi;
-                if constexpr (ST % 4 == 0) {
-                    const uint2 w = *(const uint2*)&Bp[off];
-                    lo = w.x;
-                    hi = w.y;
-                } else {
-                    const uint32_t* w = (const uint32_t*)&Bp[off];
-                    lo = w[0];
-                    hi = w[1];
-                }
-                bw[2 * g] = lo;
-                bw[2 * g + 1] = hi;
-            }
-            bf[slot] = make_uint4(bw[0], bw[1], bw[2], bw[3]);
-#pragma unroll
-            for (int mb = 0; mb < TMB; ++mb) af[slot][mb] = *(const uint4*)&Ap[mb * 32 * LDA + 16 * j];
-        };
-        read_step(0, 0);
-#pragma unroll
-        for (int j = 0; j < KSTEPS; ++j) {
-            if (j + 1 < KSTEPS) read_step(j + 1, (j + 1) & 1);
-            __builtin_amdgcn_sched_barrier(0);  // keep the reads ahead of the products they overlap with
-            // padding taps and lines that do not exist are cleared here, one step after their read was issued
-            uint4 b = bf[j & 1];
-            uint32_t* bw = (uint32_t*)&b;
-#pragma unroll
-            for (int g = 0; g < 2; ++g) {
-                const int i2 = 2 * j + g, t = i2 / SQ, sq = i2 % SQ;
-                const int ntap = 2 * t >= NROW ? 0 : (S - 4 * sq >= 4 ? 4 : S - 4 * sq);
-                // (asm: a plain AND has no tie to this point of the program and is moved up to its read, where it waits;
-                // the s_nop is the gap the hardware needs between a VALU write and an MFMA reading the register, which the
-                // compiler does not insert after inline assembly)
-                if (ntap < 2) asm volatile("v_and_b32 %0, %1, %0\n\ts_nop 1" : "+v"(bw[2 * g]) : "v"(ntap == 1 ? 0x0000FFFFu : 0u));
-                if (ntap < 4) asm volatile("v_and_b32 %0, %1, %0\n\ts_nop 1" : "+v"(bw[2 * g + 1]) : "v"(ntap == 3 ? 0x0000FFFFu : 0u));
-                if (2 * t + 1 >= NROW) {
-                    asm volatile("v_and_b32 %0, %1, %0\n\ts_nop 1" : "+v"(bw[2 * g]) : "v"(last_pair_mask));
-                    asm volatile("v_and_b32 %0, %1, %0\n\ts_nop 1" : "+v"(bw[2 * g + 1]) : "v"(last_pair_mask));
-                }
-            }
-#pragma unroll
-            for (int mb = 0; mb < TMB; ++mb) acc[mb] = mma_t::run(af[j & 1][mb], b, acc[mb]);
-            __builtin_amdgcn_sched_barrier(0);
-        }
+        const elem_t* const Bps[1] = {Bp};
+        swin16_mma_loop<CFG>(Ap, Bps, last_pair_mask, acc);
 
-
-        const float floor_v = a.relu ? 0.0f : -__builtin_inff();
+        // activation: max(x, 0) (a NaN sum becomes 0, as in every other kernel) or the identity (a NaN stays a NaN)
+        auto act = [&](float x) { return a.relu ? __builtin_fmaxf(x, 0.0f) : x; };
         if (a.out_nhwc) {
             // [N][OH][OW][K]: a lane's 4 consecutive channels of a pixel leave as one 8-byte store (K is a multiple of 4)
             const uint32_t vo = p_ok ? (uint32_t)((img * a.OHW + p) * a.K + m0 + 4 * h) * 2u : kFarOffset;
@@ -319,8 +357,8 @@ __global__ __launch_bounds__(CFG::NT) void swin16_kernel(ConvArgs a)
                     uint32_t pk[2];
 #pragma unroll
                     for (int e = 0; e < 2; ++e) {
-                        const float x0 = __builtin_fmaxf(acc[mb][4 * q + 2 * e] + bv[2 * e], floor_v);
-                        const float x1 = __builtin_fmaxf(acc[mb][4 * q + 2 * e + 1] + bv[2 * e + 1], floor_v);
+                        const float x0 = act(acc[mb][0][4 * q + 2 * e] + bv[2 * e]);
+                        const float x1 = act(acc[mb][0][4 * q + 2 * e + 1] + bv[2 * e + 1]);
                         pk[e] = (uint32_t)Prec<DT>::from_f32(x0) | ((uint32_t)Prec<DT>::from_f32(x1) << 16);
                     }
                     const int kr = mb * 32 + q * 8;
@@ -341,7 +379,7 @@ __global__ __launch_bounds__(CFG::NT) void swin16_kernel(ConvArgs a)
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     const int kr = mb * 32 + q * 8 + e;  // row of the tile, without the lane half's 4
-                    const float x = __builtin_fmaxf(acc[mb][4 * q + e] + bv[e], floor_v);
+                    const float x = act(acc[mb][0][4 * q + e] + bv[e]);
                     const uint32_t o = (full || m0 + kr + 4 * h < a.K) ? vo : kFarOffset;
                     buffer_store_elem<elem_t>(Prec<DT>::from_f32(x), rout, o);
                     if (p_ok) vo += e == 3 ? step5 : step1;

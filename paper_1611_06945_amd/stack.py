@@ -108,8 +108,6 @@ class ConvStack:
         """Whether some kernel runs layer i in format `fmt` with the following 3x3 stride-2 pool fused, writing `out_layout`."""
         if (i + 1) not in self.pool_after or (self.pool_win, self.pool_stride) != (3, 2):
             return False
-        if fmt == NCHW and out_layout == NHWC:
-            return False
         d = self._desc(i, fmt, KRSC if fmt == NHWC else KCRS, out_layout == NHWC, maxpool=True)
         return B.conv_variant_count(d) > 0
 

@@ -193,21 +193,21 @@ def test_config5_format_selection_on_a_side_stream_times_the_glue():
 
 
 @pytest.mark.parametrize("dtype", [wl.F16, wl.BF16])
-def test_config5_stack_with_the_second_pool_fused_into_its_convolution(dtype):
-    # fuse_pool fuses every pool that some kernel can run in its epilogue: with channel-innermost layers the 768-pixel
-    # tiles hold a whole 27x27 image, so the pool behind layer 2 goes; the first layer's kernels cannot pool.  With
-    # every layer in [N][C][H][W] no kernel holds a 27x27 image and nothing is fused.
+def test_config5_stack_with_the_pools_fused_into_their_convolutions(dtype):
+    # fuse_pool fuses every pool that some kernel can run in its epilogue.  The first layer's kernel for this pooling
+    # computes tiles of pooled outputs and serves both output layouts; behind layer 2 the pool goes only with
+    # channel-innermost layers, whose 768-pixel tiles hold a whole 27x27 image (no [N][C][H][W] kernel does).
     torch = torch_mod()
     planar = ConvStack([w.shape for w in wl.config5_layers(5, dtype)], dtype, pool_after=wl.STACK_POOL_AFTER, fuse_pool=True)
-    assert planar.fused == [False] * 5
+    assert planar.fused == [True, False, False, False, False]
     del planar
-    stack, shapes, gen, x, filts, biases = _stack_on_device(dtype, 5, formats=["nchw", "nhwc", "nhwc", "nhwc", "nhwc"],
-                                                            fuse_pool=True)
-    assert stack.fused == [False, True, False, False, False]
-    stack.autotune(x, filts, biases)
-    y = stack.run(x, filts, biases)
-    torch.cuda.synchronize()
-    _check_stack_against_oracle(stack, shapes, gen, dtype, y)
+    for formats in (None, ["nchw", "nhwc", "nhwc", "nhwc", "nhwc"]):
+        stack, shapes, gen, x, filts, biases = _stack_on_device(dtype, 5, formats=formats, fuse_pool=True)
+        assert stack.fused == [True, formats is not None, False, False, False]
+        stack.autotune(x, filts, biases)
+        y = stack.run(x, filts, biases)
+        torch.cuda.synchronize()
+        _check_stack_against_oracle(stack, shapes, gen, dtype, y)
 
 
 @pytest.mark.parametrize("formats,fuse_pool", [(None, False), (["nchw", "nhwc", "nhwc", "nhwc", "nhwc"], False),

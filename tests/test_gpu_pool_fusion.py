@@ -128,7 +128,7 @@ def test_fused_maxpool_is_refused_where_no_tile_holds_the_image():
     for shape, dtype, kw in [(ConvShape(2, 32, 27, 27, 32, 3, 3, 1, 1), wl.F16, {}),            # 729 pixels, 3x3 window
                              (ConvShape(2, 32, 13, 13, 32, 5, 5, 1, 2), wl.F32, {}),            # fp32, 5x5 window
                              (ConvShape(2, 32, 13, 13, 32, 3, 3, 2, 1), wl.F16, {}),            # stride 2
-                             (ConvShape(2, 3, 35, 35, 32, 11, 11, 4, 0), wl.F16, {})]:          # first layer
+                             (ConvShape(2, 3, 35, 35, 32, 11, 11, 4, 0), wl.F32, {})]:          # first layer in fp32
         d = B.desc_of(shape, dtype, maxpool=True, **kw)
         assert B.conv_variant_count(d) == 0
         assert L.conv_fwd(ctypes.byref(d), 256, 512, None, 1024, None) == B.CONV_ENOVARIANT
@@ -213,3 +213,106 @@ def test_fused_maxpool_matches_the_sequence_on_nan_sums(dtype, relu):
             got, want = to_host_f64(out, dtype), to_host_f64(seq, dtype)
             assert np.isnan(want).any() != relu, "the sequence's own NaN handling is not what this test assumes"
             assert np.array_equal(got, want, equal_nan=True), "%s: differs from conv + maxpool" % name
+
+
+# First layers (3 channels, 11x11 stride 4 or 7x7 stride 2) whose pool is computed by the convolution kernel itself on
+# tiles of 9x9 pooled outputs.
+FIRST_POOL_SHAPES = [
+    ConvShape(2, 3, 35, 35, 32, 11, 11, 4, 0),     # 7x7 -> 3x3: one partial tile per image
+    ConvShape(2, 3, 91, 99, 96, 11, 11, 4, 2),     # 22x24 -> 10x11: 2x2 tiles, the last row and column of tiles partial; even OW
+    ConvShape(1, 3, 227, 227, 40, 11, 11, 4, 0),   # the stack's first layer at one image: 55x55 -> 27x27 = 3x3 whole tiles; K ragged
+    ConvShape(3, 3, 61, 57, 64, 7, 7, 2, 3),       # 31x29 -> 15x14, rows of odd length
+    ConvShape(2, 3, 224, 224, 64, 7, 7, 2, 3),     # 112x112 -> 55x55: 7x7 tiles, rows of even length
+    ConvShape(2, 3, 40, 44, 20, 7, 7, 2, 0),       # no padding, K below one channel block
+]
+
+
+@pytest.mark.parametrize("out_nhwc", [False, True])
+@pytest.mark.parametrize("dtype", DT16)
+@pytest.mark.parametrize("si", range(len(FIRST_POOL_SHAPES)))
+def test_first_layer_fused_maxpool_every_variant(si, dtype, out_nhwc):
+    torch = torch_mod()
+    shape = FIRST_POOL_SHAPES[si]
+    if out_nhwc and shape.K % 8:
+        pytest.skip("channel-innermost pooled output needs K % 8 == 0")
+    PH, PW = (shape.OH - 3) // 2 + 1, (shape.OW - 3) // 2 + 1
+    oshape = (shape.N, PH, PW, shape.K) if out_nhwc else (shape.N, shape.K, PH, PW)
+    for ints, relu, use_bias in [(True, True, True), (True, False, False), (False, True, True)]:
+        data = data_for(shape, dtype, 4100 + 10 * si, ints)
+        conv = oracle.conv_fwd(wl.storage_to_f64(data["in"], dtype), wl.storage_to_f64(data["filt"], dtype),
+                               data["bias"].astype(np.float64) if use_bias else None,
+                               stride=shape.stride, pad=shape.pad, relu=relu)
+        want = oracle.maxpool_fwd(conv, win=3, stride=2)
+        assert want.shape == (shape.N, shape.K, PH, PW)
+        d_in, d_filt = to_device(data["in"], dtype), to_device(data["filt"], dtype)
+        d_bias = to_device(data["bias"], wl.F32) if use_bias else None
+        fused = B.desc_of(shape, dtype, relu=relu, out_nhwc=out_nhwc, maxpool=True)
+        assert B.conv_out_shape(fused) == (PH, PW)
+        names = [B.conv_variant_name(fused, i) for i in range(B.conv_variant_count(fused))]
+        assert names and all(n.startswith("swinp_") for n in names), names
+        # the two-call sequence: the same layer without the flag (any kernel), then the library's pool
+        plain = B.desc_of(shape, dtype, relu=relu)
+        full = empty_out(shape.out_shape(), dtype)
+        B.conv_fwd(plain, d_in, d_filt, d_bias, full)
+        seq = empty_out(oshape, dtype)
+        B.maxpool_fwd_layout(shape.N, shape.K, shape.OH, shape.OW, 3, 2, dtype, False, out_nhwc, full, seq)
+        torch.cuda.synchronize()
+        seq = to_host_f64(seq, dtype)
+        seq = nchw(seq) if out_nhwc else seq
+        for vi, name in enumerate(names):
+            say("  %s on %s dtype %d out_nhwc=%s ints=%s relu=%s bias=%s" % (name, shape, dtype, out_nhwc, ints, relu, use_bias))
+            got = to_host_f64(run(fused, d_in, d_filt, d_bias, oshape, dtype, vi), dtype)
+            got = nchw(got) if out_nhwc else got
+            assert np.all(np.isfinite(got)), "%s: unwritten or overflowed elements" % name
+            if ints:
+                exp = wl.storage_to_f64(wl.to_storage(want.astype(np.float32), dtype), dtype)
+                bad = np.argwhere(got != exp)
+                assert bad.size == 0, "%s: %d mismatches, first at %s got %r want %r" % (
+                    name, len(bad), tuple(bad[0]), got[tuple(bad[0])], exp[tuple(bad[0])])
+                assert np.array_equal(got, seq), "%s: differs from conv + maxpool" % name
+            else:
+                err = oracle.max_normalised_error(got, want)
+                assert err <= TOL[dtype], "%s: error %.3g" % (name, err)
+                # against the library's own sequence: other kernels sum in another order, so within the tolerance only
+                assert oracle.max_normalised_error(got, seq) <= 2 * TOL[dtype], name
+
+
+@pytest.mark.parametrize("relu", [True, False])
+def test_first_layer_fused_maxpool_on_nan_sums(relu):
+    # as above for the first-layer kernel: with the activation a NaN sum pools as 0, without it the NaN is the result
+    torch = torch_mod()
+    dtype = wl.F16
+    shape = ConvShape(2, 3, 91, 99, 32, 11, 11, 4, 2)
+    data = data_for(shape, dtype, 4300, False)
+    x = wl.storage_to_f64(data["in"], dtype).astype(np.float32)
+    x[0, 1, 40, 40] = np.nan
+    x[1, 2, 0, 98] = np.nan
+    data["in"] = wl.to_storage(x, dtype)
+    PH, PW = (shape.OH - 3) // 2 + 1, (shape.OW - 3) // 2 + 1
+    d_in, d_filt, d_bias = to_device(data["in"], dtype), to_device(data["filt"], dtype), to_device(data["bias"], wl.F32)
+    # every kernel of the layer itself puts its NaNs where the definition has them (none behind the activation)
+    plain = B.desc_of(shape, dtype, relu=relu)
+    conv_nan = np.isnan(oracle.conv_fwd(wl.storage_to_f64(data["in"], dtype), wl.storage_to_f64(data["filt"], dtype),
+                                        data["bias"].astype(np.float64), stride=shape.stride, pad=shape.pad, relu=False))
+    assert conv_nan.any()
+    for vi in range(B.conv_variant_count(plain)):
+        say("  %s relu=%s" % (B.conv_variant_name(plain, vi), relu))
+        got = to_host_f64(run(plain, d_in, d_filt, d_bias, shape.out_shape(), dtype, vi), dtype)
+        assert np.array_equal(np.isnan(got), conv_nan & (not relu)), B.conv_variant_name(plain, vi)
+        assert np.all(np.isfinite(got[~conv_nan]))
+    for out_nhwc in (False, True):
+        oshape = (shape.N, PH, PW, shape.K) if out_nhwc else (shape.N, shape.K, PH, PW)
+        fused = B.desc_of(shape, dtype, relu=relu, out_nhwc=out_nhwc, maxpool=True)
+        full = empty_out(shape.out_shape(), dtype)
+        B.conv_fwd(plain, d_in, d_filt, d_bias, full)
+        seq = empty_out(oshape, dtype)
+        B.maxpool_fwd_layout(shape.N, shape.K, shape.OH, shape.OW, 3, 2, dtype, False, out_nhwc, full, seq)
+        torch.cuda.synchronize()
+        want = to_host_f64(seq, dtype)
+        assert np.isnan(want).any() != relu, "the sequence's own NaN handling is not what this test assumes"
+        for vi in range(B.conv_variant_count(fused)):
+            say("  %s relu=%s out_nhwc=%s" % (B.conv_variant_name(fused, vi), relu, out_nhwc))
+            got = to_host_f64(run(fused, d_in, d_filt, d_bias, oshape, dtype, vi), dtype)
+            assert np.array_equal(np.isnan(got), np.isnan(want)), "NaN results are not where the sequence has them"
+            ok = ~np.isnan(want)
+            assert oracle.max_normalised_error(got[ok], want[ok]) <= 2 * TOL[dtype]
