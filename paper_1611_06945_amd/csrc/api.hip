@@ -256,7 +256,10 @@ double heuristic_cost(const Variant& v, const conv_desc& d, int OH, int OW)
         const double rounds = std::ceil(tiles / 256.0);
         const double pix_waves = (v.tn / 32.0 >= 4.0 && waves >= 8.0) ? 2.0 : 1.0;
         const double mfmas = (v.tm / 32.0) * (v.tn / 32.0 / pix_waves) * (Q / 2.0) / (waves / pix_waves);
-        return 5.0 + 0.05 * waves + rounds * mfmas * 0.030 * std::max(1.0, waves / 4.0);
+        // ... and, when the tiles outnumber the SIMDs, the chip's MFMA rate at the half efficiency these kernels reach
+        // there (filter and input slabs staged through LDS once per workgroup and chunk)
+        const double busy = tiles * waves * mfmas * 0.0305 / 1024.0 / 0.5;
+        return 5.0 + 0.05 * waves + std::max(rounds * mfmas * 0.030 * std::max(1.0, waves / 4.0), busy);
     }
     const bool window = v.family == FAM_WINDOW || (v.traits & TRAIT_WINDOW_TILES);
     double tiles;
