@@ -69,7 +69,9 @@ class Resident:
     """A workload with its tensors in device memory (optionally several rotating copies), in one of three formats:
     "nchw" (the plain contract: [N][C][H][W], [K][C][R][S]), "nhwc" (channel-innermost tensors, filters [K][R][S][C]) or
     "nhwc_packed" (channel-innermost tensors, filters in MFMA operand order).  The conversions of the latter two are
-    explicit library calls made here once, timed, and reported as `convert_us`."""
+    explicit library calls made here once, timed, and reported as `convert_us`.  "nchw_pool" is the plain contract with
+    the 3x3 stride-2 max-pool computed by the convolution kernel (CONV_FLAG_MAXPOOL_3X3S2): the output is the pooled
+    tensor, channel-innermost (what the next layer of the stack reads)."""
 
     def __init__(self, w, copies=1, fmt="nchw"):
         import numpy as np
@@ -80,9 +82,11 @@ class Resident:
 
         self.w, self.B, self.torch, self.fmt = w, B, torch, fmt
         s = w.shape
-        nh = fmt != "nchw"
-        self.desc = B.desc_of(s, w.dtype, relu=True, in_nhwc=nh, out_nhwc=nh, filt_krsc=fmt == "nhwc",
-                              filt_packed=fmt == "nhwc_packed")
+        self.pool = fmt == "nchw_pool"
+        nh = fmt in ("nhwc", "nhwc_packed")
+        self.out_nhwc = nh or self.pool
+        self.desc = B.desc_of(s, w.dtype, relu=True, in_nhwc=nh, out_nhwc=self.out_nhwc, filt_krsc=fmt == "nhwc",
+                              filt_packed=fmt == "nhwc_packed", maxpool=self.pool)
         if B.conv_variant_count(self.desc) <= 0:
             raise ValueError("no kernel serves %s in format %s" % (w.name, fmt))
         self.data = data = w.generate()
@@ -119,7 +123,8 @@ class Resident:
                                "note": "explicit conversions, host-enqueued one by one (includes launch gaps); in a stack the "
                                        "previous layer writes channel-innermost directly and filters convert once"}
             x0, f0 = x1, f1
-        oshape = (s.N, s.OH, s.OW, s.K) if nh else s.out_shape()
+        self.oh, self.ow = B.conv_out_shape(self.desc)   # pooled extent with the fused pool
+        oshape = (s.N, self.oh, self.ow, s.K) if self.out_nhwc else (s.N, s.K, self.oh, self.ow)
         self.sets = []
         for _ in range(copies):
             self.sets.append((x0.clone(), f0.clone(), torch.from_numpy(data["bias"]).cuda(),
@@ -181,7 +186,7 @@ class Resident:
             host = wl.storage_to_f64(o.view(torch.int16).cpu().numpy().view(np.uint16), w.dtype)
         else:
             host = o.cpu().numpy().astype(np.float64)
-        if self.fmt != "nchw":
+        if self.out_nhwc:
             host = np.ascontiguousarray(np.transpose(host, (0, 3, 1, 2)))
         n_out = host.size
         rng = np.random.default_rng(424242)
@@ -190,8 +195,18 @@ class Resident:
         x = wl.storage_to_f64(self.data["in"], w.dtype)
         f = wl.storage_to_f64(self.data["filt"], w.dtype)
         b = self.data["bias"].astype(np.float64)
-        ref = oracle.conv_fwd_points(x, f, b, idx, stride=s.stride, pad=s.pad, relu=True)
-        mag = oracle.conv_fwd_points(np.abs(x), np.abs(f), np.abs(b), idx, stride=s.stride, pad=s.pad, relu=False)
+        if self.pool:
+            # a pooled element is the maximum of the 9 convolution outputs under its window: those from the oracle
+            n_, k_, py, px = np.unravel_index(idx, host.shape)
+            win = np.stack([np.ravel_multi_index((n_, k_, 2 * py + dy, 2 * px + dx), (s.N, s.K, s.OH, s.OW))
+                            for dy in range(3) for dx in range(3)], axis=1).astype(np.int64)
+            ref9 = oracle.conv_fwd_points(x, f, b, win.ravel(), stride=s.stride, pad=s.pad, relu=True).reshape(win.shape)
+            mag9 = oracle.conv_fwd_points(np.abs(x), np.abs(f), np.abs(b), win.ravel(), stride=s.stride, pad=s.pad,
+                                          relu=False).reshape(win.shape)
+            ref, mag = ref9.max(axis=1), mag9.max(axis=1)
+        else:
+            ref = oracle.conv_fwd_points(x, f, b, idx, stride=s.stride, pad=s.pad, relu=True)
+            mag = oracle.conv_fwd_points(np.abs(x), np.abs(f), np.abs(b), idx, stride=s.stride, pad=s.pad, relu=False)
         got = host.ravel()[idx]
         if not np.all(np.isfinite(got)):
             raise RuntimeError("%s via %s: output holds NaN/Inf (unwritten or overflowed elements)" % (w.name, self.variant))
@@ -255,12 +270,23 @@ def cpu_model():
     return "unknown"
 
 
+def algorithmic_bytes(w, r):
+    """Bytes the operation has to move: input + filters + bias + output once each; with the fused pool the output is the
+    pooled tensor (the convolution's own output is never stored)."""
+    from paper_1611_06945_amd import workloads as wl
+
+    s, es = w.shape, wl.DTYPE_BYTES[w.dtype]
+    if not r.pool:
+        return s.algorithmic_bytes(w.dtype)
+    return s.algorithmic_bytes(w.dtype) - (s.N * s.K * s.OH * s.OW - s.N * s.K * r.oh * r.ow) * es
+
+
 def layer_report(w, launches=100, batches=5, rotate_mb=0, fmt="nchw", cpu=True, cpu_one_thread=False):
     from paper_1611_06945_amd import workloads as wl
 
     dt = wl.DTYPE_NAMES[w.dtype]
-    abytes = w.shape.algorithmic_bytes(w.dtype)
     r = Resident(w, fmt=fmt)
+    abytes = algorithmic_bytes(w, r)
     variant = r.autotune()
     med_h, _ = r.time_batches(launches, batches, warmup=20)
     med, mn = r.time_device(launches, batches)
@@ -500,7 +526,7 @@ def main():
     ap.add_argument("--workload", default="cfg4_mid3x3_n20_f32")
     ap.add_argument("--variant", help="run the headline workload on this variant instead of the autotuned one "
                                       "(for profiling one kernel; the figure is then not the headline)")
-    ap.add_argument("--format", choices=["nchw", "nhwc", "nhwc_packed"], default="nchw",
+    ap.add_argument("--format", choices=["nchw", "nhwc", "nhwc_packed", "nchw_pool"], default="nchw",
                     help="tensor formats of the workload (16-bit layers only for the channel-innermost ones); anything but "
                          "nchw is for profiling one kernel: the headline stays on the plain contract")
     ap.add_argument("--probe", action="store_true", help="print the device microbenchmarks (MFMA issue rate by occupancy and "
@@ -607,7 +633,8 @@ def main():
     log("checked %d outputs of the timed run against the oracle: max normalised error %.3g (limit %g), conditioning-relative %.3g" % (
         check["points"], check["max_norm_err"], check["limit"], check["max_cond_rel_err"]))
 
-    mfma_bound = w.shape.flops / (PEAK_TFLOPS[dt] * 1e12) >= w.shape.algorithmic_bytes(w.dtype) / (PEAK_HBM_GBS * 1e9)
+    head_bytes = algorithmic_bytes(w, r)
+    mfma_bound = w.shape.flops / (PEAK_TFLOPS[dt] * 1e12) >= head_bytes / (PEAK_HBM_GBS * 1e9)
     executed = executed_mfma_flops(variant, w.shape)
     if mfma_bound:
         # `achieved` / `frac`: what the matrix units sustain (FLOPs they execute / time), which cannot exceed the peak.  For
@@ -620,7 +647,7 @@ def main():
                 "effective_tflops_direct_flops": round(w.shape.flops / (kern_ms * 1e-3) / 1e12, 3),
                 "effective_frac_direct_flops": round(w.shape.flops / (kern_ms * 1e-3) / 1e12 / PEAK_TFLOPS[dt], 5)}
     else:
-        ach = w.shape.algorithmic_bytes(w.dtype) / (kern_ms * 1e-3) / 1e9
+        ach = head_bytes / (kern_ms * 1e-3) / 1e9
         roof = {"bound": "hbm", "achieved": round(ach, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
                 "frac": round(ach / PEAK_HBM_GBS, 5)}
     # measured ceilings of this very device, next to the published ones
@@ -684,6 +711,8 @@ def main():
         # ahead-of-time conversions, timed separately in `convert_us`): the format the stack planner selects for them
         entries += [(lw, "nhwc_packed") for lw in all_workloads()
                     if lw.dtype == wl.F16 and (lw.name.startswith("cfg4") or lw.name[:7] in ("cfg5_L2", "cfg5_L3", "cfg5_L4", "cfg5_L5"))]
+        # the stack's first layer with its 3x3 stride-2 pool computed by the convolution kernel (pooled output)
+        entries += [(lw, "nchw_pool") for lw in all_workloads() if lw.dtype == wl.F16 and lw.name.startswith("cfg5_L1")]
         for lw, fmt in entries:
             hbmish = lw.name.startswith("cfg2") or lw.name.startswith("cfg5_L1") or (lw.shape.N == 1 and lw.dtype != wl.F32)
             small = lw.name.startswith(("cfg1", "cfg2")) or (lw.name.startswith("cfg4") and lw.shape.N == 1)
