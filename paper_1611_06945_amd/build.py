@@ -20,7 +20,7 @@ CSRC = os.path.join(PKG, "csrc")
 OBJ_DIR = os.path.join(ROOT, "_build")
 LIB = os.path.join(PKG, "libconvfwd.so")
 
-SOURCES = ["api.hip", "igemm_f32.hip", "igemm_f16.hip", "igemm_bf16.hip", "ugemm_f32.hip", "ugemm_f16.hip", "ugemm_bf16.hip", "fc_kernels.hip", "nhwc_f16.hip", "nhwc_bf16.hip", "nwin_f16.hip", "nwin_bf16.hip", "wconv_f32.hip", "wconv_f16.hip", "wconv_bf16.hip", "wino_f32.hip", "swin_f16.hip", "swin_bf16.hip", "swinp_f16.hip", "swinp_bf16.hip", "pwin_f16.hip", "pwin_bf16.hip", "pwk_f32.hip", "pwin32_f32.hip", "aux_kernels.hip", "probe_kernels.hip"]
+SOURCES = ["api.hip", "igemm_f32.hip", "igemm_f16.hip", "igemm_bf16.hip", "ugemm_f32.hip", "ugemm_f16.hip", "ugemm_bf16.hip", "fc_kernels.hip", "nhwc_f16.hip", "nhwc_bf16.hip", "nwin_f16.hip", "nwin_bf16.hip", "wconv_f32.hip", "wconv_f16.hip", "wconv_bf16.hip", "wino_f32.hip", "swin_f16.hip", "swin_bf16.hip", "swinp_f16.hip", "swinp_bf16.hip", "pwin_f16.hip", "pwin_bf16.hip", "pwk_f32.hip", "pwk_f16.hip", "pwk_bf16.hip", "pwin32_f32.hip", "aux_kernels.hip", "probe_kernels.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [

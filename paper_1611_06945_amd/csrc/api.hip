@@ -72,6 +72,8 @@ State& state()
         register_wconv_f16(s->variants);
         register_wconv_bf16(s->variants);
         register_pwk_f32(s->variants);
+        register_pwk_f16(s->variants);
+        register_pwk_bf16(s->variants);
         register_pwin32_f32(s->variants);
         register_pwin_f16(s->variants);
         register_pwin_bf16(s->variants);
@@ -245,9 +247,11 @@ double heuristic_cost(const Variant& v, const conv_desc& d, int OH, int OW)
         const double kw = v.threads / 64.0, tiles = std::ceil(d.K / (double)v.tm) * std::ceil(P / (double)v.tn);
         const double per_cu = std::max(1.0, std::floor(16.0 / kw));
         const double rounds = std::ceil(tiles / (256.0 * per_cu));
-        const double mfmas = std::ceil(d.C / 8.0 / kw) * 4.0 * (v.tm / 32.0) * (v.tn / 32.0);
+        // (16-bit storage: one 32x32x16 MFMA of 16 ns per group of 16 channels, fed by eight 2-byte loads per lane)
+        const bool f32 = d.dtype == CONV_F32;
+        const double mfmas = std::ceil(d.C / (f32 ? 8.0 : 16.0) / kw) * (f32 ? 4.0 : 1.0) * (v.tm / 32.0) * (v.tn / 32.0);
         const double share = std::min(per_cu, std::max(1.0, tiles / 256.0)) * kw / 4.0;  // waves per SIMD
-        return 3.2 + rounds * (0.9 + mfmas * 0.027 * std::max(1.0, share)) + 0.3 + 0.02 * kw;
+        return 3.2 + rounds * (0.9 + mfmas * (f32 ? 0.027 : 0.030) * std::max(1.0, share)) + 0.3 + 0.02 * kw;
     }
     if (v.traits & TRAIT_CHANNEL_WAVES) {
         // one workgroup per (channel tile, run of v.tn pixels); its v.threads / 64 waves split the channels, so a SIMD

@@ -145,6 +145,8 @@ void register_wconv_f16(std::vector<Variant>& out);
 void register_wconv_bf16(std::vector<Variant>& out);
 void register_wino_f32(std::vector<Variant>& out);
 void register_pwk_f32(std::vector<Variant>& out);
+void register_pwk_f16(std::vector<Variant>& out);
+void register_pwk_bf16(std::vector<Variant>& out);
 void register_pwin32_f32(std::vector<Variant>& out);
 void register_pwin_f16(std::vector<Variant>& out);
 void register_pwin_bf16(std::vector<Variant>& out);

@@ -1,4 +1,4 @@
-// Pointwise (1x1, stride 1, no padding) convolution in fp32 for small and mid-sized operations: a GEMM
+// Pointwise (1x1, stride 1, no padding) convolution on the plain formats for small and mid-sized operations: a GEMM
 //     Out[K x P] = Filt[K x C] * X[C x P],   X[c][(n,pix)] = in[n][c][pix]
 // whose whole operand set is a few megabytes, so that its run time is one round of memory latency plus the matrix
 // work, provided every SIMD of the chip has a wave and every wave has all its loads in flight at once.
@@ -13,15 +13,23 @@
 //     wave order through LDS (deterministic), then bias + activation + store.
 //   * Loads run GD groups ahead through a ring of register slots; with few groups per wave everything is in flight
 //     from the first instruction on.
+//   * fp16 / bf16 storage: a lane of a 32x32x16 MFMA feeds 8 consecutive channels (8h .. 8h+7 of a group of 16).  Its
+//     filter values are one 16-byte load; its input values lie one channel plane apart in [N][C][H][W], so they are
+//     eight 2-byte loads (each contiguous along the pixels of the wave: 64-byte runs) put together in pairs.  That is
+//     four times the load instructions of a layout with the channels innermost, which does not matter for the
+//     operations this kernel is for: their run time is latency, not load issue.
 #pragma once
 
 #include "pwin_kernel.h"
 
 namespace convfwd {
 
-template <int KW_, int TMB_, int NBW_, int GD_>
+template <int DT_, int KW_, int TMB_, int NBW_, int GD_>
 struct PwkCfg {
-    static constexpr int KW = KW_, TMB = TMB_, NBW = NBW_, GD = GD_;
+    static constexpr int DT = DT_, KW = KW_, TMB = TMB_, NBW = NBW_, GD = GD_;
+    static constexpr int ES = DT == CONV_F32 ? 4 : 2;      // bytes per stored element
+    static constexpr int GC = DT == CONV_F32 ? 8 : 16;     // channels per group (two lane halves x 4 or 8)
+    static constexpr int HC = GC / 2;                      // channels of a lane half per group
     static constexpr int NT = 64 * KW;
     static_assert(NT <= 1024, "workgroup size");
     static constexpr int TM = 32 * TMB, TNP = 32 * NBW;
@@ -34,9 +42,11 @@ struct PwkCfg {
 template <class CFG>
 __global__ __launch_bounds__(CFG::NT) void pwk_kernel(ConvArgs a)
 {
-    constexpr int KW = CFG::KW, TMB = CFG::TMB, NBW = CFG::NBW, GD = CFG::GD, NT = CFG::NT, TM = CFG::TM, TNP = CFG::TNP;
-    constexpr int RBP = CFG::RBP;
-    typedef Mma<CONV_F32, 32> mma_t;
+    constexpr int DT = CFG::DT, KW = CFG::KW, TMB = CFG::TMB, NBW = CFG::NBW, GD = CFG::GD, NT = CFG::NT, TM = CFG::TM;
+    constexpr int TNP = CFG::TNP, RBP = CFG::RBP, ES = CFG::ES, GC = CFG::GC, HC = CFG::HC;
+    constexpr bool F32 = DT == CONV_F32;
+    typedef typename Prec<DT>::elem_t elem_t;
+    typedef Mma<DT, 32> mma_t;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
 
     const int tid = threadIdx.x, lane = tid & 63;
@@ -58,45 +68,50 @@ __global__ __launch_bounds__(CFG::NT) void pwk_kernel(ConvArgs a)
     const __amdgpu_buffer_rsrc_t rin = make_rsrc(a.in, a.in_bytes);
     const __amdgpu_buffer_rsrc_t rfilt = make_rsrc(a.filt, a.filt_bytes);
 
-    // per-lane byte offsets at channel 0 of the lane's half (h selects channels 4h .. 4h+3 of every group)
+    // per-lane byte offsets at channel 0 of the lane's half (h selects channels HC*h .. HC*h + HC-1 of every group)
     uint32_t a_off[TMB], b_off[NBW];
 #pragma unroll
     for (int mb = 0; mb < TMB; ++mb) {
         const int k = m0 + mb * 32 + li;
-        a_off[mb] = k < a.K ? (uint32_t)(k * a.C + 4 * h) * 4u : kOutOfRange;
+        a_off[mb] = k < a.K ? (uint32_t)(k * a.C + HC * h) * (uint32_t)ES : kOutOfRange;
     }
 #pragma unroll
     for (int nb = 0; nb < NBW; ++nb) {
         const int p = p0 + nb * 32 + li;
         uint32_t n, pix;
         a.dHW.divmod((uint32_t)(p < a.P ? p : 0), n, pix);
-        b_off[nb] = p < a.P ? (uint32_t)(((int)n * a.C + 4 * h) * a.HW + (int)pix) * 4u : kOutOfRange;
+        b_off[nb] = p < a.P ? (uint32_t)(((int)n * a.C + HC * h) * a.HW + (int)pix) * (uint32_t)ES : kOutOfRange;
     }
-    const int G = a.C >> 3;                  // groups of 8 channels
+    const int G = a.C / GC;                  // groups of GC channels
     const int NG = (G - kw + KW - 1) / KW;   // groups of this wave: kw, kw + KW, ...
-    const uint32_t hw4 = (uint32_t)a.HW * 4u;
+    const uint32_t hw4 = (uint32_t)a.HW * (uint32_t)ES;  // bytes from one channel plane to the next
 
-    f32x4 ar[GD][TMB];
-    float br[GD][NBW][4];
+    u32x4 ar[GD][TMB];                       // fp32: 4 channels; 16-bit: 8 channels
+    uint32_t br[GD][NBW][4];                 // fp32: 4 channels; 16-bit: 4 pairs of channels
     // loads of this wave's i-th group into ring slot `slot`; past the wave's last group every lane is pointed out of
     // range (the loads return zero and the products add nothing), so the sequence is the same for every wave
     auto load_group = [&](auto slot_c, int i) {
         constexpr int slot = decltype(slot_c)::value;
         const int g = kw + i * KW;
         const bool live = i < NG;
-        const uint32_t ca = (uint32_t)g * 32u;          // 8 channels * 4 bytes along a filter row
-        const uint32_t cb = (uint32_t)g * 8u * hw4;     // 8 channel planes
+        const uint32_t ca = (uint32_t)g * 32u;              // GC channels along a filter row: 32 bytes in every type
+        const uint32_t cb = (uint32_t)g * (uint32_t)GC * hw4;  // GC channel planes
 #pragma unroll
-        for (int mb = 0; mb < TMB; ++mb) {
-            const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rfilt, (int)((live && a_off[mb] != kOutOfRange) ? a_off[mb] + ca : kOutOfRange), 0, 0);
-            ar[slot][mb] = __builtin_bit_cast(f32x4, v);
-        }
+        for (int mb = 0; mb < TMB; ++mb)
+            ar[slot][mb] = __builtin_amdgcn_raw_buffer_load_b128(rfilt, (int)((live && a_off[mb] != kOutOfRange) ? a_off[mb] + ca : kOutOfRange), 0, 0);
 #pragma unroll
         for (int nb = 0; nb < NBW; ++nb) {
             const uint32_t base = (live && b_off[nb] != kOutOfRange) ? b_off[nb] + cb : kOutOfRange;
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
-                br[slot][nb][j] = buffer_load_elem<float>(rin, base == kOutOfRange ? kOutOfRange : base + (uint32_t)j * hw4);
+            for (int j = 0; j < 4; ++j) {
+                if constexpr (F32) {
+                    br[slot][nb][j] = buffer_load_elem<uint32_t>(rin, base == kOutOfRange ? kOutOfRange : base + (uint32_t)j * hw4);
+                } else {
+                    const uint32_t lo = buffer_load_elem<uint16_t>(rin, base == kOutOfRange ? kOutOfRange : base + (uint32_t)(2 * j) * hw4);
+                    const uint32_t hi = buffer_load_elem<uint16_t>(rin, base == kOutOfRange ? kOutOfRange : base + (uint32_t)(2 * j + 1) * hw4);
+                    br[slot][nb][j] = lo | (hi << 16);
+                }
+            }
         }
     };
 
@@ -113,12 +128,25 @@ __global__ __launch_bounds__(CFG::NT) void pwk_kernel(ConvArgs a)
     for (int r = 0; r < rounds; ++r) {
         static_for<GD>([&](auto sc) {
             constexpr int slot = decltype(sc)::value;
+            if constexpr (F32) {
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
+                for (int j = 0; j < 4; ++j)
+#pragma unroll
+                    for (int mb = 0; mb < TMB; ++mb)
+#pragma unroll
+                        for (int nb = 0; nb < NBW; ++nb) {
+                            // (copies first: a bit cast applied directly to a vector element reads the vector's first element)
+                            const uint32_t av = ar[slot][mb][j], bv = br[slot][nb][j];
+                            acc[mb][nb] = mma_t::run(__builtin_bit_cast(float, av), __builtin_bit_cast(float, bv), acc[mb][nb]);
+                        }
+            } else {
 #pragma unroll
                 for (int mb = 0; mb < TMB; ++mb)
 #pragma unroll
-                    for (int nb = 0; nb < NBW; ++nb) acc[mb][nb] = mma_t::run(ar[slot][mb][j], br[slot][nb][j], acc[mb][nb]);
+                    for (int nb = 0; nb < NBW; ++nb)
+                        acc[mb][nb] = mma_t::run(make_uint4(ar[slot][mb].x, ar[slot][mb].y, ar[slot][mb].z, ar[slot][mb].w),
+                                                 make_uint4(br[slot][nb][0], br[slot][nb][1], br[slot][nb][2], br[slot][nb][3]), acc[mb][nb]);
+            }
             load_group(sc, (r + 1) * GD + slot);
         });
     }
@@ -149,7 +177,7 @@ __global__ __launch_bounds__(CFG::NT) void pwk_kernel(ConvArgs a)
     const bool pok = rg0 < CPT && p < a.P;
     uint32_t n, pix;
     a.dHW.divmod((uint32_t)(pok ? p : 0), n, pix);
-    uint32_t o = (uint32_t)(((int)n * a.K + m0 + rg0 * 4) * a.HW + (int)pix) * 4u;
+    uint32_t o = (uint32_t)(((int)n * a.K + m0 + rg0 * 4) * a.HW + (int)pix) * (uint32_t)ES;
     const float* src = &red[col * RBP];
     for (int rg = rg0; rg < RG; rg += CPT) {
         f32x4 x = *(const f32x4*)&src[rg * 4];
@@ -161,7 +189,7 @@ __global__ __launch_bounds__(CFG::NT) void pwk_kernel(ConvArgs a)
             float y = x[i] + bv[i];
             if (a.relu) y = y > 0.0f ? y : 0.0f;
             const bool oki = pok && m0 + rg * 4 + i < a.K;
-            buffer_store_elem<float>(y, rout, oki ? o + (uint32_t)i * hw4 : kOutOfRange);
+            buffer_store_elem<elem_t>(Prec<DT>::from_f32(y), rout, oki ? o + (uint32_t)i * hw4 : kOutOfRange);
         }
         o += 4u * CPT * hw4;
     }
@@ -181,16 +209,16 @@ hipError_t pwk_launch(const Variant&, ConvArgs& a, hipStream_t s)
 template <class CFG>
 bool pwk_valid(const Variant&, const conv_desc& d, int OH, int OW)
 {
-    if (d.dtype != CONV_F32 || d.R != 1 || d.S != 1 || d.stride != 1 || d.pad != 0) return false;
+    if (d.dtype != CFG::DT || d.R != 1 || d.S != 1 || d.stride != 1 || d.pad != 0) return false;
     if (d.flags & ~(uint32_t)CONV_FLAG_RELU) return false;  // plain formats, no fused pool
-    if ((d.C % 8) != 0) return false;
+    if ((d.C % CFG::GC) != 0) return false;
     const long long P = (long long)d.N * OH * OW;
     const long long tiles = ((P + CFG::TNP - 1) / CFG::TNP) * ((d.K + CFG::TM - 1) / CFG::TM);
     if (tiles > 0x7fffffffLL) return false;
     const long long lim = 1LL << 31;  // byte offsets are formed in 32 bits, with room for the look-ahead past the end
     if ((long long)d.N * d.C * d.H * d.W * 4 >= lim || (long long)d.K * d.C * 4 >= lim || (long long)d.K * P * 4 >= lim) return false;
-    // a wave needs at least one group of 8 channels; beyond 4 idle rounds the split only costs
-    if (d.C / 8 < CFG::KW) return false;
+    // a wave needs at least one group of channels
+    if (d.C / CFG::GC < CFG::KW) return false;
     return true;
 }
 
@@ -199,13 +227,13 @@ void pwk_register(std::vector<Variant>& out)
 {
     Variant v;
     char buf[160];
-    snprintf(buf, sizeof buf, "pwk_f32_M%dN%d_w%d_g%d", CFG::TM, CFG::TNP, CFG::KW, CFG::GD);
+    snprintf(buf, sizeof buf, "pwk_%s_M%dN%d_w%d_g%d", dtype_name(CFG::DT), CFG::TM, CFG::TNP, CFG::KW, CFG::GD);
     v.name = buf;
-    v.dtype = CONV_F32;
+    v.dtype = CFG::DT;
     v.split = 1;
     v.tm = CFG::TM;
     v.tn = CFG::TNP;
-    v.tk = 8 * CFG::KW;
+    v.tk = CFG::GC * CFG::KW;
     v.threads = CFG::NT;
     v.family = FAM_POINTWISE;
     v.specificity = 6;

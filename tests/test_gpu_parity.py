@@ -67,6 +67,8 @@ SMALL_SHAPES = [
     ConvShape(4, 16, 7, 9, 24, 5, 5, 1, 2),     # fp32 window kernel with channel-waves, 5x5: chunks of 8 channels, pixel tiles straddle images
     ConvShape(3, 72, 6, 10, 50, 1, 1, 1, 0),    # pointwise with the channels split over the waves of a workgroup: 9 groups of 8 channels over 4 or 8 waves, ragged K and pixel tiles
     ConvShape(2, 136, 5, 7, 100, 1, 1, 1, 0),   # the same over 16 waves (17 groups), tiles straddle images, odd row length
+    ConvShape(3, 144, 6, 10, 50, 1, 1, 1, 0),   # the same in 16-bit storage: 9 groups of 16 channels over 4 or 8 waves
+    ConvShape(2, 272, 5, 7, 100, 1, 1, 1, 0),   # 17 groups of 16 channels over 16 waves, odd row length (2-byte rows at odd offsets)
 ]
 
 
