@@ -316,3 +316,45 @@ def test_first_layer_fused_maxpool_on_nan_sums(relu):
             assert np.array_equal(np.isnan(got), np.isnan(want)), "NaN results are not where the sequence has them"
             ok = ~np.isnan(want)
             assert oracle.max_normalised_error(got[ok], want[ok]) <= 2 * TOL[dtype]
+
+
+@pytest.mark.parametrize("dtype", DT16)
+def test_first_layer_fused_maxpool_random_shapes(dtype):
+    # seeded random first layers (any image size from "one pooling window" up, any padding below the window, ragged K, both
+    # output layouts): every pooled element against the oracle's convolution followed by its pool
+    torch = torch_mod()
+    rng = np.random.default_rng(4400 + dtype)
+    for si in range(10):
+        R, stride = [(11, 4), (7, 2)][int(rng.integers(0, 2))]
+        lo = R + 2 * stride   # at least 3 convolution outputs per side: one pooling window
+        shape = ConvShape(int(rng.choice([1, 2, 3])), 3, int(rng.integers(lo, 150)), int(rng.integers(lo, 150)),
+                          int(rng.choice([8, 20, 32, 40, 64, 96, 100, 136])), R, R, stride, int(rng.integers(0, 4)))
+        out_nhwc = bool(rng.integers(0, 2)) and shape.K % 8 == 0
+        relu = bool(rng.integers(0, 4))
+        use_bias = bool(rng.integers(0, 4))
+        PH, PW = (shape.OH - 3) // 2 + 1, (shape.OW - 3) // 2 + 1
+        oshape = (shape.N, PH, PW, shape.K) if out_nhwc else (shape.N, shape.K, PH, PW)
+        for ints in (True, False):
+            data = data_for(shape, dtype, 4500 + 10 * si, ints)
+            conv = oracle.conv_fwd(wl.storage_to_f64(data["in"], dtype), wl.storage_to_f64(data["filt"], dtype),
+                                   data["bias"].astype(np.float64) if use_bias else None,
+                                   stride=shape.stride, pad=shape.pad, relu=relu)
+            want = oracle.maxpool_fwd(conv, win=3, stride=2)
+            d_in, d_filt = to_device(data["in"], dtype), to_device(data["filt"], dtype)
+            d_bias = to_device(data["bias"], wl.F32) if use_bias else None
+            fused = B.desc_of(shape, dtype, relu=relu, out_nhwc=out_nhwc, maxpool=True)
+            names = [B.conv_variant_name(fused, i) for i in range(B.conv_variant_count(fused))]
+            assert names, "no variant pools %s" % (shape,)
+            for vi, name in enumerate(names):
+                say("  %s on %s dtype %d out_nhwc=%s ints=%s relu=%s bias=%s" % (name, shape, dtype, out_nhwc, ints, relu, use_bias))
+                got = to_host_f64(run(fused, d_in, d_filt, d_bias, oshape, dtype, vi), dtype)
+                got = nchw(got) if out_nhwc else got
+                assert np.all(np.isfinite(got)), "%s: unwritten or overflowed elements" % name
+                if ints:
+                    exp = wl.storage_to_f64(wl.to_storage(want.astype(np.float32), dtype), dtype)
+                    bad = np.argwhere(got != exp)
+                    assert bad.size == 0, "%s on %s: %d mismatches, first at %s got %r want %r" % (
+                        name, shape, len(bad), tuple(bad[0]), got[tuple(bad[0])], exp[tuple(bad[0])])
+                else:
+                    err = oracle.max_normalised_error(got, want)
+                    assert err <= TOL[dtype], "%s on %s: error %.3g" % (name, shape, err)
