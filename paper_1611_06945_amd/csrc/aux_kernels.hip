@@ -335,6 +335,8 @@ __global__ __launch_bounds__(256) void transpose_kernel(const E* __restrict__ in
 // Filters [K][C][R][S] -> the MFMA operand order of the packed-filter window kernels:
 // out[row block rb][16-channel group c16][tap t][half g][row m][8 channels j] = filt[rb*32 + m][c16*16 + g*8 + j][t],
 // zero for rows past K.  One thread writes one 16-byte vector (the 8 channels one lane feeds to a 32x32x16 MFMA).
+// This version gathers its 8 values straight from memory: every lane touches another filter row, so it is the fallback
+// for windows too large for the LDS version below.
 __global__ __launch_bounds__(256) void pack_filters16_kernel(const uint16_t* __restrict__ filt, uint4* __restrict__ out, int K,
                                                             int C, int RS, int nvec)
 {
@@ -357,16 +359,52 @@ __global__ __launch_bounds__(256) void pack_filters16_kernel(const uint16_t* __r
     out[v] = make_uint4(w[0], w[1], w[2], w[3]);
 }
 
+// The same conversion for one (row block, 16-channel group) per workgroup, through LDS: the 32 rows' pieces (16 channels x
+// RS taps, contiguous in [K][C][R][S] and 16-byte aligned because C is a multiple of 16) come in as 16-byte vectors, the
+// 8 values of an output vector are gathered from LDS, and consecutive threads write consecutive output vectors.
+// `lds` holds 32 rows of 16*RS + 8 elements.
+constexpr int kPackMaxRS = 49;  // 7x7: 25 KB of LDS per workgroup
+__device__ __forceinline__ void pack_block16(const uint16_t* __restrict__ filt, uint4* __restrict__ out, int K, int C, int RS, int blk,
+                                             uint16_t* lds)
+{
+    const int C16 = C >> 4, rb = blk / C16, c16 = blk - rb * C16;
+    const int pitch = 16 * RS + 8, vrow = 2 * RS;  // elements per LDS row; 16-byte vectors per row piece
+    for (int v = threadIdx.x; v < 32 * vrow; v += 256) {
+        const int row = v / vrow, q = v - row * vrow, k = rb * 32 + row;
+        uint4 x = make_uint4(0, 0, 0, 0);
+        if (k < K) x = *(const uint4*)(filt + ((size_t)k * C + c16 * 16) * RS + q * 8);
+        *(uint4*)&lds[row * pitch + q * 8] = x;
+    }
+    __syncthreads();
+    uint4* dst = out + (size_t)blk * RS * 64;
+    for (int v = threadIdx.x; v < 64 * RS; v += 256) {
+        const int m = v & 31, g = (v >> 5) & 1, t = v >> 6;
+        const uint16_t* src = &lds[m * pitch + g * 8 * RS + t];
+        uint32_t w[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) w[j] = (uint32_t)src[2 * j * RS] | ((uint32_t)src[(2 * j + 1) * RS] << 16);
+        dst[v] = make_uint4(w[0], w[1], w[2], w[3]);
+    }
+}
+
+__global__ __launch_bounds__(256) void pack_filters16_lds_kernel(const uint16_t* __restrict__ filt, uint4* __restrict__ out, int K,
+                                                                int C, int RS)
+{
+    extern __shared__ __attribute__((aligned(16))) uint16_t pack_lds[];
+    pack_block16(filt, out, K, C, RS, blockIdx.x, pack_lds);
+}
+
 // Both conversions a packed-filter kernel needs when it serves a layer handed over in the plain formats, in ONE launch
 // ahead of it: blocks [0, in_blocks) transpose the input [N][C][HW] -> [N][HW][C] (32 x 32 tiles through LDS), the
-// remaining blocks write the filters in MFMA operand order (as pack_filters16_kernel).
+// remaining blocks write the filters in MFMA operand order (one (row block, channel group) each, as above).
 __global__ __launch_bounds__(256) void prep16_kernel(const uint16_t* __restrict__ in, uint16_t* __restrict__ in_out, int C, int HW,
                                                     int tiles_s, int tiles_c, int in_blocks, const uint16_t* __restrict__ filt,
-                                                    uint4* __restrict__ filt_out, int K, int RS, int nvec)
+                                                    uint4* __restrict__ filt_out, int K, int RS)
 {
-    __shared__ uint16_t tile[32][33];
+    extern __shared__ __attribute__((aligned(16))) uint16_t pack_lds[];
     const int b = blockIdx.x;
     if (b < in_blocks) {
+        uint16_t(*tile)[33] = (uint16_t(*)[33])pack_lds;  // [32][33]
         const int per_img = tiles_s * tiles_c;
         const int a = b / per_img, rem = b - a * per_img;
         const int b0 = (rem / tiles_s) * 32, s0 = (rem % tiles_s) * 32;
@@ -386,43 +424,38 @@ __global__ __launch_bounds__(256) void prep16_kernel(const uint16_t* __restrict_
         }
         return;
     }
-    const int v = (b - in_blocks) * 256 + threadIdx.x;
-    if (v >= nvec) return;
-    const int m = v & 31, g = (v >> 5) & 1;
-    int rest = v >> 6;
-    const int t = rest % RS;
-    rest /= RS;
-    const int C16 = C >> 4, c16 = rest % C16, rb = rest / C16;
-    const int k = rb * 32 + m, c = c16 * 16 + g * 8;
-    uint32_t w[4] = {0, 0, 0, 0};
-    if (k < K) {
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            const uint32_t h = filt[((size_t)k * C + c + j) * RS + t];
-            w[j >> 1] |= h << ((j & 1) * 16);
-        }
-    }
-    filt_out[v] = make_uint4(w[0], w[1], w[2], w[3]);
+    pack_block16(filt, filt_out, K, C, RS, b - in_blocks, pack_lds);
 }
 
-hipError_t launch_prep16(const void* in, void* in_out, int N, int C, int HW, const void* filt, void* filt_out, int K, int RS,
-                         hipStream_t s)
-{
-    const int tiles_s = (HW + 31) / 32, tiles_c = (C + 31) / 32;
-    const long long in_blocks = (long long)N * tiles_s * tiles_c;
-    const long long nvec = (long long)((K + 31) / 32) * 32 * (C / 16) * RS * 2;
-    const long long blocks = in_blocks + (nvec + 255) / 256;
-    if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(prep16_kernel, dim3((unsigned)blocks), dim3(256), 0, s, (const uint16_t*)in, (uint16_t*)in_out, C, HW,
-                       tiles_s, tiles_c, (int)in_blocks, (const uint16_t*)filt, (uint4*)filt_out, K, RS, (int)nvec);
-    return hipGetLastError();
-}
+static size_t pack_lds_bytes(int RS) { return sizeof(uint16_t) * 32 * (size_t)(16 * RS + 8); }
 
 hipError_t launch_pack_filters16(const void* filt, void* out, int K, int C, int RS, hipStream_t s)
 {
+    if (RS <= kPackMaxRS) {
+        const long long blocks = (long long)((K + 31) / 32) * (C / 16);
+        if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+        hipLaunchKernelGGL(pack_filters16_lds_kernel, dim3((unsigned)blocks), dim3(256), pack_lds_bytes(RS), s, (const uint16_t*)filt,
+                           (uint4*)out, K, C, RS);
+        return hipGetLastError();
+    }
     const long long nvec = (long long)((K + 31) / 32) * 32 * (C / 16) * RS * 2;
     hipLaunchKernelGGL(pack_filters16_kernel, dim3((unsigned)((nvec + 255) / 256)), dim3(256), 0, s, (const uint16_t*)filt,
                        (uint4*)out, K, C, RS, (int)nvec);
+    return hipGetLastError();
+}
+
+// (the packed-filter window kernels exist for 3x3 and 5x5 windows: RS <= kPackMaxRS always holds here)
+hipError_t launch_prep16(const void* in, void* in_out, int N, int C, int HW, const void* filt, void* filt_out, int K, int RS,
+                         hipStream_t s)
+{
+    if (RS > kPackMaxRS) return hipErrorInvalidValue;
+    const int tiles_s = (HW + 31) / 32, tiles_c = (C + 31) / 32;
+    const long long in_blocks = (long long)N * tiles_s * tiles_c;
+    const long long blocks = in_blocks + (long long)((K + 31) / 32) * (C / 16);
+    if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+    const size_t lds = std::max(pack_lds_bytes(RS), sizeof(uint16_t) * 32 * 33);
+    hipLaunchKernelGGL(prep16_kernel, dim3((unsigned)blocks), dim3(256), lds, s, (const uint16_t*)in, (uint16_t*)in_out, C, HW,
+                       tiles_s, tiles_c, (int)in_blocks, (const uint16_t*)filt, (uint4*)filt_out, K, RS);
     return hipGetLastError();
 }
 
