@@ -452,6 +452,12 @@ def sweep_appendix_a(batch, dtype, table_out=None, launches=100, batches=5):
                     "bound": "mfma" if t_mfma >= t_hbm else "hbm",
                     "frac_roofline": round(max(t_mfma, t_hbm) / (med * 1e-3), 5),
                     "n_variants": n})
+        executed = executed_mfma_flops(chosen, w.shape)
+        if ops[-1]["bound"] == "mfma" and executed != w.shape.flops:
+            # a Winograd variant: the fraction of the MFMA peak counts the FLOPs the matrix units execute (never above 1);
+            # the rate by the direct definition's FLOP count stays in `gflops` and `effective_frac_direct_flops`
+            ops[-1]["effective_frac_direct_flops"] = ops[-1]["frac_roofline"]
+            ops[-1]["frac_roofline"] = round(executed / (PEAK_TFLOPS[dt] * 1e12) / (med * 1e-3), 5)
         if ops[-1]["bound"] == "hbm":
             # stream-bound operation: repeat over enough distinct tensor sets to defeat the 256 MB last-level cache
             copies = max(2, int(600e6 / abytes) + 1)
@@ -485,9 +491,13 @@ def sweep_appendix_a(batch, dtype, table_out=None, launches=100, batches=5):
     }
     if table_out:
         with open(table_out, "w") as fh:
+            fh.write("command (repo root, one MI355X): python3 bench.py --sweep appendix_a --sweep-batch %d --sweep-dtype %s --table-out %s\n\n"
+                     % (batch, dt, table_out))
             fh.write("ms: per launch, device events around batches of launches issued by the library (conv_time_us; median); "
                      "tuner us: the same variant as timed by the autotuner; one-variant us: the single variant valid on "
-                     "every operation with the smallest total, timed the same way; gain = one-variant / tuner.\n\n")
+                     "every operation with the smallest total, timed the same way; gain = one-variant / tuner.  GFLOP and "
+                     "GFLOP/s count the FLOPs of the direct definition; for a Winograd variant (wino_*) the fraction of the roofline "
+                     "counts the FLOPs its matrix instructions execute (2.25x fewer).\n\n")
             fh.write("| # | operation (KSZ,S,OC, in -> out) | GFLOP | variant | ms | tuner us | GFLOP/s | bound | frac of roofline | one-variant us | gain |\n")
             fh.write("|---|---|---|---|---|---|---|---|---|---|---|\n")
             for i, o in enumerate(ops):
