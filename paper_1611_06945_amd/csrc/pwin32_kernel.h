@@ -19,6 +19,17 @@
 
 #include "pwin_kernel.h"
 
+// Compile-time experiment hook (0 in the product): bit 16 = workgroups write phase time stamps (100 MHz ticks) into the
+// workspace, 8 per workgroup, when one is passed.
+#ifndef PWIN32_EXP
+#define PWIN32_EXP 0
+#endif
+#if PWIN32_EXP & 16
+#define PWIN32_STAMP(i) do { if (tid == 0 && a.ws) ((unsigned long long*)a.ws)[(size_t)blockIdx.x * 8 + (i)] = wall_clock64(); } while (0)
+#else
+#define PWIN32_STAMP(i) do { } while (0)
+#endif
+
 namespace convfwd {
 
 template <int R_, int S_, int KW_, int WN_, int TMB_, int NBW_, int CPW_, int SLOTS_, int PD_ = 1>
@@ -86,6 +97,7 @@ __global__ __launch_bounds__(CFG::NT) void pwin32_kernel(ConvArgs a)
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int kw = wave % KW, wn = wave / KW;
     const int li = lane & 31, h = lane >> 5;
+    PWIN32_STAMP(0);
 
     const int PT = (int)a.dX.d, PWs = (int)a.dY.d, PHs = (int)a.dZ.d;
     const int MT = (a.K + TM - 1) / TM, T = MT * PT;
@@ -176,10 +188,12 @@ __global__ __launch_bounds__(CFG::NT) void pwin32_kernel(ConvArgs a)
             for (int v = 0; v < 16; ++v) acc[mb][nb][v] = 0.0f;
 
     const int nchunks = a.C / CB;
+    PWIN32_STAMP(1);
     load_chunk(0);
     store_chunk(0);
     load_chunk(1);  // unconditional: with a single chunk the data is never used
     __syncthreads();
+    PWIN32_STAMP(2);
 
     constexpr int STEPS = (CPW / 2) * RS;  // MFMA steps of a wave per chunk: (channel pair, tap)
     float af[SETS][TMB], bf[SETS][NBW];
@@ -231,6 +245,7 @@ __global__ __launch_bounds__(CFG::NT) void pwin32_kernel(ConvArgs a)
         do_chunk(std::false_type{}, std::false_type{}, chunk);
     }
 
+    PWIN32_STAMP(3);
     // ---- add the KW channel-waves' partial sums in wave order, then bias + activation + store ----------------------
     float* const red = (float*)smem_raw;  // [KW][TNP][RBP] + [RB] bias
     const __amdgpu_buffer_rsrc_t rbias = make_rsrc(a.bias, a.bias ? (uint32_t)a.K * 4u : 0u);
@@ -288,6 +303,7 @@ __global__ __launch_bounds__(CFG::NT) void pwin32_kernel(ConvArgs a)
             }
         }
     }
+    PWIN32_STAMP(4);
 }
 
 template <class CFG>
