@@ -66,9 +66,11 @@ enum {
      * rule for fusing an operation into the write of the convolution result, Section 3 "Graph-level Optimizations").
      * Needs OH, OW >= 3.  Served by the window kernels whose workgroup holds a whole output image (stride 1; fp16/bf16:
      * OH*OW <= 192 for 3x3 and 5x5 windows, <= 768 for 5x5 channel-innermost; fp32: 3x3 windows, OH*OW <= 208, planar
-     * tensors); other descriptors give CONV_ENOVARIANT and the caller
+     * tensors), and for fp16/bf16 first layers (C = 3; 11x11 stride 4 or 7x7 stride 2; any image size; planar input,
+     * pooled output in either format, K % 8 == 0 for the channel-innermost one) by a kernel whose workgroups compute tiles
+     * of pooled outputs; other descriptors give CONV_ENOVARIANT and the caller
      * runs maxpool_fwd() behind the convolution.  The result is bit-identical to that sequence run with the same
-     * variant, NaN sums included (with the activation they become 0 before the pool, as in the sequence; without it a
+     * variant (for the first-layer kernel: with a kernel that sums in the same order), NaN sums included (with the activation they become 0 before the pool, as in the sequence; without it a
      * NaN in the window is the result); only the sign of a zero result can differ when the activation is the identity.
      * Not combinable with CONV_FLAG_FILT_WINOGRAD. */
     CONV_FLAG_MAXPOOL_3X3S2 = 32u,
