@@ -355,35 +355,51 @@ class ConvStack:
         x_scratch = torch.empty_like(x)
         x_cvt = self._time_op(lambda: B.conv_convert_layout(
             s0.N, s0.C, s0.H * s0.W, self.dtype, x, x_scratch)) if self.nhwc_capable(0) else float("inf")
-        # best[i][fmt] = cheapest time of layers 0..i-1 plus glue, arriving at layer i with its input in layout fmt
-        best = [{NCHW: 0.0, NHWC: x_cvt}]
-        back = []
-        for i in range(n):
-            nxt, bk = {}, {}
-            for want in (NCHW, NHWC):            # layout handed on after layer i
-                if i == n - 1 and want != NCHW:
-                    continue
-                for (fmt, olay), t in conv_t[i].items():
-                    # a pool converts from olay to `want`; without a pool the kernel may write `want` itself
-                    total = best[i].get(fmt, float("inf")) + t + glue_t[i][(olay, want)]
-                    if total < nxt.get(want, float("inf")):
-                        nxt[want], bk[want] = total, (fmt, olay, False)
-                for (fmt, olay), t in fused_t[i].items():
-                    total = best[i].get(fmt, float("inf")) + t
-                    if olay == want and total < nxt.get(want, float("inf")):
-                        nxt[want], bk[want] = total, (fmt, olay, True)
-            best.append(nxt)
-            back.append(bk)
-        want, chosen, olays, fused = NCHW, [None] * n, [None] * n, [False] * n
-        for i in range(n - 1, -1, -1):
-            fmt, olay, fz = back[i][want]
-            chosen[i], olays[i], fused[i] = fmt, olay, fz
-            want = fmt
+        chosen, olays, fused, total = plan_formats(conv_t, fused_t, glue_t, x_cvt)
         self.plan_times = {"conv_us": conv_t, "glue_us": glue_t, "fused_pool_us": fused_t, "input_convert_us": x_cvt,
-                           "total_us": best[n][NCHW]}
+                           "total_us": total}
         self.formats = chosen
         self.out_layouts = olays
         self.fused = fused
         self.filt_formats = [(KRSC if chosen[i] == NHWC else KCRS) if fused[i] else filt_pick[i][(chosen[i], olays[i])]
                              for i in range(n)]
         self._build()
+
+
+def plan_formats(conv_t, fused_t, glue_t, x_cvt):
+    """The cheapest assignment of data formats over a chain of layers, by dynamic programming (pure host logic).
+
+    conv_t[i][(fmt, olay)]: microseconds of layer i run in format `fmt` writing layout `olay`; fused_t[i][(fmt, olay)]:
+    the same with the following pool computed by the convolution (`olay` is then the pooled tensor's layout);
+    glue_t[i][(olay, want)]: microseconds of what turns layout `olay` into the layout `want` handed to layer i + 1 (the
+    pool behind layer i, which converts on the way, or an explicit conversion; 0 where nothing is needed); x_cvt: the
+    conversion of the stack's planar input to channel-innermost (inf if layer 0 has no such kernel).  The last layer
+    hands on [N][C][H][W].  Returns (format per layer, output layout per layer, pool fused per layer, total)."""
+    n = len(conv_t)
+    # best[i][fmt] = cheapest time of layers 0..i-1 plus glue, arriving at layer i with its input in layout fmt
+    best = [{NCHW: 0.0, NHWC: x_cvt}]
+    back = []
+    for i in range(n):
+        nxt, bk = {}, {}
+        for want in (NCHW, NHWC):            # layout handed on after layer i
+            if i == n - 1 and want != NCHW:
+                continue
+            for (fmt, olay), t in conv_t[i].items():
+                # a pool converts from olay to `want`; without a pool the kernel may write `want` itself
+                total = best[i].get(fmt, float("inf")) + t + glue_t[i][(olay, want)]
+                if total < nxt.get(want, float("inf")):
+                    nxt[want], bk[want] = total, (fmt, olay, False)
+            for (fmt, olay), t in fused_t[i].items():
+                total = best[i].get(fmt, float("inf")) + t
+                if olay == want and total < nxt.get(want, float("inf")):
+                    nxt[want], bk[want] = total, (fmt, olay, True)
+        best.append(nxt)
+        back.append(bk)
+    if NCHW not in best[n]:
+        raise ValueError("no assignment of formats serves the chain")
+    want, chosen, olays, fused = NCHW, [None] * n, [None] * n, [False] * n
+    for i in range(n - 1, -1, -1):
+        fmt, olay, fz = back[i][want]
+        chosen[i], olays[i], fused[i] = fmt, olay, fz
+        want = fmt
+    return chosen, olays, fused, best[n][NCHW]
