@@ -482,8 +482,11 @@ void pwin_register(std::vector<Variant>& out)
 {
     Variant v;
     char buf[160];
-    snprintf(buf, sizeof buf, "pwin_%s_%dx%d_M%dN%dC%d_w%dx%d_a%d%s", dtype_name(CFG::DT), CFG::R, CFG::S, CFG::TM, CFG::TNP,
-             CFG::CB, CFG::KW, CFG::WN, CFG::AD, CFG::ALIGN8 ? "_p8" : "");
+    // (the 32-row tiles for small operations come with several slab sizes: theirs is part of the name)
+    char slots[24] = "";
+    if (CFG::TM == 32) snprintf(slots, sizeof slots, "_s%d", CFG::SLOTS);
+    snprintf(buf, sizeof buf, "pwin_%s_%dx%d_M%dN%dC%d_w%dx%d_a%d%s%s", dtype_name(CFG::DT), CFG::R, CFG::S, CFG::TM, CFG::TNP,
+             CFG::CB, CFG::KW, CFG::WN, CFG::AD, CFG::ALIGN8 ? "_p8" : "", slots);
     v.name = buf;
     v.dtype = CFG::DT;
     v.split = 1;

@@ -94,6 +94,9 @@ PACKED_SHAPES = [
     ConvShape(2, 32, 27, 27, 40, 5, 5, 1, 2),    # 5x5, the stack's second layer at reduced width
     ConvShape(3, 96, 15, 11, 64, 5, 5, 1, 1),    # 5x5, border narrower than half the window, three chunks of 32
     ConvShape(1, 64, 9, 9, 33, 5, 5, 1, 0),      # 5x5 without padding, 25 output pixels
+    ConvShape(2, 48, 9, 11, 40, 3, 3, 1, 1),     # 48 channels: only the chunks of 16 divide them (no split over waves)
+    ConvShape(3, 16, 12, 12, 24, 5, 5, 1, 2),    # 5x5 over a single group of 16 channels
+    ConvShape(2, 96, 28, 28, 32, 3, 3, 1, 1),    # rows of 28 pixels: the 32-row tiles with 256 slab positions
 ]
 
 
