@@ -276,7 +276,9 @@ def test_winograd_variants_and_the_transformed_filter_format():
     # K is padded to a multiple of 4 in that format
     assert B.conv_transformed_filter_bytes(B.desc_of(ConvShape(1, 8, 9, 9, 10, 3, 3, 1, 1), 0)) == 16 * 12 * 8 * 4
     L = B.lib()
-    for sh2, dt, kw in [(ConvShape(2, 16, 13, 13, 40, 3, 3, 1, 1), 1, {}),              # 16-bit storage
+    # 16-bit storage has no Winograd-domain format: its ahead-of-time format is the MFMA operand order (C % 16 == 0)
+    assert B.conv_transformed_filter_bytes(B.desc_of(ConvShape(2, 16, 13, 13, 40, 3, 3, 1, 1), 1)) == 64 * 16 * 9 * 2
+    for sh2, dt, kw in [(ConvShape(2, 8, 13, 13, 40, 3, 3, 1, 1), 1, {}),               # 16-bit storage, C % 16 != 0
                         (ConvShape(2, 16, 13, 13, 40, 5, 5, 1, 2), 0, {}),              # 5x5
                         (ConvShape(2, 16, 13, 13, 40, 3, 3, 2, 1), 0, {}),              # stride 2
                         (ConvShape(2, 12, 13, 13, 40, 3, 3, 1, 1), 0, {})]:             # C % 8 != 0
